@@ -1,0 +1,143 @@
+/*
+ * svdcache.h -- C ABI of the SVD-Cache hot path for AMD MI355X (gfx950).
+ *
+ * The library implements the per-block, per-timestep cache step of
+ * "Forecast the Principal, Stabilize the Residual" (SVD-Cache):
+ *
+ *   svdcache_fit_basis   rank-k right-singular basis V_k and singular values of
+ *                        a feature matrix F (Sec. 3.2, Eq. 4-5; the "one-time
+ *                        SVD" of Sec. 3.3)
+ *   svdcache_full_step   full-compute step: C = F V_k, R = F - C V_k^T,
+ *                        EMA update of the coefficient state (Eq. 8-11)
+ *   svdcache_forecast    cached step: Fhat = S V_k^T + R (Sec. 3.4-3.5)
+ *
+ * all batched over B independent blocks of equal shape.
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer (HIP global memory) unless the
+ *     argument is documented as "host".  The structs are host memory.
+ *   - The caller owns every buffer.  The library never allocates or frees
+ *     device memory and keeps no state between calls.
+ *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and return; results are ready once the stream
+ *     has been synchronised.  Buffers must stay alive until then.
+ *   - Errors found on the host (null pointer, bad shape, alignment, parameter
+ *     range, workspace too small) are returned before anything is launched.
+ *     No exceptions cross this boundary.
+ *   - Matrices are dense row-major.  F, R, Fhat: [B, N, D] with row stride
+ *     `ldf` and block stride `block_stride` (both in elements), element type
+ *     `dtype`.  V: [B, D, k] float32 contiguous (k fastest).  S, C: [B, N, k]
+ *     float32 contiguous.  sigma: [B, k] float32.
+ */
+#ifndef SVDCACHE_H
+#define SVDCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* storage type of F, R and Fhat; arithmetic always accumulates in float32 or wider */
+typedef enum { SVDC_F32 = 0, SVDC_BF16 = 1 } svdc_dtype;
+
+typedef enum {
+  SVDC_OK = 0,
+  SVDC_E_NULL = -1,      /* a required pointer is NULL                          */
+  SVDC_E_SHAPE = -2,     /* B,N,D,k, strides or ranks out of the supported range */
+  SVDC_E_DTYPE = -3,     /* unknown dtype                                        */
+  SVDC_E_ALIGN = -4,     /* pointer or stride not aligned as documented          */
+  SVDC_E_PARAM = -5,     /* alpha, oversampling, iteration count out of range    */
+  SVDC_E_WORKSPACE = -6, /* workspace / packed-basis buffer too small            */
+  SVDC_E_HIP = -7        /* a HIP runtime call or kernel launch failed           */
+} svdc_status;
+
+/* One batched problem: B independent blocks of identical shape.
+ *   1 <= k <= min(N, D), k <= 1024;  ldf >= D;  block_stride >= (N-1)*ldf + D.
+ *   Base pointers of F/R/Fhat must be 16-byte aligned; with dtype BF16, D, ldf
+ *   and block_stride must be multiples of 8 elements, with F32 multiples of 4. */
+typedef struct {
+  int32_t B, N, D, k;
+  int64_t ldf;
+  int64_t block_stride;
+  int32_t dtype; /* svdc_dtype */
+} svdc_shape;
+
+/* Parameters of the randomized basis fit.  Zero-initialise for defaults. */
+typedef struct {
+  int32_t oversample_p;  /* sketch width l = k + p (clamped to min(N, D), at most 256); 0 -> p = k, -1 -> p = 0 */
+  int32_t power_iters_q; /* applications of F^T F before the Rayleigh-Ritz step; 0 -> 3 (bf16) / 4 (f32); -1 -> none */
+  uint64_t seed;         /* seed of the Gaussian test matrix                     */
+} svdc_fit_params;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int32_t svdcache_version(void);
+
+/* Human-readable text for a status code (static storage, never NULL). */
+const char* svdcache_strerror(int32_t status);
+
+/* Bytes of device workspace svdcache_fit_basis needs for this shape and these
+ * parameters (params may be NULL = defaults).  Returns 0 for an invalid shape. */
+size_t svdcache_fit_workspace_bytes(const svdc_shape* shape, const svdc_fit_params* params);
+
+/* Bytes of the packed copy of the basis that the matrix-core kernels read
+ * (see svdcache_pack_basis).  Returns 0 when the shape has no matrix-core
+ * path; the step functions then take packed = NULL. */
+size_t svdcache_packed_basis_bytes(const svdc_shape* shape);
+
+/* 1 if full_step / forecast run their matrix-core (MFMA) kernels for this
+ * shape when a packed basis is supplied, 0 if they use the general kernels. */
+int32_t svdcache_has_mfma_path(const svdc_shape* shape);
+
+/* Basis fit (Sec. 3.2, Eq. 4-5): the k leading right singular vectors of each
+ * F[b] and their singular values, by randomized subspace iteration with a
+ * Rayleigh-Ritz step (an approximation of the truncated SVD whose error is
+ * controlled by oversample_p and power_iters_q).
+ *   F       in   [B,N,D] dtype
+ *   V       out  [B,D,k] float32, orthonormal columns, ordered by descending sigma
+ *   sigma   out  [B,k]   float32, descending
+ *   fro2    out  [B]     float32, ||F[b]||_F^2 (denominator of the energy rule, Eq. 6); may be NULL
+ *   workspace    device scratch of at least svdcache_fit_workspace_bytes() bytes, 256-byte aligned
+ * Signs of the columns of V are arbitrary.  Several launches on `stream`. */
+int32_t svdcache_fit_basis(const svdc_shape* shape, const svdc_fit_params* params,
+                           const void* F, float* V, float* sigma, float* fro2,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Re-lay V [B,D,k] float32 into the operand format of the matrix-core kernels
+ * (bf16 high and low parts, tiled per 64-lane wavefront).  The packed buffer
+ * is opaque, belongs to the caller, and stays valid for as long as V is
+ * unchanged: pack once per fitted basis, reuse at every timestep.
+ *   packed  out  svdcache_packed_basis_bytes(shape) bytes, 256-byte aligned */
+int32_t svdcache_pack_basis(const svdc_shape* shape, const float* V, void* packed,
+                            size_t packed_bytes, void* stream);
+
+/* Full-compute step (Eq. 8-11), one pass over F:
+ *   C = F V                       coefficients in the cached basis (sigma of Eq. 8-9 cancels)
+ *   R = F - C V^T                 residual (Eq. 10)
+ *   S = C                         if init != 0 (first full step)
+ *   S = (1-alpha) S + alpha C     otherwise; alpha = 1 - beta of Eq. 11 (beta = 0.9 <-> alpha = 0.1)
+ *   F       in      [B,N,D] dtype
+ *   V       in      [B,D,k] float32 (used as given, not re-orthonormalised)
+ *   packed  in      packed copy of the same V, or NULL (general kernel)
+ *   R       out     [B,N,D] dtype; may be the same buffer as F (in place)
+ *   S       in/out  [B,N,k] float32 (not read when init != 0)
+ *   C       out     [B,N,k] float32; may be NULL
+ *   alpha   in (0, 1] */
+int32_t svdcache_full_step(const svdc_shape* shape, const void* F, const float* V,
+                           const void* packed, void* R, float* S, float* C,
+                           float alpha, int32_t init, void* stream);
+
+/* Cached step (Sec. 3.4 last paragraph, Sec. 3.5): the EMA state is the forecast
+ * of the principal coefficients and the residual is reused:
+ *   Fhat = S V^T + R
+ *   S in [B,N,k] float32;  V in [B,D,k] float32;  packed as above or NULL;
+ *   R in [B,N,D] dtype;  Fhat out [B,N,D] dtype, may be the same buffer as R
+ *   if the caller no longer needs R. */
+int32_t svdcache_forecast(const svdc_shape* shape, const float* S, const float* V,
+                          const void* packed, const void* R, void* Fhat, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SVDCACHE_H */

@@ -1,0 +1,21 @@
+"""MI355X-native SVD-Cache hot path: thin Python binding over libsvdcache.so.
+
+Every arithmetic step runs in the HIP kernels behind the C ABI declared in
+include/svdcache.h; this package only marshals torch tensors (device memory
+and the current stream) into that ABI.  There is no CPU fallback: calling any
+function without the compiled library, or with tensors that are not on the
+GPU, raises.
+"""
+from .binding import (
+    SvdcError, Shape, lib_path, load_library, exported_symbols,
+    svdcache_version, svdcache_strerror, svdcache_fit_workspace_bytes, svdcache_packed_basis_bytes,
+    svdcache_has_mfma_path, svdcache_fit_basis, svdcache_pack_basis, svdcache_full_step, svdcache_forecast,
+    make_shape, fit_basis, pack_basis,
+)
+
+__all__ = [
+    "SvdcError", "Shape", "lib_path", "load_library", "exported_symbols",
+    "svdcache_version", "svdcache_strerror", "svdcache_fit_workspace_bytes", "svdcache_packed_basis_bytes",
+    "svdcache_has_mfma_path", "svdcache_fit_basis", "svdcache_pack_basis", "svdcache_full_step",
+    "svdcache_forecast", "make_shape", "fit_basis", "pack_basis",
+]

@@ -1,0 +1,183 @@
+"""ctypes binding of the C ABI in include/svdcache.h (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+
+SVDC_F32, SVDC_BF16 = 0, 1
+_DTYPES = {torch.float32: SVDC_F32, torch.bfloat16: SVDC_BF16}
+
+
+class SvdcError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {svdcache_strerror(code)} (status {code})")
+
+
+class Shape(C.Structure):
+    """Mirror of svdc_shape."""
+    _fields_ = [("B", C.c_int32), ("N", C.c_int32), ("D", C.c_int32), ("k", C.c_int32),
+                ("ldf", C.c_int64), ("block_stride", C.c_int64), ("dtype", C.c_int32)]
+
+
+class FitParams(C.Structure):
+    """Mirror of svdc_fit_params."""
+    _fields_ = [("oversample_p", C.c_int32), ("power_iters_q", C.c_int32), ("seed", C.c_uint64)]
+
+
+EXPORTS = {
+    "svdcache_version": (C.c_int32, []),
+    "svdcache_strerror": (C.c_char_p, [C.c_int32]),
+    "svdcache_fit_workspace_bytes": (C.c_size_t, [C.POINTER(Shape), C.POINTER(FitParams)]),
+    "svdcache_packed_basis_bytes": (C.c_size_t, [C.POINTER(Shape)]),
+    "svdcache_has_mfma_path": (C.c_int32, [C.POINTER(Shape)]),
+    "svdcache_fit_basis": (C.c_int32, [C.POINTER(Shape), C.POINTER(FitParams), C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "svdcache_pack_basis": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "svdcache_full_step": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_void_p]),
+    "svdcache_forecast": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p]),
+}
+
+_lib = None
+
+
+def lib_path() -> str:
+    return os.path.join(PKG_DIR, "libsvdcache.so")
+
+
+def exported_symbols():
+    return sorted(EXPORTS)
+
+
+def load_library():
+    """Load libsvdcache.so from the package directory; raises if it was not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2601_07396_amd.build` "
+                           "(there is no fallback path)")
+    lib = C.CDLL(path)
+    for name, (res, args) in EXPORTS.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def svdcache_version() -> int:
+    return load_library().svdcache_version()
+
+
+def svdcache_strerror(code: int) -> str:
+    return load_library().svdcache_strerror(code).decode()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _need_gpu(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise RuntimeError("svdcache: tensors must live in GPU memory (no CPU path exists)")
+
+
+def make_shape(F: torch.Tensor, k: int) -> Shape:
+    """Shape descriptor of a feature tensor [B, N, D] (or [N, D]) whose last dim is contiguous."""
+    if F.dim() == 2:
+        F = F.unsqueeze(0)
+    if F.dim() != 3 or F.stride(2) != 1:
+        raise ValueError("F must be [B, N, D] with a contiguous last dimension")
+    if F.dtype not in _DTYPES:
+        raise ValueError("F must be float32 or bfloat16")
+    B, N, D = F.shape
+    bs = F.stride(0) if B > 1 else max(F.stride(0), (N - 1) * F.stride(1) + D)
+    return Shape(B, N, D, k, F.stride(1), bs, _DTYPES[F.dtype])
+
+
+def _check(code: int, where: str):
+    if code != 0:
+        raise SvdcError(code, where)
+
+
+def svdcache_fit_workspace_bytes(shape: Shape, p: int = 0, q: int = 0, seed: int = 0) -> int:
+    fp = FitParams(p, q, seed)
+    return load_library().svdcache_fit_workspace_bytes(C.byref(shape), C.byref(fp))
+
+
+def svdcache_packed_basis_bytes(shape: Shape) -> int:
+    return load_library().svdcache_packed_basis_bytes(C.byref(shape))
+
+
+def svdcache_has_mfma_path(shape: Shape) -> bool:
+    return bool(load_library().svdcache_has_mfma_path(C.byref(shape)))
+
+
+def svdcache_fit_basis(shape: Shape, F, V, sigma, fro2, workspace, p: int = 0, q: int = 0, seed: int = 0):
+    _need_gpu(F, V, sigma, fro2, workspace)
+    fp = FitParams(p, q, seed)
+    rc = load_library().svdcache_fit_basis(C.byref(shape), C.byref(fp), _ptr(F), _ptr(V), _ptr(sigma), _ptr(fro2),
+                                           _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "svdcache_fit_basis")
+
+
+def svdcache_pack_basis(shape: Shape, V, packed):
+    _need_gpu(V, packed)
+    rc = load_library().svdcache_pack_basis(C.byref(shape), _ptr(V), _ptr(packed),
+                                            packed.numel() * packed.element_size(), _stream())
+    _check(rc, "svdcache_pack_basis")
+
+
+def svdcache_full_step(shape: Shape, F, V, packed, R, S, Cout, alpha: float, init: bool):
+    _need_gpu(F, V, packed, R, S, Cout)
+    rc = load_library().svdcache_full_step(C.byref(shape), _ptr(F), _ptr(V), _ptr(packed), _ptr(R), _ptr(S),
+                                           _ptr(Cout), float(alpha), int(bool(init)), _stream())
+    _check(rc, "svdcache_full_step")
+
+
+def svdcache_forecast(shape: Shape, S, V, packed, R, Fhat):
+    _need_gpu(S, V, packed, R, Fhat)
+    rc = load_library().svdcache_forecast(C.byref(shape), _ptr(S), _ptr(V), _ptr(packed), _ptr(R), _ptr(Fhat),
+                                          _stream())
+    _check(rc, "svdcache_forecast")
+
+
+# ---- conveniences that only allocate (torch owns the memory) ------------------------------------
+
+def fit_basis(F: torch.Tensor, k: int, p: int = 0, q: int = 0, seed: int = 0):
+    """Allocate outputs + workspace and call svdcache_fit_basis. Returns (V [B,D,k], sigma [B,k], fro2 [B])."""
+    shape = make_shape(F, k)
+    dev = F.device
+    V = torch.empty(shape.B, shape.D, k, device=dev, dtype=torch.float32)
+    sigma = torch.empty(shape.B, k, device=dev, dtype=torch.float32)
+    fro2 = torch.empty(shape.B, device=dev, dtype=torch.float32)
+    nbytes = svdcache_fit_workspace_bytes(shape, p, q, seed)
+    if nbytes == 0:
+        raise SvdcError(-2, "svdcache_fit_workspace_bytes")
+    ws = torch.empty(nbytes, device=dev, dtype=torch.uint8)
+    svdcache_fit_basis(shape, F, V, sigma, fro2, ws, p, q, seed)
+    return V, sigma, fro2
+
+
+def pack_basis(shape: Shape, V: torch.Tensor):
+    """Packed copy of V for the matrix-core kernels, or None when the shape has no such path."""
+    n = svdcache_packed_basis_bytes(shape)
+    if n == 0:
+        return None
+    packed = torch.empty(n, device=V.device, dtype=torch.uint8)
+    svdcache_pack_basis(shape, V, packed)
+    return packed

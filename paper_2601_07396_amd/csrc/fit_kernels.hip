@@ -1,0 +1,544 @@
+// Basis fit (Sec. 3.2, Eq. 4-5): the k leading right singular vectors of F by
+// randomized subspace iteration followed by a Rayleigh-Ritz step.
+//
+//   Q <- orth(Omega)                       Omega: D x l Gaussian, l = k + p
+//   repeat q times:  Y = F Q;  Z = F^T Y;  Q <- orth(Z)       (one application of F^T F)
+//   Y = F Q;  H = Y^T Y = L L^T;  L^T = U diag(sigma) W^T     (one-sided Jacobi, fp64)
+//   V_k = Q W[:, :k],  sigma_k = sigma[:k]
+//
+// orth() is CholeskyQR applied twice; every l x l object (Gram matrices, Cholesky
+// factors, Jacobi rotations) is float64 because Z = F^T F Q has the squared
+// condition number of F's leading part and its Gram matrix squares it again.
+// The tall matrices Q, Z (D x l) and Y (N x l) are float32.
+//
+// This file holds the general (vector-ALU) kernels; the two products with F have
+// matrix-core versions in mfma_kernels.hip.
+#include <algorithm>
+#include <utility>
+
+#include "svdc_device.h"
+#include "svdc_internal.h"
+
+namespace svdc {
+
+// ---------------------------------------------------------------------------
+// counter-based Gaussian test matrix
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+  // 64-bit finaliser (xor-shift-multiply rounds); statistically adequate for a sketch matrix
+  x ^= x >> 30; x *= 0xbf58476d1ce4e5b9ull;
+  x ^= x >> 27; x *= 0x94d049bb133111ebull;
+  x ^= x >> 31;
+  return x;
+}
+
+__global__ void init_omega_kernel(float* Q, int64_t per_block, int64_t total, uint64_t seed) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const uint64_t h = mix64(seed * 0x9e3779b97f4a7c15ull + (uint64_t)i + 1);
+  const uint32_t a = (uint32_t)h, c = (uint32_t)(h >> 32);
+  const float u1 = ((float)(a >> 8) + 0.5f) * (1.0f / 16777216.0f);   // (0,1)
+  const float u2 = ((float)(c >> 8) + 0.5f) * (1.0f / 16777216.0f);
+  Q[i] = sqrtf(-2.0f * __logf(u1)) * __cosf(6.283185307179586f * u2);  // Box-Muller
+  (void)per_block;
+}
+
+__global__ void fill_zero_kernel(double* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.0;
+}
+__global__ void fill_zero_f32_kernel(float* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+// ---------------------------------------------------------------------------
+// products with F (general fp32 version)
+//   TRANS = false:  Out[N x l]  = F[N x D] * Bm[D x l]
+//   TRANS = true :  Out[D x l] += F^T      * Bm[N x l]   (rows of F split over grid.z, atomic accumulate)
+// 64 x 64 output tile per workgroup, 4 x 4 per thread, 16-deep steps through LDS.
+// ---------------------------------------------------------------------------
+template <typename T, bool TRANS>
+__global__ __launch_bounds__(256) void fit_gemm_kernel(const T* __restrict__ F, const float* __restrict__ Bm,
+                                                       float* Out, int N, int D, int l, int64_t ldf,
+                                                       int64_t bstride, int ksplit_len, int nsplit) {
+  __shared__ float As[16][64 + 4];
+  __shared__ float Bs[16][64 + 4];
+  const int b = blockIdx.z / nsplit, split = blockIdx.z % nsplit;
+  const int M = TRANS ? D : N, K = TRANS ? N : D;
+  const int m0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
+  const int kbeg = split * ksplit_len, kend = min(K, kbeg + ksplit_len);
+  const T* f = F + (int64_t)b * bstride;
+  const float* bm = Bm + (int64_t)b * K * l;
+  float* out = Out + (int64_t)b * M * l;
+  const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+  for (int k0 = kbeg; k0 < kend; k0 += 16) {
+    if (!TRANS) {
+      const int m = t >> 2, kk = (t & 3) * 4;
+      const int64_t row = m0 + m;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int kidx = k0 + kk + e;
+        As[kk + e][m] = (row < M && kidx < kend) ? ld_elem(f, row * ldf + kidx) : 0.f;
+      }
+    } else {
+      const int kk = t >> 4, m = (t & 15) * 4;
+      const int64_t n = k0 + kk;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int d = m0 + m + e;
+        As[kk][m + e] = (n < kend && d < M) ? ld_elem(f, n * ldf + d) : 0.f;
+      }
+    }
+    {
+      const int kk = t >> 4, j = (t & 15) * 4;
+      const int64_t kidx = k0 + kk;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int col = j0 + j + e;
+        Bs[kk][j + e] = (kidx < kend && col < l) ? bm[kidx * l + col] : 0.f;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], bb[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) bb[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * bb[j];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int64_t row = m0 + ty * 4 + i;
+    if (row >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int col = j0 + tx * 4 + j;
+      if (col >= l) continue;
+      if (TRANS) atomicAdd(&out[row * l + col], acc[i][j]);
+      else out[row * l + col] = acc[i][j];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// G[l x l] += A^T A in float64, A float32 [rows x l]; rows split over grid.x
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gram_f64_kernel(const float* __restrict__ A, double* G, int rows, int l,
+                                                       int rows_per_slice, int ntile) {
+  __shared__ float Ai[16][64];
+  __shared__ float Aj[16][64];
+  const int b = blockIdx.z;
+  const int ti = blockIdx.y / ntile, tj = blockIdx.y % ntile;
+  const float* a = A + (int64_t)b * rows * l;
+  double* g = G + (int64_t)b * l * l;
+  const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+  const int rbeg = blockIdx.x * rows_per_slice, rend = min(rows, rbeg + rows_per_slice);
+  double acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+  for (int r0 = rbeg; r0 < rend; r0 += 16) {
+    const int rr = t >> 4, c = (t & 15) * 4;
+    const int64_t r = r0 + rr;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int ci = ti * 64 + c + e, cj = tj * 64 + c + e;
+      Ai[rr][c + e] = (r < rend && ci < l) ? a[r * l + ci] : 0.f;
+      Aj[rr][c + e] = (r < rend && cj < l) ? a[r * l + cj] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int rr2 = 0; rr2 < 16; ++rr2) {
+      double x[4], y[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) x[i] = (double)Ai[rr2][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) y[j] = (double)Aj[rr2][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] += x[i] * y[j];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int gi = ti * 64 + ty * 4 + i;
+    if (gi >= l) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int gj = tj * 64 + tx * 4 + j;
+      if (gj < l) atomicAdd(&g[(int64_t)gi * l + gj], acc[i][j]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Cholesky factor of a (shifted) Gram matrix and the transposed inverse factor.
+//   in : G [l x l] symmetric positive semi-definite, float64
+//   out: G lower triangle = L with G + shift I = L L^T, upper triangle zeroed
+//        Minv [l x l] = L^-T (upper triangular), so that Z * Minv has orthonormal columns
+// One workgroup per block.  The matrix lives in LDS when it fits.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void chol_inv_kernel(double* G, double* Minv, int l, int use_lds,
+                                                       double rel_shift) {
+  extern __shared__ double dyn_lds[];
+  __shared__ double s_shift;
+  const int b = blockIdx.x, t = threadIdx.x;
+  double* g = G + (int64_t)b * l * l;
+  double* A = use_lds ? dyn_lds : g;
+  if (t < kWave) {
+    double mx = 0.0;
+    for (int i = t; i < l; i += kWave) mx = fmax(mx, g[(int64_t)i * l + i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o, kWave));
+    if (t == 0) s_shift = mx * rel_shift;
+  }
+  if (use_lds)
+    for (int idx = t; idx < l * l; idx += 256) A[idx] = g[idx];
+  __syncthreads();
+  for (int i = t; i < l; i += 256) A[i * l + i] += s_shift;
+  __syncthreads();
+
+  for (int c = 0; c < l; ++c) {
+    const double piv = sqrt(fmax(A[c * l + c], 1e-300));
+    __syncthreads();
+    if (t == 0) A[c * l + c] = piv;
+    for (int i = c + 1 + t; i < l; i += 256) A[i * l + c] /= piv;
+    __syncthreads();
+    const int n = l - c - 1;
+    for (int idx = t; idx < n * n; idx += 256) {
+      const int i = c + 1 + idx / n, j = c + 1 + idx % n;
+      if (j <= i) A[i * l + j] -= A[i * l + c] * A[j * l + c];
+    }
+    __syncthreads();
+  }
+
+  if (Minv) {
+    // column j of L^-1 by forward substitution, stored as row j of Minv = L^-T
+    double* m = Minv + (int64_t)b * l * l;
+    for (int j = t; j < l; j += 256) {
+      double* mj = m + (int64_t)j * l;
+      for (int i = 0; i < j; ++i) mj[i] = 0.0;
+      mj[j] = 1.0 / A[j * l + j];
+      for (int i = j + 1; i < l; ++i) {
+        double s = 0.0;
+        for (int mm = j; mm < i; ++mm) s += A[i * l + mm] * mj[mm];
+        mj[i] = -s / A[i * l + i];
+      }
+    }
+  }
+  __syncthreads();
+  for (int idx = t; idx < l * l; idx += 256) {
+    const int i = idx / l, j = idx % l;
+    if (j > i) g[idx] = 0.0;
+    else if (use_lds) g[idx] = A[idx];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Out[rows x m] (float32) = In[rows x l] (float32) * M[l x m] (float64, row stride ldm)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rows_times_small_kernel(const float* __restrict__ In,
+                                                               const double* __restrict__ M, float* Out,
+                                                               int rows, int l, int m, int ldm) {
+  __shared__ float tile[16][256];
+  const int b = blockIdx.y, t = threadIdx.x;
+  const float* in = In + (int64_t)b * rows * l;
+  const double* mm = M + (int64_t)b * l * ldm;
+  float* out = Out + (int64_t)b * rows * m;
+  const int r0 = blockIdx.x * 16;
+  for (int idx = t; idx < 16 * l; idx += 256) {
+    const int rr = idx / l, c = idx % l;
+    tile[rr][c] = (r0 + rr < rows) ? in[(int64_t)(r0 + rr) * l + c] : 0.f;
+  }
+  __syncthreads();
+  const int rr = t >> 4, jj = t & 15;
+  if (r0 + rr >= rows) return;
+  for (int j = jj; j < m; j += 16) {
+    double acc = 0.0;
+    for (int i = 0; i < l; ++i) acc += (double)tile[rr][i] * mm[(int64_t)i * ldm + j];
+    out[(int64_t)(r0 + rr) * m + j] = (float)acc;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// One-sided (Hestenes) Jacobi SVD of A = L^T (l x l, float64), one workgroup per
+// block: plane rotations on column pairs until all columns are orthogonal, with
+// a round-robin ordering so that l/2 disjoint pairs are rotated concurrently.
+// Then sigma_j = ||A[:, j]||, columns sorted by descending sigma.
+//   Lfac  in   [l x l] lower-triangular Cholesky factor of H = Y^T Y
+//   Wout  out  [l x l] row-major, column r = right singular vector of rank r
+//   sigma out  [k] leading singular values
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ Lfac, double* Wout, float* sigma,
+                                                     double* gA, double* gW, int l, int k, int a_in_lds,
+                                                     int w_in_lds, const double* fro_acc, float* fro2) {
+  extern __shared__ double dyn_lds[];
+  __shared__ double nrm[256];
+  __shared__ int s_rot;
+  const int b = blockIdx.x, t = threadIdx.x;
+  const double* Lf = Lfac + (int64_t)b * l * l;
+  double* A = a_in_lds ? dyn_lds : gA + (int64_t)b * l * l;                       // column-major
+  double* W = w_in_lds ? dyn_lds + (a_in_lds ? l * l : 0) : gW + (int64_t)b * l * l;  // column-major
+  for (int idx = t; idx < l * l; idx += 256) {
+    const int c = idx / l, r = idx % l;
+    A[idx] = (r <= c) ? Lf[idx] : 0.0;   // A[r][c] = L[c][r]
+    W[idx] = (r == c) ? 1.0 : 0.0;
+  }
+  if (t == 0 && fro2) fro2[b] = (float)fro_acc[b];
+  __syncthreads();
+
+  const int le = (l + 1) & ~1;         // players in the round-robin (one dummy if l is odd)
+  const int npairs = le / 2;           // <= 128
+  int tp = 64;
+  while (tp > 1 && tp * npairs > 256) tp >>= 1;
+  const int group = t / tp, gl = t % tp;
+  const bool active = group < npairs;
+
+  for (int sweep = 0; sweep < 40; ++sweep) {
+    if (t == 0) s_rot = 0;
+    __syncthreads();
+    for (int step = 0; step < le - 1; ++step) {
+      int p = 0, q = 0;
+      if (active) {
+        if (group == 0) { p = le - 1; q = step % (le - 1); }
+        else { p = (step + group) % (le - 1); q = (step + (le - 1) - group) % (le - 1); }
+      }
+      if (active && p < l && q < l) {
+        double* ap = A + (int64_t)p * l;
+        double* aq = A + (int64_t)q * l;
+        double al = 0.0, be = 0.0, ga = 0.0;
+        for (int r = gl; r < l; r += tp) {
+          const double x = ap[r], y = aq[r];
+          al += x * x; be += y * y; ga += x * y;
+        }
+        for (int o = tp >> 1; o > 0; o >>= 1) {
+          al += __shfl_xor(al, o, kWave);
+          be += __shfl_xor(be, o, kWave);
+          ga += __shfl_xor(ga, o, kWave);
+        }
+        if (fabs(ga) > 1e-15 * sqrt(al * be) && ga != 0.0) {
+          const double zeta = (be - al) / (2.0 * ga);
+          const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+          const double cs = 1.0 / sqrt(1.0 + tt * tt), sn = cs * tt;
+          double* wp = W + (int64_t)p * l;
+          double* wq = W + (int64_t)q * l;
+          for (int r = gl; r < l; r += tp) {
+            const double x = ap[r], y = aq[r];
+            ap[r] = cs * x - sn * y;
+            aq[r] = sn * x + cs * y;
+            const double u = wp[r], v = wq[r];
+            wp[r] = cs * u - sn * v;
+            wq[r] = sn * u + cs * v;
+          }
+          if (gl == 0) atomicAdd(&s_rot, 1);
+        }
+      }
+      __syncthreads();
+    }
+    const int rot = s_rot;
+    __syncthreads();
+    if (rot == 0) break;
+  }
+
+  for (int j = t; j < l; j += 256) {
+    double s = 0.0;
+    for (int r = 0; r < l; ++r) s += A[(int64_t)j * l + r] * A[(int64_t)j * l + r];
+    nrm[j] = s;
+  }
+  __syncthreads();
+  double* wo = Wout + (int64_t)b * l * l;
+  for (int j = t; j < l; j += 256) {
+    const double nj = nrm[j];
+    int rank = 0;
+    for (int i = 0; i < l; ++i) rank += (nrm[i] > nj || (nrm[i] == nj && i < j)) ? 1 : 0;
+    if (rank < k) sigma[(int64_t)b * k + rank] = (float)sqrt(nj);
+    for (int i = 0; i < l; ++i) wo[(int64_t)i * l + rank] = W[(int64_t)j * l + i];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// sum of squares of F[b] in float64 (||F||_F^2 for the energy rule, Eq. 6)
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void sumsq_kernel(const T* __restrict__ F, double* acc, int N, int D,
+                                                    int64_t ldf, int64_t bstride, int rows_per_group) {
+  __shared__ double part[4];
+  const int b = blockIdx.y, t = threadIdx.x;
+  const T* f = F + (int64_t)b * bstride;
+  const int r0 = blockIdx.x * rows_per_group, r1 = min(N, r0 + rows_per_group);
+  double s = 0.0;
+  for (int r = r0; r < r1; ++r)
+    for (int d = t; d < D; d += 256) {
+      const float x = ld_elem(f, (int64_t)r * ldf + d);
+      s += (double)x * (double)x;
+    }
+  s = wave_sum(s);
+  if ((t & 63) == 0) part[t >> 6] = s;
+  __syncthreads();
+  if (t == 0) atomicAdd(&acc[b], part[0] + part[1] + part[2] + part[3]);
+}
+
+// ---------------------------------------------------------------------------
+// host orchestration
+// ---------------------------------------------------------------------------
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan) {
+  int pp = p ? p->oversample_p : 0;
+  int q = p ? p->power_iters_q : 0;
+  if (pp < -1 || q < -1 || pp > 4096 || q > 64) return false;
+  if (pp == 0) pp = s.k;
+  if (pp == -1) pp = 0;
+  if (q == 0) q = (s.dtype == SVDC_BF16) ? 3 : 4;
+  if (q == -1) q = 0;
+  int l = s.k + pp;
+  l = std::min(l, std::min(s.N, s.D));
+  l = std::min(l, 256);
+  if (l < s.k) return false;  // k > 256 is not supported by the fit
+  plan->l = l;
+  plan->q = q;
+  plan->seed = p ? p->seed : 0;
+  size_t off = 0;
+  const size_t B = s.B;
+  plan->off_Q = off; off = align_up(off + B * s.D * l * sizeof(float), 256);
+  plan->off_Z = off; off = align_up(off + B * s.D * l * sizeof(float), 256);
+  plan->off_Y = off; off = align_up(off + B * (size_t)s.N * l * sizeof(float), 256);
+  plan->off_G = off; off = align_up(off + B * l * l * sizeof(double), 256);
+  plan->off_M = off; off = align_up(off + B * l * l * sizeof(double), 256);
+  plan->off_W = off; off = align_up(off + 2 * B * l * l * sizeof(double), 256);
+  plan->off_misc = off; off = align_up(off + B * sizeof(double), 256);
+  plan->total = off;
+  return true;
+}
+
+namespace {
+
+constexpr size_t kLdsBudget = 150 * 1024;  // dynamic LDS a single workgroup may take (160 KB per CU)
+
+int32_t set_dyn_lds(const void* fn, size_t bytes) {
+  if (bytes <= 48 * 1024) return SVDC_OK;
+  return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess
+             ? SVDC_OK : SVDC_E_HIP;
+}
+
+void zero_f64(double* p, int64_t n, hipStream_t st) {
+  fill_zero_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(p, n);
+}
+void zero_f32(float* p, int64_t n, hipStream_t st) {
+  fill_zero_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(p, n);
+}
+
+template <typename T>
+void gemm_fq(const svdc_shape& s, int l, const T* F, const float* Q, float* Y, hipStream_t st) {
+  dim3 grid((s.N + 63) / 64, (l + 63) / 64, s.B);
+  fit_gemm_kernel<T, false><<<grid, 256, 0, st>>>(F, Q, Y, s.N, s.D, l, s.ldf, s.block_stride, s.D, 1);
+}
+template <typename T>
+void gemm_fty(const svdc_shape& s, int l, const T* F, const float* Y, float* Z, hipStream_t st) {
+  zero_f32(Z, (int64_t)s.B * s.D * l, st);
+  const int split_len = 1024;
+  const int nsplit = (s.N + split_len - 1) / split_len;
+  dim3 grid((s.D + 63) / 64, (l + 63) / 64, s.B * nsplit);
+  fit_gemm_kernel<T, true><<<grid, 256, 0, st>>>(F, Y, Z, s.N, s.D, l, s.ldf, s.block_stride, split_len, nsplit);
+}
+
+void gram(const float* A, double* G, int B, int rows, int l, hipStream_t st) {
+  zero_f64(G, (int64_t)B * l * l, st);
+  const int ntile = (l + 63) / 64;
+  const int rows_per_slice = 256;
+  dim3 grid((rows + rows_per_slice - 1) / rows_per_slice, ntile * ntile, B);
+  gram_f64_kernel<<<grid, 256, 0, st>>>(A, G, rows, l, rows_per_slice, ntile);
+}
+
+int32_t chol_inv(double* G, double* Minv, int B, int l, hipStream_t st) {
+  const size_t bytes = (size_t)l * l * sizeof(double);
+  const int use_lds = bytes <= kLdsBudget;
+  if (use_lds && set_dyn_lds((const void*)chol_inv_kernel, bytes) != SVDC_OK) return SVDC_E_HIP;
+  chol_inv_kernel<<<B, 256, use_lds ? bytes : 0, st>>>(G, Minv, l, use_lds, 1e-14);
+  return SVDC_OK;
+}
+
+// Q_out = orth(Z_in) by CholeskyQR2; Z_in is overwritten (used as the intermediate).
+int32_t orth(float* Zin, float* Qout, double* G, double* M, int B, int rows, int l, hipStream_t st) {
+  dim3 ag((rows + 15) / 16, B);
+  gram(Zin, G, B, rows, l, st);
+  if (chol_inv(G, M, B, l, st) != SVDC_OK) return SVDC_E_HIP;
+  rows_times_small_kernel<<<ag, 256, 0, st>>>(Zin, M, Qout, rows, l, l, l);
+  gram(Qout, G, B, rows, l, st);
+  if (chol_inv(G, M, B, l, st) != SVDC_OK) return SVDC_E_HIP;
+  rows_times_small_kernel<<<ag, 256, 0, st>>>(Qout, M, Zin, rows, l, l, l);
+  return SVDC_OK;
+}
+
+template <typename T>
+int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float* V, float* sigma, float* fro2,
+                      char* ws, hipStream_t st) {
+  const int l = pl.l, B = s.B;
+  float* Q = (float*)(ws + pl.off_Q);
+  float* Z = (float*)(ws + pl.off_Z);
+  float* Y = (float*)(ws + pl.off_Y);
+  double* G = (double*)(ws + pl.off_G);
+  double* M = (double*)(ws + pl.off_M);
+  double* Wg = (double*)(ws + pl.off_W);
+  double* misc = (double*)(ws + pl.off_misc);
+
+  const int64_t nq = (int64_t)B * s.D * l;
+  init_omega_kernel<<<(unsigned)((nq + 255) / 256), 256, 0, st>>>(Z, (int64_t)s.D * l, nq, pl.seed);
+  // orth() leaves its result in its first argument after the second pass
+  if (orth(Z, Q, G, M, B, s.D, l, st) != SVDC_OK) return SVDC_E_HIP;
+  std::swap(Q, Z);  // Q now names the orthonormal basis
+
+  for (int it = 0; it < pl.q; ++it) {
+    gemm_fq<T>(s, l, F, Q, Y, st);
+    gemm_fty<T>(s, l, F, Y, Z, st);
+    if (orth(Z, Q, G, M, B, s.D, l, st) != SVDC_OK) return SVDC_E_HIP;
+    std::swap(Q, Z);
+  }
+
+  // Rayleigh-Ritz on span(Q)
+  gemm_fq<T>(s, l, F, Q, Y, st);
+  gram(Y, G, B, s.N, l, st);
+  if (chol_inv(G, nullptr, B, l, st) != SVDC_OK) return SVDC_E_HIP;
+  if (fro2) {
+    zero_f64(misc, B, st);
+    const int rpg = 64;
+    sumsq_kernel<T><<<dim3((s.N + rpg - 1) / rpg, B), 256, 0, st>>>(F, misc, s.N, s.D, s.ldf, s.block_stride, rpg);
+  }
+  const size_t mat = (size_t)l * l * sizeof(double);
+  const int a_in_lds = mat <= kLdsBudget;
+  const int w_in_lds = 2 * mat <= kLdsBudget;
+  const size_t lds = (a_in_lds ? mat : 0) + (w_in_lds ? mat : 0);
+  if (set_dyn_lds((const void*)jacobi_kernel, lds) != SVDC_OK) return SVDC_E_HIP;
+  jacobi_kernel<<<B, 256, lds, st>>>(G, M, sigma, Wg, Wg + (int64_t)B * l * l, l, s.k, a_in_lds, w_in_lds, misc,
+                                     fro2);
+  rows_times_small_kernel<<<dim3((s.D + 15) / 16, B), 256, 0, st>>>(Q, M, V, s.D, l, s.k, l);
+  return launch_status();
+}
+
+}  // namespace
+
+int32_t run_fit(const svdc_shape& s, const FitPlan& plan, const void* F, float* V, float* sigma, float* fro2,
+                void* workspace, hipStream_t st) {
+  if (s.dtype == SVDC_BF16)
+    return run_fit_typed<bf16_t>(s, plan, (const bf16_t*)F, V, sigma, fro2, (char*)workspace, st);
+  return run_fit_typed<float>(s, plan, (const float*)F, V, sigma, fro2, (char*)workspace, st);
+}
+
+}  // namespace svdc

@@ -1,0 +1,111 @@
+// C ABI of libsvdcache: argument validation and dispatch.  See include/svdcache.h.
+#include <stdint.h>
+
+#include "svdc_internal.h"
+
+using namespace svdc;
+
+namespace {
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int32_t check_shape(const svdc_shape* s) {
+  if (!s) return SVDC_E_NULL;
+  if (s->dtype != SVDC_F32 && s->dtype != SVDC_BF16) return SVDC_E_DTYPE;
+  if (s->B < 1 || s->B > 65535 || s->N < 1 || s->D < 1 || s->k < 1) return SVDC_E_SHAPE;
+  if (s->k > s->N || s->k > s->D || s->k > 1024) return SVDC_E_SHAPE;
+  if (s->ldf < s->D) return SVDC_E_SHAPE;
+  if (s->block_stride < (int64_t)(s->N - 1) * s->ldf + s->D) return SVDC_E_SHAPE;
+  const int64_t unit = s->dtype == SVDC_BF16 ? 8 : 4;
+  if (s->D % unit || s->ldf % unit || s->block_stride % unit) return SVDC_E_ALIGN;
+  return SVDC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t svdcache_version(void) { return 100; }
+
+const char* svdcache_strerror(int32_t status) {
+  switch (status) {
+    case SVDC_OK: return "ok";
+    case SVDC_E_NULL: return "a required pointer is NULL";
+    case SVDC_E_SHAPE: return "shape, stride or rank out of the supported range";
+    case SVDC_E_DTYPE: return "unknown dtype";
+    case SVDC_E_ALIGN: return "pointer or stride not aligned as documented";
+    case SVDC_E_PARAM: return "parameter out of range";
+    case SVDC_E_WORKSPACE: return "workspace or packed-basis buffer too small";
+    case SVDC_E_HIP: return "HIP runtime call or kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+size_t svdcache_fit_workspace_bytes(const svdc_shape* shape, const svdc_fit_params* params) {
+  FitPlan plan;
+  if (check_shape(shape) != SVDC_OK || !make_fit_plan(*shape, params, &plan)) return 0;
+  return plan.total;
+}
+
+size_t svdcache_packed_basis_bytes(const svdc_shape* shape) {
+  if (check_shape(shape) != SVDC_OK || !mfma_shape_supported(*shape)) return 0;
+  return mfma_packed_bytes(*shape);
+}
+
+int32_t svdcache_has_mfma_path(const svdc_shape* shape) {
+  return check_shape(shape) == SVDC_OK && mfma_shape_supported(*shape) ? 1 : 0;
+}
+
+int32_t svdcache_fit_basis(const svdc_shape* shape, const svdc_fit_params* params, const void* F, float* V,
+                           float* sigma, float* fro2, void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!F || !V || !sigma || !workspace) return SVDC_E_NULL;
+  if (!aligned(F, 16) || !aligned(V, 16) || !aligned(workspace, 256)) return SVDC_E_ALIGN;
+  FitPlan plan;
+  if (shape->k > 256) return SVDC_E_SHAPE;
+  if (!make_fit_plan(*shape, params, &plan)) return SVDC_E_PARAM;
+  if (workspace_bytes < plan.total) return SVDC_E_WORKSPACE;
+  return run_fit(*shape, plan, F, V, sigma, fro2, workspace, (hipStream_t)stream);
+}
+
+int32_t svdcache_pack_basis(const svdc_shape* shape, const float* V, void* packed, size_t packed_bytes,
+                            void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!V || !packed) return SVDC_E_NULL;
+  if (!mfma_shape_supported(*shape)) return SVDC_E_SHAPE;
+  if (!aligned(V, 16) || !aligned(packed, 256)) return SVDC_E_ALIGN;
+  if (packed_bytes < mfma_packed_bytes(*shape)) return SVDC_E_WORKSPACE;
+  return launch_pack_basis(*shape, V, packed, (hipStream_t)stream);
+}
+
+int32_t svdcache_full_step(const svdc_shape* shape, const void* F, const float* V, const void* packed, void* R,
+                           float* S, float* C, float alpha, int32_t init, void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!F || !V || !R || !S) return SVDC_E_NULL;
+  if (!(alpha > 0.f && alpha <= 1.f)) return SVDC_E_PARAM;
+  if (!aligned(F, 16) || !aligned(R, 16) || !aligned(V, 16) || !aligned(S, 16) || (C && !aligned(C, 16)))
+    return SVDC_E_ALIGN;
+  if (packed && mfma_shape_supported(*shape)) {
+    if (!aligned(packed, 256)) return SVDC_E_ALIGN;
+    return launch_full_step_mfma(*shape, F, packed, R, S, C, alpha, init != 0, (hipStream_t)stream);
+  }
+  return launch_full_step_general(*shape, F, V, R, S, C, alpha, init != 0, (hipStream_t)stream);
+}
+
+int32_t svdcache_forecast(const svdc_shape* shape, const float* S, const float* V, const void* packed,
+                          const void* R, void* Fhat, void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!S || !V || !R || !Fhat) return SVDC_E_NULL;
+  if (!aligned(R, 16) || !aligned(Fhat, 16) || !aligned(V, 16) || !aligned(S, 16)) return SVDC_E_ALIGN;
+  if (packed && mfma_shape_supported(*shape)) {
+    if (!aligned(packed, 256)) return SVDC_E_ALIGN;
+    return launch_forecast_mfma(*shape, S, packed, R, Fhat, (hipStream_t)stream);
+  }
+  return launch_forecast_general(*shape, S, V, R, Fhat, (hipStream_t)stream);
+}
+
+}  // extern "C"

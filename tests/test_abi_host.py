@@ -1,0 +1,92 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2601_07396_amd as pkg
+from paper_2601_07396_amd.binding import Shape, FitParams
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(pkg.lib_path()):
+        from paper_2601_07396_amd import build
+        build.build()
+    return pkg.load_library()
+
+
+def test_header_symbols_are_exported(lib):
+    header = open(os.path.join(ROOT, "include", "svdcache.h")).read()
+    declared = set(re.findall(r"\b(svdcache_\w+)\s*\(", header))
+    assert {"svdcache_fit_basis", "svdcache_full_step", "svdcache_forecast"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in the header but not exported"
+    assert declared == set(pkg.exported_symbols())
+
+
+def test_version_and_strerror(lib):
+    assert pkg.svdcache_version() >= 100
+    assert pkg.svdcache_strerror(0) == "ok"
+    for code in range(-7, 0):
+        assert pkg.svdcache_strerror(code) not in ("ok", "unknown status")
+    assert pkg.svdcache_strerror(-99) == "unknown status"
+
+
+def _shape(**kw):
+    d = dict(B=1, N=64, D=64, k=8, ldf=64, block_stride=64 * 64, dtype=0)
+    d.update(kw)
+    return Shape(**d)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(dtype=7), -3), (dict(B=0), -2), (dict(k=0), -2), (dict(k=65), -2), (dict(N=4, k=8), -2),
+    (dict(ldf=32), -2), (dict(block_stride=100), -2), (dict(D=66, ldf=66, block_stride=66 * 64), -4),
+    (dict(dtype=1, D=68, ldf=68, block_stride=68 * 64), -4),
+])
+def test_bad_shapes_are_rejected_on_the_host(lib, kw, code):
+    s = _shape(**kw)
+    dummy = C.c_void_p(256)   # never dereferenced: validation fails first
+    rc = lib.svdcache_full_step(C.byref(s), dummy, dummy, None, dummy, dummy, None, 0.5, 1, None)
+    assert rc == code
+    rc = lib.svdcache_forecast(C.byref(s), dummy, dummy, None, dummy, dummy, None)
+    assert rc == code
+    assert lib.svdcache_fit_workspace_bytes(C.byref(s), None) == 0
+
+
+def test_null_alpha_alignment_workspace(lib):
+    s = _shape()
+    p = C.c_void_p(256)
+    assert lib.svdcache_full_step(None, p, p, None, p, p, None, 0.5, 1, None) == -1
+    assert lib.svdcache_full_step(C.byref(s), None, p, None, p, p, None, 0.5, 1, None) == -1
+    assert lib.svdcache_full_step(C.byref(s), p, p, None, p, None, None, 0.5, 1, None) == -1
+    for bad in (0.0, -0.1, 1.5, float("nan")):
+        assert lib.svdcache_full_step(C.byref(s), p, p, None, p, p, None, bad, 1, None) == -5
+    assert lib.svdcache_full_step(C.byref(s), C.c_void_p(260), p, None, p, p, None, 0.5, 1, None) == -4
+    assert lib.svdcache_forecast(C.byref(s), p, p, None, None, p, None) == -1
+    need = lib.svdcache_fit_workspace_bytes(C.byref(s), None)
+    assert need > 0
+    assert lib.svdcache_fit_basis(C.byref(s), None, p, p, p, None, p, need - 1, None) == -6
+    assert lib.svdcache_fit_basis(C.byref(s), None, p, p, p, None, None, need, None) == -1
+    fp = FitParams(-5, 0, 0)
+    assert lib.svdcache_fit_basis(C.byref(s), C.byref(fp), p, p, p, None, p, need, None) == -5
+
+
+def test_workspace_grows_with_sketch_width(lib):
+    s = _shape(N=512, D=256, k=16, ldf=256, block_stride=512 * 256)
+    a = pkg.svdcache_fit_workspace_bytes(s, p=-1)
+    b = pkg.svdcache_fit_workspace_bytes(s, p=16)
+    c = pkg.svdcache_fit_workspace_bytes(s, p=48)
+    assert 0 < a < b < c
+
+
+def test_calls_refuse_cpu_tensors():
+    import torch
+    F = torch.zeros(1, 64, 64)
+    s = pkg.make_shape(F, 8)
+    with pytest.raises(RuntimeError, match="GPU"):
+        pkg.svdcache_forecast(s, torch.zeros(1, 64, 8), torch.zeros(1, 64, 8), None, F, F)

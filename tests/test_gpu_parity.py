@@ -1,0 +1,210 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2601_07396_amd as pkg
+from oracle import ref_fit_basis, ref_full_step, ref_forecast
+from synth import WORKLOADS, FeatureStream, is_full_step
+from util import TOL, to_np, rel_err, assert_close, principal_sines
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _rand_problem(B, N, D, k, dtype, seed, ldf=None):
+    g = torch.Generator().manual_seed(seed)
+    ldf = D if ldf is None else ldf
+    buf = torch.zeros(B, N, ldf, dtype=dtype)
+    buf[:, :, :D] = torch.randn(B, N, D, generator=g).to(dtype)
+    V = torch.linalg.qr(torch.randn(B, D, k, generator=g, dtype=torch.float64))[0].float().contiguous()
+    S = torch.randn(B, N, k, generator=g)
+    return buf, V, S
+
+
+def _run_full(Fbuf, D, V, S, alpha, init, want_C=True, inplace=False, packed="auto"):
+    F = Fbuf.to(DEV)
+    Fv = F[:, :, :D]
+    shape = pkg.make_shape(Fv, V.shape[2])
+    Vd, Sd = V.to(DEV), S.clone().to(DEV)
+    pk = pkg.pack_basis(shape, Vd) if packed == "auto" else None
+    R = F if inplace else torch.full_like(F, 7.0)
+    Cd = torch.empty_like(Sd) if want_C else None
+    pkg.svdcache_full_step(shape, Fv, Vd, pk, R[:, :, :D], Sd, Cd, alpha, init)
+    torch.cuda.synchronize()
+    return R, Sd, Cd, shape, pk
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("B,N,D,k", [(2, 256, 64, 8), (1, 37, 72, 5), (3, 130, 200, 17), (1, 1, 8, 1),
+                                     (1, 20, 16, 16), (2, 67, 264, 40)])
+def test_full_step_and_forecast_general_shapes(dtype, B, N, D, k):
+    store = "f32" if dtype == torch.float32 else "bf16"
+    Fbuf, V, S0 = _rand_problem(B, N, D, k, dtype, seed=B * 1000 + N)
+    for init in (True, False):
+        R, S, Cc, shape, pk = _run_full(Fbuf, D, V, S0, 0.3, init)
+        Fh = torch.empty_like(R)
+        pkg.svdcache_forecast(shape, S, V.to(DEV), pk, R, Fh)
+        torch.cuda.synchronize()
+        for b in range(B):
+            Rr, Sr, Cr = ref_full_step(to_np(Fbuf[b]), to_np(V[b]), to_np(S0[b]), 0.3, init, store)
+            assert_close(to_np(R[b]), Rr, store, f"R[{b}]", floor_of=to_np(Fbuf[b]))
+            assert_close(to_np(S[b]), Sr, "f32", f"S[{b}]")
+            assert_close(to_np(Cc[b]), Cr, "f32", f"C[{b}]")
+            # forecast checked with the GPU's own (S, R) as inputs to the oracle
+            Fr = ref_forecast(to_np(S[b]), to_np(V[b]), to_np(R[b]), store)
+            assert_close(to_np(Fh[b]), Fr, store, f"Fhat[{b}]")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_strided_rows_inplace_and_null_C(dtype):
+    store = "f32" if dtype == torch.float32 else "bf16"
+    B, N, D, k, ldf = 2, 50, 64, 8, 96
+    Fbuf, V, S0 = _rand_problem(B, N, D, k, dtype, seed=5, ldf=ldf)
+    R, S, Cc, shape, pk = _run_full(Fbuf, D, V, S0, 0.5, False, want_C=False, inplace=True)
+    assert Cc is None and shape.ldf == ldf
+    for b in range(B):
+        Rr, Sr, _ = ref_full_step(to_np(Fbuf[b, :, :D]), to_np(V[b]), to_np(S0[b]), 0.5, False, store)
+        assert_close(to_np(R[b, :, :D]), Rr, store, "R in place")
+        assert_close(to_np(S[b]), Sr, "f32", "S")
+    # the padding columns beyond D are not touched
+    assert torch.equal(R[:, :, D:].cpu(), Fbuf[:, :, D:])
+    # forecast in place (Fhat aliases R)
+    Rc = R.clone()
+    pkg.svdcache_forecast(shape, S, V.to(DEV), pk, R[:, :, :D], R[:, :, :D])
+    torch.cuda.synchronize()
+    for b in range(B):
+        Fr = ref_forecast(to_np(S[b]), to_np(V[b]), to_np(Rc[b, :, :D]), store)
+        assert_close(to_np(R[b, :, :D]), Fr, store, "Fhat in place")
+
+
+def test_forecast_after_init_reproduces_F_exactly_in_fp32_tolerance():
+    B, N, D, k = 1, 64, 128, 16
+    Fbuf, V, S0 = _rand_problem(B, N, D, k, torch.float32, seed=9)
+    R, S, Cc, shape, pk = _run_full(Fbuf, D, V, S0, 0.5, True)
+    assert torch.equal(S, Cc)
+    Fh = torch.empty_like(R)
+    pkg.svdcache_forecast(shape, S, V.to(DEV), pk, R, Fh)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(Fh), to_np(Fbuf)) <= 1e-6
+
+
+def _fit_checks(F_cpu, V, sigma, fro2, k, store, lead=None):
+    """Compare a fitted basis with the exact truncated SVD.  Several bases are correct (signs,
+    rotations inside clusters of close singular values), so compare what is unique: singular values,
+    captured energy, orthonormality, and the leading subspace scaled by its spectral gap."""
+    tol = TOL[store]
+    Fd = to_np(F_cpu)
+    n_all = min(Fd.shape)
+    _, s_all, _ = ref_fit_basis(Fd, n_all) if n_all <= 512 else (None, None, None)
+    Vr, sr, fr = ref_fit_basis(Fd, k)
+    Vg = to_np(V)
+    assert np.abs(Vg.T @ Vg - np.eye(k)).max() <= 1e-5
+    sg = to_np(sigma)
+    assert np.all(np.diff(sg) <= 1e-6 * sg[0])
+    assert np.abs(sg / sr - 1).max() <= tol, f"sigma rel err {np.abs(sg / sr - 1).max():.2e}"
+    assert abs(float(fro2) / fr - 1) <= 1e-5
+    captured = np.sum((Fd @ Vg) ** 2)
+    assert 1 - captured / np.sum(sr ** 2) <= tol
+    # sigma reported must be the norms of F v_j
+    assert np.abs(np.linalg.norm(Fd @ Vg, axis=0) / sg - 1).max() <= max(tol, 1e-4)
+    if s_all is not None:
+        lead = lead or max(1, k // 2)
+        gap = s_all[lead - 1] / (s_all[lead - 1] - s_all[lead])
+        sines = principal_sines(Vg[:, :lead], Vr[:, :lead])
+        assert sines.max() <= tol * gap + 2e-4 * gap, f"leading subspace off: {sines.max():.2e} (gap factor {gap:.1f})"
+
+
+def test_fit_basis_tiny_config():
+    wl = WORKLOADS["tiny"]
+    F = torch.stack([FeatureStream(wl, b).at(0) for b in range(wl.B)])
+    V, sigma, fro2 = pkg.fit_basis(F.to(DEV), wl.k)
+    torch.cuda.synchronize()
+    for b in range(wl.B):
+        _fit_checks(F[b], V[b], sigma[b], fro2[b], wl.k, "f32")
+
+
+@pytest.mark.parametrize("dtype,N,D,k", [(torch.float32, 300, 96, 12), (torch.bfloat16, 500, 160, 16),
+                                          (torch.float32, 40, 64, 40), (torch.bfloat16, 129, 72, 3)])
+def test_fit_basis_power_law_inputs(dtype, N, D, k):
+    store = "f32" if dtype == torch.float32 else "bf16"
+    wl = WORKLOADS["flux1"].with_(N=N, D=D, k=k, dtype=store, signal_rank=min(48, D, N), rho=0.05)
+    F = FeatureStream(wl, 0).at(0).unsqueeze(0)
+    V, sigma, fro2 = pkg.fit_basis(F.to(DEV), k, q=6 if store == "f32" else 0)
+    torch.cuda.synchronize()
+    _fit_checks(F[0], V[0], sigma[0], fro2[0], k, store)
+
+
+def test_tiny_trajectory_matches_oracle_step_by_step():
+    """Config 1: 2 blocks, 256 x 64, k = 8, fp32, 10 steps, every 3rd a full step, alpha = 0.5.
+    The GPU-fitted basis is handed to the oracle so both sides use the same V."""
+    wl = WORKLOADS["tiny"]
+    streams = [FeatureStream(wl, b) for b in range(wl.B)]
+    feats = [torch.stack([s.at(t) for s in streams]) for t in range(wl.T)]
+    F0 = feats[0].to(DEV)
+    shape = pkg.make_shape(F0, wl.k)
+    V, sigma, _ = pkg.fit_basis(F0, wl.k)
+    pk = pkg.pack_basis(shape, V)
+    R = torch.empty_like(F0)
+    S = torch.empty(wl.B, wl.N, wl.k, device=DEV)
+    Fh = torch.empty_like(F0)
+    Vn = [to_np(V[b]) for b in range(wl.B)]
+    Rr = [None] * wl.B
+    Sr = [None] * wl.B
+    first = True
+    for t in range(wl.T):
+        if is_full_step(t, wl.interval):
+            pkg.svdcache_full_step(shape, feats[t].to(DEV), V, pk, R, S, None, wl.alpha, first)
+            torch.cuda.synchronize()
+            for b in range(wl.B):
+                Rr[b], Sr[b], _ = ref_full_step(to_np(feats[t][b]), Vn[b], Sr[b], wl.alpha, first, "f32")
+                assert_close(to_np(R[b]), Rr[b], "f32", f"t={t} R[{b}]")
+                assert_close(to_np(S[b]), Sr[b], "f32", f"t={t} S[{b}]")
+            first = False
+        else:
+            pkg.svdcache_forecast(shape, S, V, pk, R, Fh)
+            torch.cuda.synchronize()
+            for b in range(wl.B):
+                assert_close(to_np(Fh[b]), ref_forecast(Sr[b], Vn[b], Rr[b], "f32"), "f32", f"t={t} Fhat[{b}]")
+
+
+def test_checkpoint_split_is_bit_identical():
+    """The state is (V, S, R) in caller-owned tensors: 10 steps in one go equal 5 + restore + 5."""
+    wl = WORKLOADS["tiny"]
+    feats = [torch.stack([FeatureStream(wl, b).at(t) for b in range(wl.B)]).to(DEV) for t in range(wl.T)]
+    shape = pkg.make_shape(feats[0], wl.k)
+    V, _, _ = pkg.fit_basis(feats[0], wl.k)
+
+    def run(t0, t1, R, S, outs):
+        for t in range(t0, t1):
+            if is_full_step(t, wl.interval):
+                pkg.svdcache_full_step(shape, feats[t], V, None, R, S, None, wl.alpha, t == 0)
+                outs.append(R.clone())
+            else:
+                Fh = torch.empty_like(R)
+                pkg.svdcache_forecast(shape, S, V, None, R, Fh)
+                outs.append(Fh)
+        torch.cuda.synchronize()
+
+    R1, S1, o1 = torch.zeros_like(feats[0]), torch.zeros(wl.B, wl.N, wl.k, device=DEV), []
+    run(0, wl.T, R1, S1, o1)
+    R2, S2, o2 = torch.zeros_like(feats[0]), torch.zeros(wl.B, wl.N, wl.k, device=DEV), []
+    run(0, 5, R2, S2, o2)
+    saved = (R2.cpu(), S2.cpu())
+    R3, S3 = saved[0].to(DEV), saved[1].to(DEV)
+    run(5, wl.T, R3, S3, o2)
+    assert all(torch.equal(a, b) for a, b in zip(o1, o2))
+
+
+def test_errors_reported_through_the_binding():
+    F = torch.zeros(1, 16, 16, device=DEV)
+    shape = pkg.make_shape(F, 4)
+    V = torch.zeros(1, 16, 4, device=DEV)
+    S = torch.zeros(1, 16, 4, device=DEV)
+    with pytest.raises(pkg.SvdcError) as e:
+        pkg.svdcache_full_step(shape, F, V, None, F, S, None, 0.0, True)
+    assert e.value.code == -5
+    with pytest.raises(pkg.SvdcError) as e:
+        pkg.svdcache_fit_basis(shape, F, V, S, None, torch.zeros(16, device=DEV, dtype=torch.uint8))
+    assert e.value.code == -6
