@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the SVD-Cache hot path on one MI355X.
+
+One "step" is one sampling trajectory of the FLUX-shaped full-model workload: 57 cached blocks of
+4608 x 3072 bf16 features, rank 32, 50 timesteps with a full-compute step every 6th:
+
+    1 x svdcache_fit_basis (+ pack)   at t = 0        (one-time SVD, Sec. 3.3)
+    9 x svdcache_full_step            t = 0, 6, .., 48 (Eq. 8-11)
+   41 x svdcache_forecast             all other t      (Sec. 3.5)
+
+each call batched over the 57 blocks.  Inputs are synthetic (synth/), resident in HBM before the
+timed region.  Prints ONE JSON line; `value` is the algorithmic HBM bytes of a trajectory divided by
+its wall time.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TF = 2500.0     # dense bf16, published
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by a
+# copy kernel of known size (see profiles/); None until measured for the kernel that dominates.
+MEASURED_TRAFFIC = {}
+
+
+def algorithmic_bytes(wl, q_passes):
+    """Bytes each call must move (what the method needs, nothing it avoids), per batched launch."""
+    B, N, D, k, b = wl.B, wl.N, wl.D, wl.k, wl.elem_bytes
+    full = B * (2 * N * D * b + 2 * N * k * 4 + D * k * 4)          # read F, write R, S in/out, V
+    fore = B * (2 * N * D * b + N * k * 4 + D * k * 4)              # read R, write Fhat, S, V
+    fit = B * (q_passes * N * D * b)                                # one read of F per product with F
+    return full, fore, fit
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="flux57")
+    ap.add_argument("--k", type=int, default=0, help="override the rank")
+    ap.add_argument("--blocks", type=int, default=0, help="override the number of blocks")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); nothing here shards across GPUs",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2601_07396_amd as pkg
+    from synth import WORKLOADS, FeatureStream, is_full_step
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    if not os.path.exists(pkg.lib_path()):
+        from paper_2601_07396_amd import build
+        build.build()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = WORKLOADS[args.workload]
+    if args.k:
+        wl = wl.with_(k=args.k)
+    if args.blocks:
+        wl = wl.with_(B=args.blocks)
+    B, N, D, k = wl.B, wl.N, wl.D, wl.k
+    full_ts = [t for t in range(wl.T) if is_full_step(t, wl.interval)]
+    n_full, n_cached = len(full_ts), wl.T - len(full_ts)
+
+    # ---- synthetic inputs, resident in HBM ---------------------------------------------------
+    t0 = time.time()
+    dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    feats = [torch.empty(B, N, D, device=dev, dtype=dt) for _ in full_ts]
+    for b in range(B):
+        fs = FeatureStream(wl, b, device=dev)
+        for i, t in enumerate(full_ts):
+            feats[i][b] = fs.at(t)
+        del fs
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+
+    shape = pkg.make_shape(feats[0], k)
+    V = torch.empty(B, D, k, device=dev)
+    sigma = torch.empty(B, k, device=dev)
+    fro2 = torch.empty(B, device=dev)
+    ws = torch.empty(pkg.svdcache_fit_workspace_bytes(shape), device=dev, dtype=torch.uint8)
+    npk = pkg.svdcache_packed_basis_bytes(shape)
+    packed = torch.empty(npk, device=dev, dtype=torch.uint8) if npk else None
+    R = torch.empty_like(feats[0])
+    Fh = torch.empty_like(feats[0])
+    S = torch.empty(B, N, k, device=dev)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    times = {"fit": [], "full": [], "fore": []}
+
+    def trajectory(record):
+        fi = 0
+        for t in range(wl.T):
+            if is_full_step(t, wl.interval):
+                if t == 0:
+                    a, bb = ev(), ev()
+                    a.record()
+                    pkg.svdcache_fit_basis(shape, feats[0], V, sigma, fro2, ws)
+                    if packed is not None:
+                        pkg.svdcache_pack_basis(shape, V, packed)
+                    bb.record()
+                    if record:
+                        times["fit"].append((a, bb))
+                a, bb = ev(), ev()
+                a.record()
+                pkg.svdcache_full_step(shape, feats[fi], V, packed, R, S, None, wl.alpha, t == 0)
+                bb.record()
+                if record:
+                    times["full"].append((a, bb))
+                fi += 1
+            else:
+                a, bb = ev(), ev()
+                a.record()
+                pkg.svdcache_forecast(shape, S, V, packed, R, Fh)
+                bb.record()
+                if record:
+                    times["fore"].append((a, bb))
+
+    for _ in range(args.warmup):
+        trajectory(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        trajectory(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    avg = {kk: float(np.mean([a.elapsed_time(b) for a, b in v])) for kk, v in times.items()}
+    lo = {kk: float(np.min([a.elapsed_time(b) for a, b in v])) for kk, v in times.items()}
+
+    # ---- work accounting -------------------------------------------------------------------------
+    q = 3 if wl.dtype == "bf16" else 4
+    passes = 2 * q + 1
+    l = min(2 * k, N, D, 256)
+    by_full, by_fore, by_fit = algorithmic_bytes(wl, passes)
+    step_bytes = by_fit + n_full * by_full + n_cached * by_fore
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    fit_flops = B * passes * 2.0 * N * D * l
+    kernels = {
+        "svdcache_forecast": {"launches_per_step": n_cached, "avg_ms": avg["fore"], "min_ms": lo["fore"],
+                              "GBps": by_fore / avg["fore"] / 1e6, "bytes": by_fore},
+        "svdcache_full_step": {"launches_per_step": n_full, "avg_ms": avg["full"], "min_ms": lo["full"],
+                               "GBps": by_full / avg["full"] / 1e6, "bytes": by_full},
+        "svdcache_fit_basis": {"launches_per_step": 1, "avg_ms": avg["fit"], "min_ms": lo["fit"],
+                               "GBps": by_fit / avg["fit"] / 1e6, "TFLOPs": fit_flops / avg["fit"] / 1e9,
+                               "mfma_frac": fit_flops / avg["fit"] / 1e9 / MFMA_BF16_PEAK_TF,
+                               "sketch_width": l, "power_iters": q, "products_with_F": passes},
+    }
+    share = {"svdcache_forecast": n_cached * avg["fore"], "svdcache_full_step": n_full * avg["full"],
+             "svdcache_fit_basis": avg["fit"]}
+    dom = max(share, key=share.get)
+    dom_kernel = {"svdcache_forecast": "forecast_mfma_kernel", "svdcache_full_step": "full_step_mfma_kernel",
+                  "svdcache_fit_basis": "fit (several kernels)"}[dom]
+    if packed is None:
+        dom_kernel = dom_kernel.replace("mfma", "general")
+    ach = kernels[dom]["GBps"]
+    roofline = {"kernel": dom_kernel, "entry_point": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(dom_kernel),
+                "avg_launch_ms": kernels[dom]["avg_ms"], "algorithmic_bytes_per_launch": kernels[dom]["bytes"]}
+
+    # ---- CPU oracle on a bounded sample ----------------------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ref_fit_basis, ref_full_step, ref_forecast
+        try:
+            import threadpoolctl
+            threads = max(i["num_threads"] for i in threadpoolctl.threadpool_info()) if threadpoolctl.threadpool_info() else 1
+        except Exception:
+            threads = os.cpu_count() or 1
+        F0 = feats[0][0].to("cpu").double().numpy()
+        store = wl.dtype
+        t0 = time.perf_counter()
+        Vr, _, _ = ref_fit_basis(F0, k)
+        Rr, Sr, _ = ref_full_step(F0, Vr, None, wl.alpha, True, store)
+        ref_forecast(Sr, Vr, Rr, store)
+        cpu_s = time.perf_counter() - t0
+        one_block = (by_fit + by_full + by_fore) / B
+        cpu = {"value": one_block / cpu_s / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+               "seconds": cpu_s,
+               "sample": f"1 of {B} blocks ({N}x{D} {wl.dtype}, k={k}): one exact basis fit + one full step + one "
+                         f"cached step, numpy float64; bytes counted as for the GPU path"}
+
+    out = {
+        "metric": "SVD-Cache hot path (basis fit + full steps + cached steps) algorithmic HBM GB/s",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 storage, bf16x2-split MFMA products, f32 accumulate" if wl.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {B} blocks x {N} x {D} {wl.dtype}, k={k}, {wl.T} timesteps, full step "
+                               f"every {wl.interval} (per step: 1 fit + {n_full} full steps + {n_cached} cached steps)",
+                   "alpha": wl.alpha, "blocks": B, "N": N, "D": D, "k": k},
+        "frac_of_hbm_peak": value / HBM_PEAK_GBS,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "input_generation_s": gen_s,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

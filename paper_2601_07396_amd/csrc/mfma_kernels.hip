@@ -1,16 +1,445 @@
-// Matrix-core (MFMA) kernels for bf16 features -- placeholder until the fast path lands.
+// Matrix-core (MFMA) kernels for bf16 features on gfx950.
+//
+// All contractions go through v_mfma_f32_16x16x32_bf16 (wave64):
+//     D[m][n] += sum_kk A[m][kk] * B[kk][n],   m, n in 0..15, kk in 0..31
+// operand layout per lane l (r = l % 16, g = l / 16):
+//     A: 8 bf16 = A[m = r][kk = 8g .. 8g+7]        B: 8 bf16 = B[kk = 8g .. 8g+7][n = r]
+//     D: 4 f32  = D[m = 4g .. 4g+3][n = r]
+// The contraction index kk may be any fixed permutation of the mathematical
+// index as long as A and B use the same one, and the rows of A (columns of B)
+// may be any permutation of the output index.  The kernels below choose those
+// permutations so that
+//   * a lane's 16-byte piece of a feature row (8 consecutive hidden channels
+//     of one token) is at once a global-memory vector load, an MFMA operand
+//     and the position of the MFMA result it must be combined with, and
+//   * the accumulators of the projection are, after conversion to bf16,
+//     directly the operand of the reconstruction,
+// so no value ever moves between lanes.
+//
+// Basis operands are pre-packed once per fitted basis (svdcache_pack_basis)
+// as bf16 "high" and "low" parts (V = hi + lo to ~16 significant bits) in
+// per-wavefront tiles of 64 lanes x 16 bytes.
 #include "svdc_device.h"
 #include "svdc_internal.h"
 
 namespace svdc {
 
-bool mfma_shape_supported(const svdc_shape&) { return false; }
-size_t mfma_packed_bytes(const svdc_shape&) { return 0; }
-int32_t launch_pack_basis(const svdc_shape&, const float*, void*, hipStream_t) { return SVDC_E_SHAPE; }
-int32_t launch_full_step_mfma(const svdc_shape&, const void*, const void*, void*, float*, float*, float, int,
-                              hipStream_t) { return SVDC_E_SHAPE; }
-int32_t launch_forecast_mfma(const svdc_shape&, const float*, const void*, const void*, void*, hipStream_t) {
-  return SVDC_E_SHAPE;
+namespace {
+
+constexpr int kWavesPerGroup = 4;
+
+__device__ __forceinline__ f32x4 mfma16(const u32x4& a, const u32x4& b, const f32x4& c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                 0, 0, 0);
+}
+
+// rank padded to 32, 64 or 128 (one reconstruction MFMA contracts 32 coefficients)
+__host__ __device__ inline int padded_rank(int k) { return k <= 32 ? 32 : (k <= 64 ? 64 : 128); }
+
+// ---------------------------------------------------------------------------
+// Packed basis.  Per block, four arrays of D * KP bf16 each (KP = padded rank):
+//   P1hi, P1lo : projection operand.      tile (cg, jt) of 64 lanes x 8 bf16:
+//                lane (r, g), e  ->  V[d = 32 cg + 8 g + e][j = 16 jt + r]
+//   P2hi, P2lo : reconstruction operand, NEGATED.   tile (cg, t, kt):
+//                lane (r, g), e  -> -V[d = 32 cg + 8 (r / 4) + 4 t + r % 4][j = 32 kt + 16 (e / 4) + 4 g + e % 4]
+// with cg = d / 32 the 32-channel chunk, jt the 16-coefficient tile, t the
+// half of the chunk, kt the 32-coefficient group.  Entries with j >= k are 0.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_basis_kernel(const float* __restrict__ V, uint16_t* __restrict__ P,
+                                                         int D, int k, int KP) {
+  const int b = blockIdx.y;
+  const int64_t per = (int64_t)D * KP;           // elements per array
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= per) return;
+  const float* v = V + (int64_t)b * D * k;
+  uint16_t* p = P + (int64_t)b * 4 * per;
+  const int e = idx & 7, lane = (idx >> 3) & 63, r = lane & 15, g = lane >> 4;
+  const int64_t tile = idx >> 9;
+  {  // projection operand
+    const int KT = KP / 16;
+    const int jt = tile % KT, cg = tile / KT;
+    const int d = 32 * cg + 8 * g + e, j = 16 * jt + r;
+    const float x = j < k ? v[(int64_t)d * k + j] : 0.f;
+    const bf16_t hi = (bf16_t)x;
+    const bf16_t lo = (bf16_t)(x - (float)hi);
+    p[idx] = __builtin_bit_cast(uint16_t, hi);
+    p[per + idx] = __builtin_bit_cast(uint16_t, lo);
+  }
+  {  // reconstruction operand (negated so that the MFMA computes F - V C^T)
+    const int KT2 = KP / 32;
+    const int kt = tile % KT2, t = (tile / KT2) & 1, cg = tile / (2 * KT2);
+    const int d = 32 * cg + 8 * (r >> 2) + 4 * t + (r & 3);
+    const int j = 32 * kt + 16 * (e >> 2) + 4 * g + (e & 3);
+    const float x = j < k ? -v[(int64_t)d * k + j] : 0.f;
+    const bf16_t hi = (bf16_t)x;
+    const bf16_t lo = (bf16_t)(x - (float)hi);
+    p[2 * per + idx] = __builtin_bit_cast(uint16_t, hi);
+    p[3 * per + idx] = __builtin_bit_cast(uint16_t, lo);
+  }
+}
+
+// Workgroup id -> (block, row tile) such that the workgroups that land on one
+// XCD (ids congruent modulo 8) walk through the blocks one after the other:
+// each XCD's L2 then holds the packed basis of one or two blocks at a time.
+__device__ __forceinline__ bool xcd_tile(int tiles_per_block, int total, int* b, int* tile) {
+  const int per_xcd = (total + 7) / 8;
+  const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (v >= total) return false;
+  *b = v / tiles_per_block;
+  *tile = v % tiles_per_block;
+  return true;
+}
+
+// split 8 fp32 coefficients into bf16 high and low operand words
+__device__ __forceinline__ void split_operand(const float (&c)[8], u32x4* hi, u32x4* lo) {
+  float rem[8];
+  uint32_t h[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    h[i] = pack_bf16(c[2 * i], c[2 * i + 1]);
+    rem[2 * i] = c[2 * i] - bf16_lo(h[i]);
+    rem[2 * i + 1] = c[2 * i + 1] - bf16_hi(h[i]);
+  }
+  *hi = u32x4{h[0], h[1], h[2], h[3]};
+  *lo = u32x4{pack_bf16(rem[0], rem[1]), pack_bf16(rem[2], rem[3]), pack_bf16(rem[4], rem[5]),
+              pack_bf16(rem[6], rem[7])};
+}
+
+// ---------------------------------------------------------------------------
+// Cached step (Sec. 3.5):  Fhat = S V^T + R   for bf16 R / Fhat.
+// A workgroup of 4 waves takes 16*RT token rows; wave w takes the channels
+// [w D/4, (w+1) D/4) of those rows, in chunks of 32.  Per chunk and 16-row tile:
+// two MFMAs per 32 coefficients (one per half chunk) whose accumulator starts
+// at R; the packed basis is negated, so the coefficient operand is -S and the
+// MFMA computes Fhat^T = R^T + (-V)(-S)^T.
+// R is read once and Fhat written once; S (k floats per row) is read by every
+// wave of the group.
+// ---------------------------------------------------------------------------
+template <int RT, int KT2, bool SPLIT>
+__global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restrict__ S,
+                                                            const uint16_t* __restrict__ P, const bf16_t* R,
+                                                            bf16_t* Fh, int N, int D, int k, int64_t ldf,
+                                                            int64_t bstride, int tiles_per_block, int total) {
+  int b, tile;
+  if (!xcd_tile(tiles_per_block, total, &b, &tile)) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  constexpr int KP = KT2 * 32;
+  const int64_t per = (int64_t)D * KP;
+  const u32x4* P2hi = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 2 * per);
+  const u32x4* P2lo = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 3 * per);
+  const int row0 = tile * 16 * RT;
+
+  // coefficient operand: lane (r, g) needs -S[row][j = 32 kt + 16 t + 4 g + i]
+  u32x4 shi[RT][KT2], slo[RT][KT2];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int row = min(row0 + 16 * rt + r, N - 1);
+    const float* srow = S + ((int64_t)b * N + row) * k;
+#pragma unroll
+    for (int kt = 0; kt < KT2; ++kt) {
+      float c[8];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int j = 32 * kt + 16 * t + 4 * g;
+        if (j + 3 < k) {
+          const f32x4 x = *reinterpret_cast<const f32x4*>(srow + j);
+          c[4 * t] = -x[0]; c[4 * t + 1] = -x[1]; c[4 * t + 2] = -x[2]; c[4 * t + 3] = -x[3];
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) c[4 * t + i] = (j + i < k) ? -srow[j + i] : 0.f;
+        }
+      }
+      split_operand(c, &shi[rt][kt], &slo[rt][kt]);
+    }
+  }
+
+  const int nchunk = D / (32 * kWavesPerGroup);
+  const int cg0 = wave * nchunk;
+  const bf16_t* rbase = R + (int64_t)b * bstride;
+  bf16_t* obase = Fh + (int64_t)b * bstride;
+  for (int c = 0; c < nchunk; ++c) {
+    const int cg = cg0 + c;
+    const int col = 32 * cg + 8 * g;
+    u32x4 a_hi[2][KT2], a_lo[2][KT2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int kt = 0; kt < KT2; ++kt) {
+        const int64_t ti = ((int64_t)cg * 2 + t) * KT2 + kt;
+        a_hi[t][kt] = P2hi[ti * 64 + lane];
+        if (SPLIT) a_lo[t][kt] = P2lo[ti * 64 + lane];
+      }
+    u32x4 rin[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int row = min(row0 + 16 * rt + r, N - 1);
+      rin[rt] = *reinterpret_cast<const u32x4*>(rbase + (int64_t)row * ldf + col);
+    }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      u32x4 out;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        f32x4 acc = {bf16_lo(rin[rt][2 * t]), bf16_hi(rin[rt][2 * t]), bf16_lo(rin[rt][2 * t + 1]),
+                     bf16_hi(rin[rt][2 * t + 1])};
+#pragma unroll
+        for (int kt = 0; kt < KT2; ++kt) {
+          acc = mfma16(a_hi[t][kt], shi[rt][kt], acc);
+          if (SPLIT) {
+            acc = mfma16(a_hi[t][kt], slo[rt][kt], acc);
+            acc = mfma16(a_lo[t][kt], shi[rt][kt], acc);
+          }
+        }
+        out[2 * t] = pack_bf16(acc[0], acc[1]);
+        out[2 * t + 1] = pack_bf16(acc[2], acc[3]);
+      }
+      const int row = row0 + 16 * rt + r;
+      if (row < N) *reinterpret_cast<u32x4*>(obase + (int64_t)row * ldf + col) = out;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Full-compute step (Eq. 8-11) for bf16 F / R, one pass over F.
+// A workgroup of 4 waves holds a tile of 16*RT token rows x D channels in
+// registers: wave w keeps the channels [w D/4, (w+1) D/4) of all rows as packed
+// bf16 (RT * CH * 4 VGPRs, CH = D / 128 chunks of 32 channels).
+//   phase 1  C^T partial = V^T F^T over the wave's channels (MFMA), partials of
+//            the 4 waves summed through LDS in a fixed order
+//   EMA      wave w updates S (and writes C) for row tile w, w+4, ...
+//   phase 2  R^T = F^T - V C^T per chunk: accumulator starts at F, A operand
+//            is the negated basis, B operand is C (bf16 high + low parts)
+// ---------------------------------------------------------------------------
+template <int CH, int RT, int KT2, bool SPLIT>
+__global__ __launch_bounds__(256) void full_step_mfma_kernel(const bf16_t* F, const uint16_t* __restrict__ P,
+                                                             bf16_t* R, float* S, float* C, int N, int k,
+                                                             int64_t ldf, int64_t bstride, float alpha, int init,
+                                                             int tiles_per_block, int total) {
+  constexpr int KP = KT2 * 32, KT = KT2 * 2, D = CH * 128;
+  __shared__ f32x4 part[kWavesPerGroup][KT][RT][64];
+  int b, tile;
+  if (!xcd_tile(tiles_per_block, total, &b, &tile)) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  const int64_t per = (int64_t)D * KP;
+  const u32x4* P1hi = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per);
+  const u32x4* P1lo = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + per);
+  const u32x4* P2hi = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 2 * per);
+  const u32x4* P2lo = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 3 * per);
+  const int row0 = tile * 16 * RT;
+  const int cg0 = wave * CH;
+  const bf16_t* fbase = F + (int64_t)b * bstride;
+  bf16_t* obase = R + (int64_t)b * bstride;
+
+  // the wave's slab of the tile: 16 bytes per lane per (row tile, chunk)
+  u32x4 f[RT][CH];
+#pragma unroll
+  for (int c = 0; c < CH; ++c)
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int row = min(row0 + 16 * rt + r, N - 1);
+      f[rt][c] = *reinterpret_cast<const u32x4*>(fbase + (int64_t)row * ldf + 32 * (cg0 + c) + 8 * g);
+    }
+
+  // phase 1: acc[jt][rt] = C^T[j = 16 jt + 4 g + i][row = 16 rt + r] restricted to this wave's channels
+  f32x4 acc[KT][RT];
+#pragma unroll
+  for (int jt = 0; jt < KT; ++jt)
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) acc[jt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int c = 0; c < CH; ++c) {
+#pragma unroll
+    for (int jt = 0; jt < KT; ++jt) {
+      const int64_t ti = (int64_t)(cg0 + c) * KT + jt;
+      const u32x4 vh = P1hi[ti * 64 + lane];
+      u32x4 vl;
+      if (SPLIT) vl = P1lo[ti * 64 + lane];
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        acc[jt][rt] = mfma16(vh, f[rt][c], acc[jt][rt]);
+        if (SPLIT) acc[jt][rt] = mfma16(vl, f[rt][c], acc[jt][rt]);
+      }
+    }
+  }
+
+  // sum the four partial products through LDS, same order in every wave
+#pragma unroll
+  for (int jt = 0; jt < KT; ++jt)
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) part[wave][jt][rt][lane] = acc[jt][rt];
+  __syncthreads();
+#pragma unroll
+  for (int jt = 0; jt < KT; ++jt)
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      f32x4 s = part[0][jt][rt][lane];
+#pragma unroll
+      for (int w = 1; w < kWavesPerGroup; ++w) {
+        const f32x4 p = part[w][jt][rt][lane];
+        s[0] += p[0]; s[1] += p[1]; s[2] += p[2]; s[3] += p[3];
+      }
+      acc[jt][rt] = s;
+    }
+
+  // EMA update (Eq. 11, alpha = 1 - beta) and coefficient output, one wave per row tile
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    if ((rt % kWavesPerGroup) != wave) continue;
+    const int row = row0 + 16 * rt + r;
+    if (row >= N) continue;
+    const int64_t srow = ((int64_t)b * N + row) * k;
+#pragma unroll
+    for (int jt = 0; jt < KT; ++jt) {
+      const int j = 16 * jt + 4 * g;
+      const f32x4 c4 = acc[jt][rt];
+      if (j + 3 < k) {
+        f32x4 s4 = c4;
+        if (!init) {
+          const f32x4 old = *reinterpret_cast<const f32x4*>(S + srow + j);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) s4[i] = (1.f - alpha) * old[i] + alpha * c4[i];
+        }
+        *reinterpret_cast<f32x4*>(S + srow + j) = s4;
+        if (C) *reinterpret_cast<f32x4*>(C + srow + j) = c4;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (j + i < k) {
+            const float s1 = init ? c4[i] : (1.f - alpha) * S[srow + j + i] + alpha * c4[i];
+            S[srow + j + i] = s1;
+            if (C) C[srow + j + i] = c4[i];
+          }
+      }
+    }
+  }
+
+  // coefficient operand of the reconstruction: kk = 8 g + 4 t + i  <->  j = 32 kt + 16 t + 4 g + i
+  u32x4 chi[RT][KT2], clo[RT][KT2];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int kt = 0; kt < KT2; ++kt) {
+      float c8[8];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c8[4 * t + i] = acc[2 * kt + t][rt][i];
+      split_operand(c8, &chi[rt][kt], &clo[rt][kt]);
+    }
+
+  // phase 2: residual, chunk by chunk
+#pragma unroll
+  for (int c = 0; c < CH; ++c) {
+    u32x4 a_hi[2][KT2], a_lo[2][KT2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int kt = 0; kt < KT2; ++kt) {
+        const int64_t ti = ((int64_t)(cg0 + c) * 2 + t) * KT2 + kt;
+        a_hi[t][kt] = P2hi[ti * 64 + lane];
+        if (SPLIT) a_lo[t][kt] = P2lo[ti * 64 + lane];
+      }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      u32x4 out;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        f32x4 a = {bf16_lo(f[rt][c][2 * t]), bf16_hi(f[rt][c][2 * t]), bf16_lo(f[rt][c][2 * t + 1]),
+                   bf16_hi(f[rt][c][2 * t + 1])};
+#pragma unroll
+        for (int kt = 0; kt < KT2; ++kt) {
+          a = mfma16(a_hi[t][kt], chi[rt][kt], a);
+          if (SPLIT) {
+            a = mfma16(a_hi[t][kt], clo[rt][kt], a);
+            a = mfma16(a_lo[t][kt], chi[rt][kt], a);
+          }
+        }
+        out[2 * t] = pack_bf16(a[0], a[1]);
+        out[2 * t + 1] = pack_bf16(a[2], a[3]);
+      }
+      const int row = row0 + 16 * rt + r;
+      if (row < N) *reinterpret_cast<u32x4*>(obase + (int64_t)row * ldf + 32 * (cg0 + c) + 8 * g) = out;
+    }
+  }
+}
+
+constexpr bool kSplit = true;  // bf16 high + low operand parts (fp32-level products)
+
+}  // namespace
+
+bool mfma_shape_supported(const svdc_shape& s) {
+  if (s.dtype != SVDC_BF16) return false;
+  if (s.D % 128 != 0 || s.k > 128 || s.k % 4 != 0) return false;
+  const int ch = s.D / 128;
+  return ch == 2 || ch == 4 || ch == 24;
+}
+
+size_t mfma_packed_bytes(const svdc_shape& s) {
+  return (size_t)s.B * 4 * s.D * padded_rank(s.k) * sizeof(uint16_t);
+}
+
+int32_t launch_pack_basis(const svdc_shape& s, const float* V, void* packed, hipStream_t st) {
+  const int KP = padded_rank(s.k);
+  const int64_t per = (int64_t)s.D * KP;
+  dim3 grid((unsigned)((per + 255) / 256), s.B);
+  pack_basis_kernel<<<grid, 256, 0, st>>>(V, (uint16_t*)packed, s.D, s.k, KP);
+  return launch_status();
+}
+
+namespace {
+
+template <int RT, int KT2>
+int32_t forecast_launch(const svdc_shape& s, const float* S, const void* packed, const void* R, void* Fhat,
+                        hipStream_t st) {
+  const int tiles = (s.N + 16 * RT - 1) / (16 * RT);
+  const int total = tiles * s.B;
+  const int grid = (total + 7) / 8 * 8;
+  forecast_mfma_kernel<RT, KT2, kSplit><<<grid, 256, 0, st>>>(S, (const uint16_t*)packed, (const bf16_t*)R,
+                                                              (bf16_t*)Fhat, s.N, s.D, s.k, s.ldf, s.block_stride,
+                                                              tiles, total);
+  return launch_status();
+}
+
+template <int CH, int RT, int KT2>
+int32_t full_step_launch(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
+                         float alpha, int init, hipStream_t st) {
+  const int tiles = (s.N + 16 * RT - 1) / (16 * RT);
+  const int total = tiles * s.B;
+  const int grid = (total + 7) / 8 * 8;
+  full_step_mfma_kernel<CH, RT, KT2, kSplit><<<grid, 256, 0, st>>>((const bf16_t*)F, (const uint16_t*)packed,
+                                                                   (bf16_t*)R, S, C, s.N, s.k, s.ldf,
+                                                                   s.block_stride, alpha, init, tiles, total);
+  return launch_status();
+}
+
+template <int CH>
+int32_t full_step_by_rank(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
+                          float alpha, int init, hipStream_t st) {
+  constexpr int RT1 = CH <= 8 ? 4 : 3, RT2 = CH <= 8 ? 4 : 2, RT4 = CH <= 8 ? 2 : 1;
+  const int kp = padded_rank(s.k);
+  if (kp == 32) return full_step_launch<CH, RT1, 1>(s, F, packed, R, S, C, alpha, init, st);
+  if (kp == 64) return full_step_launch<CH, RT2, 2>(s, F, packed, R, S, C, alpha, init, st);
+  return full_step_launch<CH, RT4, 4>(s, F, packed, R, S, C, alpha, init, st);
+}
+
+}  // namespace
+
+int32_t launch_full_step_mfma(const svdc_shape& s, const void* F, const void* packed, void* R, float* S,
+                              float* C, float alpha, int init, hipStream_t st) {
+  switch (s.D / 128) {
+    case 2: return full_step_by_rank<2>(s, F, packed, R, S, C, alpha, init, st);
+    case 4: return full_step_by_rank<4>(s, F, packed, R, S, C, alpha, init, st);
+    case 24: return full_step_by_rank<24>(s, F, packed, R, S, C, alpha, init, st);
+    default: return SVDC_E_SHAPE;
+  }
+}
+
+int32_t launch_forecast_mfma(const svdc_shape& s, const float* S, const void* packed, const void* R,
+                             void* Fhat, hipStream_t st) {
+  const int kp = padded_rank(s.k);
+  if (kp == 32) return forecast_launch<4, 1>(s, S, packed, R, Fhat, st);
+  if (kp == 64) return forecast_launch<4, 2>(s, S, packed, R, Fhat, st);
+  return forecast_launch<2, 4>(s, S, packed, R, Fhat, st);
 }
 
 }  // namespace svdc

@@ -208,3 +208,81 @@ def test_errors_reported_through_the_binding():
     with pytest.raises(pkg.SvdcError) as e:
         pkg.svdcache_fit_basis(shape, F, V, S, None, torch.zeros(16, device=DEV, dtype=torch.uint8))
     assert e.value.code == -6
+
+
+# ---------------------------------------------------------------------------------------------
+# matrix-core (MFMA) path for bf16 features
+# ---------------------------------------------------------------------------------------------
+
+def _lowrank_problem(B, N, D, k, seed, rho=0.05):
+    """bf16 features with most energy in span(V) (like the real workload) plus a 5 % residual,
+    so that R is a small difference of large terms."""
+    g = torch.Generator().manual_seed(seed)
+    V = torch.linalg.qr(torch.randn(B, D, k, generator=g, dtype=torch.float64))[0]
+    Cc = torch.randn(B, N, k, generator=g, dtype=torch.float64) * (torch.arange(1, k + 1) ** -0.6)
+    sig = Cc @ V.transpose(1, 2)
+    noise = torch.randn(B, N, D, generator=g, dtype=torch.float64)
+    noise *= (rho / (1 - rho)) ** 0.5 * sig.norm() / noise.norm()
+    F = (sig + noise) * (D ** 0.5 / (sig.norm() / (B * N) ** 0.5))
+    S = Cc.float() * float(F.abs().mean() / sig.abs().mean())
+    return F.to(torch.bfloat16), V.float().contiguous(), S.contiguous()
+
+
+@pytest.mark.parametrize("B,N,D,k", [(2, 200, 256, 32), (1, 77, 512, 8), (3, 64, 256, 64), (1, 131, 512, 128),
+                                     (2, 49, 256, 20), (1, 150, 3072, 32), (2, 70, 3072, 64), (1, 140, 3072, 128),
+                                     (1, 33, 3072, 16)])
+def test_mfma_full_step_and_forecast(B, N, D, k):
+    F, V, S0 = _lowrank_problem(B, N, D, k, seed=N * 7 + k)
+    shape = pkg.make_shape(F, k)
+    assert pkg.svdcache_has_mfma_path(shape)
+    for init in (True, False):
+        R, S, Cc, shape, pk = _run_full(F, D, V, S0, 0.5, init)
+        assert pk is not None
+        Fh = torch.empty_like(R)
+        pkg.svdcache_forecast(shape, S, V.to(DEV), pk, R, Fh)
+        torch.cuda.synchronize()
+        for b in range(B):
+            Rr, Sr, Cr = ref_full_step(to_np(F[b]), to_np(V[b]), to_np(S0[b]), 0.5, init, "bf16")
+            assert_close(to_np(R[b]), Rr, "bf16", f"R[{b}]", floor_of=to_np(F[b]))
+            assert_close(to_np(S[b]), Sr, "f32", f"S[{b}]")
+            assert_close(to_np(Cc[b]), Cr, "f32", f"C[{b}]")
+            Fr = ref_forecast(to_np(S[b]), to_np(V[b]), to_np(R[b]), "bf16")
+            assert_close(to_np(Fh[b]), Fr, "bf16", f"Fhat[{b}]")
+            # the split-operand arithmetic is far inside the bf16 budget: the error is the output rounding
+            assert rel_err(to_np(R[b]), Rr) <= 3e-3 and rel_err(to_np(Fh[b]), Fr) <= 3e-3
+
+
+def test_mfma_and_general_paths_agree():
+    """Same inputs through the packed (MFMA) and the unpacked (general) kernels."""
+    B, N, D, k = 2, 100, 512, 32
+    F, V, S0 = _lowrank_problem(B, N, D, k, seed=3)
+    Ra, Sa, Ca, shape, pk = _run_full(F, D, V, S0, 0.3, False)
+    Rb, Sb, Cb, _, none = _run_full(F, D, V, S0, 0.3, False, packed=None)
+    assert pk is not None and none is None
+    assert rel_err(to_np(Sa), to_np(Sb)) <= 1e-5 and rel_err(to_np(Ca), to_np(Cb)) <= 1e-5
+    assert rel_err(to_np(Ra), to_np(Rb)) <= 3e-3
+    Fa, Fb = torch.empty_like(Ra), torch.empty_like(Ra)
+    pkg.svdcache_forecast(shape, Sa, V.to(DEV), pk, Ra, Fa)
+    pkg.svdcache_forecast(shape, Sa, V.to(DEV), None, Ra, Fb)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(Fa), to_np(Fb)) <= 3e-3
+
+
+def test_mfma_inplace_and_strided():
+    B, N, D, k, ldf = 2, 90, 256, 32, 384
+    F, V, S0 = _lowrank_problem(B, N, D, k, seed=11)
+    buf = torch.zeros(B, N, ldf, dtype=torch.bfloat16)
+    buf[:, :, :D] = F
+    R, S, _, shape, pk = _run_full(buf, D, V, S0, 0.5, False, want_C=False, inplace=True)
+    assert pk is not None and shape.ldf == ldf
+    for b in range(B):
+        Rr, Sr, _ = ref_full_step(to_np(F[b]), to_np(V[b]), to_np(S0[b]), 0.5, False, "bf16")
+        assert_close(to_np(R[b, :, :D]), Rr, "bf16", "R in place", floor_of=to_np(F[b]))
+        assert_close(to_np(S[b]), Sr, "f32", "S")
+    assert torch.equal(R[:, :, D:].cpu(), buf[:, :, D:])
+    Rc = R.clone()
+    pkg.svdcache_forecast(shape, S, V.to(DEV), pk, R[:, :, :D], R[:, :, :D])
+    torch.cuda.synchronize()
+    for b in range(B):
+        assert_close(to_np(R[b, :, :D]), ref_forecast(to_np(S[b]), to_np(V[b]), to_np(Rc[b, :, :D]), "bf16"),
+                     "bf16", "Fhat in place")
