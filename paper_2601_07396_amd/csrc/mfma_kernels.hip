@@ -107,94 +107,107 @@ __device__ __forceinline__ void split_operand(const float (&c)[8], u32x4* hi, u3
 
 // ---------------------------------------------------------------------------
 // Cached step (Sec. 3.5):  Fhat = S V^T + R   for bf16 R / Fhat.
-// A workgroup of 4 waves takes 16*RT token rows; wave w takes the channels
-// [w D/4, (w+1) D/4) of those rows, in chunks of 32.  Per chunk and 16-row tile:
-// two MFMAs per 32 coefficients (one per half chunk) whose accumulator starts
-// at R; the packed basis is negated, so the coefficient operand is -S and the
-// MFMA computes Fhat^T = R^T + (-V)(-S)^T.
-// R is read once and Fhat written once; S (k floats per row) is read by every
-// wave of the group.
+//
+// Basis-stationary: a wave keeps the (negated) reconstruction operands of NCW
+// consecutive 32-channel chunks in registers and streams 16-row tiles of R past
+// them, so the basis is read from L2 once per workgroup, not once per tile.
+// A workgroup of 4 waves covers 4*NCW chunks (a "slab" of 128*NCW channels) and
+// kTilesPerGroup row tiles; adjacent workgroup ids are adjacent slabs of the same
+// rows.  Per tile and chunk: two MFMAs per 32 coefficients whose accumulator
+// starts at R; the coefficient operand is -S (bf16 high + low parts), so the
+// MFMA computes Fhat^T = R^T + (-V)(-S)^T.  PD tiles are kept in flight.
 // ---------------------------------------------------------------------------
-template <int RT, int KT2, bool SPLIT>
+constexpr int kTilesPerGroup = 8;
+
+template <int NCW, int KT2, bool SPLIT, int PD>
 __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restrict__ S,
                                                             const uint16_t* __restrict__ P, const bf16_t* R,
                                                             bf16_t* Fh, int N, int D, int k, int64_t ldf,
-                                                            int64_t bstride, int tiles_per_block, int total) {
-  int b, tile;
-  if (!xcd_tile(tiles_per_block, total, &b, &tile)) return;
+                                                            int64_t bstride, int NS, int groups_per_block) {
+  const int slab = blockIdx.x % NS;
+  const int rgb = blockIdx.x / NS;
+  const int b = rgb / groups_per_block, rg = rgb % groups_per_block;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
   constexpr int KP = KT2 * 32;
   const int64_t per = (int64_t)D * KP;
   const u32x4* P2hi = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 2 * per);
   const u32x4* P2lo = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 3 * per);
-  const int row0 = tile * 16 * RT;
+  const int cg0 = (slab * kWavesPerGroup + wave) * NCW;
+  const bf16_t* rbase = R + (int64_t)b * bstride + 32 * cg0 + 8 * g;
+  bf16_t* obase = Fh + (int64_t)b * bstride + 32 * cg0 + 8 * g;
+  const float* sbase = S + (int64_t)b * N * k;
+  const int tile0 = rg * kTilesPerGroup;
+  const int ntiles = min(kTilesPerGroup, (N + 15) / 16 - tile0);
 
-  // coefficient operand: lane (r, g) needs -S[row][j = 32 kt + 16 t + 4 g + i]
-  u32x4 shi[RT][KT2], slo[RT][KT2];
+  u32x4 rin[PD][NCW];
+  f32x4 sraw[PD][KT2][2];
+  // lane (r, g) needs S[row][j = 32 kt + 16 t + 4 g + i], i = 0..3 (zero beyond k)
+  auto load_tile = [&](int tile, u32x4(&ri)[NCW], f32x4(&sr)[KT2][2]) {
+    const int row = min(tile * 16 + r, N - 1);
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    const int row = min(row0 + 16 * rt + r, N - 1);
-    const float* srow = S + ((int64_t)b * N + row) * k;
-#pragma unroll
-    for (int kt = 0; kt < KT2; ++kt) {
-      float c[8];
+    for (int kt = 0; kt < KT2; ++kt)
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const int j = 32 * kt + 16 * t + 4 * g;
-        if (j + 3 < k) {
-          const f32x4 x = *reinterpret_cast<const f32x4*>(srow + j);
-          c[4 * t] = -x[0]; c[4 * t + 1] = -x[1]; c[4 * t + 2] = -x[2]; c[4 * t + 3] = -x[3];
-        } else {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) c[4 * t + i] = (j + i < k) ? -srow[j + i] : 0.f;
-        }
+        sr[kt][t] = (j < k) ? *reinterpret_cast<const f32x4*>(sbase + (int64_t)row * k + j)
+                            : f32x4{0.f, 0.f, 0.f, 0.f};
       }
-      split_operand(c, &shi[rt][kt], &slo[rt][kt]);
-    }
-  }
+#pragma unroll
+    for (int c = 0; c < NCW; ++c) ri[c] = *reinterpret_cast<const u32x4*>(rbase + (int64_t)row * ldf + 32 * c);
+  };
+#pragma unroll
+  for (int u = 0; u < PD; ++u)
+    if (u < ntiles) load_tile(tile0 + u, rin[u], sraw[u]);
 
-  const int nchunk = D / (32 * kWavesPerGroup);
-  const int cg0 = wave * nchunk;
-  const bf16_t* rbase = R + (int64_t)b * bstride;
-  bf16_t* obase = Fh + (int64_t)b * bstride;
-  for (int c = 0; c < nchunk; ++c) {
-    const int cg = cg0 + c;
-    const int col = 32 * cg + 8 * g;
-    u32x4 a_hi[2][KT2], a_lo[2][KT2];
+  u32x4 a_hi[NCW][2][KT2], a_lo[NCW][2][KT2];
+#pragma unroll
+  for (int c = 0; c < NCW; ++c)
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int kt = 0; kt < KT2; ++kt) {
-        const int64_t ti = ((int64_t)cg * 2 + t) * KT2 + kt;
-        a_hi[t][kt] = P2hi[ti * 64 + lane];
-        if (SPLIT) a_lo[t][kt] = P2lo[ti * 64 + lane];
+        const int64_t ti = ((int64_t)(cg0 + c) * 2 + t) * KT2 + kt;
+        a_hi[c][t][kt] = P2hi[ti * 64 + lane];
+        if (SPLIT) a_lo[c][t][kt] = P2lo[ti * 64 + lane];
       }
-    u32x4 rin[RT];
+
+  for (int it = 0; it < ntiles; it += PD) {
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      const int row = min(row0 + 16 * rt + r, N - 1);
-      rin[rt] = *reinterpret_cast<const u32x4*>(rbase + (int64_t)row * ldf + col);
-    }
+    for (int u = 0; u < PD; ++u) {
+      if (it + u >= ntiles) continue;
+      const int tile = tile0 + it + u;
+      u32x4 shi[KT2], slo[KT2];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      u32x4 out;
+      for (int kt = 0; kt < KT2; ++kt) {
+        float c8[8];
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        f32x4 acc = {bf16_lo(rin[rt][2 * t]), bf16_hi(rin[rt][2 * t]), bf16_lo(rin[rt][2 * t + 1]),
-                     bf16_hi(rin[rt][2 * t + 1])};
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int kt = 0; kt < KT2; ++kt) {
-          acc = mfma16(a_hi[t][kt], shi[rt][kt], acc);
-          if (SPLIT) {
-            acc = mfma16(a_hi[t][kt], slo[rt][kt], acc);
-            acc = mfma16(a_lo[t][kt], shi[rt][kt], acc);
+          for (int i = 0; i < 4; ++i) c8[4 * t + i] = -sraw[u][kt][t][i];
+        split_operand(c8, &shi[kt], &slo[kt]);
+      }
+      const int row = tile * 16 + r;
+#pragma unroll
+      for (int c = 0; c < NCW; ++c) {
+        u32x4 out;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          f32x4 acc = {bf16_lo(rin[u][c][2 * t]), bf16_hi(rin[u][c][2 * t]), bf16_lo(rin[u][c][2 * t + 1]),
+                       bf16_hi(rin[u][c][2 * t + 1])};
+#pragma unroll
+          for (int kt = 0; kt < KT2; ++kt) {
+            acc = mfma16(a_hi[c][t][kt], shi[kt], acc);
+            if (SPLIT) {
+              acc = mfma16(a_hi[c][t][kt], slo[kt], acc);
+              acc = mfma16(a_lo[c][t][kt], shi[kt], acc);
+            }
           }
+          out[2 * t] = pack_bf16(acc[0], acc[1]);
+          out[2 * t + 1] = pack_bf16(acc[2], acc[3]);
         }
-        out[2 * t] = pack_bf16(acc[0], acc[1]);
-        out[2 * t + 1] = pack_bf16(acc[2], acc[3]);
+        if (row < N) *reinterpret_cast<u32x4*>(obase + (int64_t)row * ldf + 32 * c) = out;
       }
-      const int row = row0 + 16 * rt + r;
-      if (row < N) *reinterpret_cast<u32x4*>(obase + (int64_t)row * ldf + col) = out;
+      if (it + u + PD < ntiles) load_tile(tile + PD, rin[u], sraw[u]);
     }
   }
 }
@@ -388,16 +401,35 @@ int32_t launch_pack_basis(const svdc_shape& s, const float* V, void* packed, hip
 
 namespace {
 
-template <int RT, int KT2>
+template <int NCW, int KT2, int PD>
 int32_t forecast_launch(const svdc_shape& s, const float* S, const void* packed, const void* R, void* Fhat,
                         hipStream_t st) {
-  const int tiles = (s.N + 16 * RT - 1) / (16 * RT);
-  const int total = tiles * s.B;
-  const int grid = (total + 7) / 8 * 8;
-  forecast_mfma_kernel<RT, KT2, kSplit><<<grid, 256, 0, st>>>(S, (const uint16_t*)packed, (const bf16_t*)R,
-                                                              (bf16_t*)Fhat, s.N, s.D, s.k, s.ldf, s.block_stride,
-                                                              tiles, total);
+  const int NS = s.D / (128 * NCW);
+  const int ntile = (s.N + 15) / 16;
+  const int gpb = (ntile + kTilesPerGroup - 1) / kTilesPerGroup;
+  const int64_t grid = (int64_t)NS * gpb * s.B;
+  if (grid > 0x7fffffff) return SVDC_E_SHAPE;
+  forecast_mfma_kernel<NCW, KT2, kSplit, PD><<<(unsigned)grid, 256, 0, st>>>(
+      S, (const uint16_t*)packed, (const bf16_t*)R, (bf16_t*)Fhat, s.N, s.D, s.k, s.ldf, s.block_stride, NS, gpb);
   return launch_status();
+}
+
+// widest slab per wave (NCW chunks) that divides D / 128 and keeps the basis operands in registers
+template <int KT2, int PD>
+int32_t forecast_by_width(const svdc_shape& s, const float* S, const void* packed, const void* R, void* Fhat,
+                          hipStream_t st) {
+  constexpr int kMax = KT2 == 1 ? 12 : (KT2 == 2 ? 6 : 4);
+  const int m = s.D / 128;
+  if constexpr (kMax >= 12) {
+    if (m % 12 == 0) return forecast_launch<12, KT2, PD>(s, S, packed, R, Fhat, st);
+  }
+  if constexpr (kMax >= 6) {
+    if (m % 6 == 0) return forecast_launch<6, KT2, PD>(s, S, packed, R, Fhat, st);
+  }
+  if (m % 4 == 0) return forecast_launch<4, KT2, PD>(s, S, packed, R, Fhat, st);
+  if (m % 3 == 0) return forecast_launch<3, KT2, PD>(s, S, packed, R, Fhat, st);
+  if (m % 2 == 0) return forecast_launch<2, KT2, PD>(s, S, packed, R, Fhat, st);
+  return forecast_launch<1, KT2, PD>(s, S, packed, R, Fhat, st);
 }
 
 template <int CH, int RT, int KT2>
@@ -437,9 +469,9 @@ int32_t launch_full_step_mfma(const svdc_shape& s, const void* F, const void* pa
 int32_t launch_forecast_mfma(const svdc_shape& s, const float* S, const void* packed, const void* R,
                              void* Fhat, hipStream_t st) {
   const int kp = padded_rank(s.k);
-  if (kp == 32) return forecast_launch<4, 1>(s, S, packed, R, Fhat, st);
-  if (kp == 64) return forecast_launch<4, 2>(s, S, packed, R, Fhat, st);
-  return forecast_launch<2, 4>(s, S, packed, R, Fhat, st);
+  if (kp == 32) return forecast_by_width<1, 1>(s, S, packed, R, Fhat, st);
+  if (kp == 64) return forecast_by_width<2, 2>(s, S, packed, R, Fhat, st);
+  return forecast_by_width<4, 2>(s, S, packed, R, Fhat, st);
 }
 
 }  // namespace svdc
