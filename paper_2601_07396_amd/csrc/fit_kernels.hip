@@ -424,6 +424,9 @@ bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan)
   plan->off_M = off; off = align_up(off + B * l * l * sizeof(double), 256);
   plan->off_W = off; off = align_up(off + 2 * B * l * l * sizeof(double), 256);
   plan->off_misc = off; off = align_up(off + B * sizeof(double), 256);
+  plan->mfma = fit_mfma_supported(s, l);
+  plan->off_Qp = off;
+  if (plan->mfma) off = align_up(off + fit_mfma_packed_q_bytes(s, l), 256);
   plan->total = off;
   return true;
 }
@@ -505,19 +508,38 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   if (orth(Z, Q, G, M, B, s.D, l, st) != SVDC_OK) return SVDC_E_HIP;
   std::swap(Q, Z);  // Q now names the orthonormal basis
 
+  void* Qp = ws + pl.off_Qp;
+  const bool want_fro = fro2 != nullptr;
+  bool fro_done = false;
+  if (want_fro) zero_f64(misc, B, st);
+  // Y = F Q.  The last product feeds the Rayleigh-Ritz step and uses the full-precision operand split.
+  auto project = [&](bool last) {
+    if (pl.mfma) {
+      fit_mfma_pack_q(s, l, Q, Qp, st);
+      zero_f32(Y, (int64_t)B * s.N * l, st);
+      fit_mfma_project(s, l, F, Qp, Y, (last && want_fro) ? misc : nullptr, last, st);
+      if (last && want_fro) fro_done = true;
+    } else {
+      gemm_fq<T>(s, l, F, Q, Y, st);
+    }
+  };
   for (int it = 0; it < pl.q; ++it) {
-    gemm_fq<T>(s, l, F, Q, Y, st);
-    gemm_fty<T>(s, l, F, Y, Z, st);
+    project(false);
+    if (pl.mfma) {
+      zero_f32(Z, (int64_t)B * s.D * l, st);
+      fit_mfma_backproject(s, l, F, Y, Z, st);
+    } else {
+      gemm_fty<T>(s, l, F, Y, Z, st);
+    }
     if (orth(Z, Q, G, M, B, s.D, l, st) != SVDC_OK) return SVDC_E_HIP;
     std::swap(Q, Z);
   }
 
   // Rayleigh-Ritz on span(Q)
-  gemm_fq<T>(s, l, F, Q, Y, st);
+  project(true);
   gram(Y, G, B, s.N, l, st);
   if (chol_inv(G, nullptr, B, l, st) != SVDC_OK) return SVDC_E_HIP;
-  if (fro2) {
-    zero_f64(misc, B, st);
+  if (want_fro && !fro_done) {
     const int rpg = 64;
     sumsq_kernel<T><<<dim3((s.N + rpg - 1) / rpg, B), 256, 0, st>>>(F, misc, s.N, s.D, s.ldf, s.block_stride, rpg);
   }

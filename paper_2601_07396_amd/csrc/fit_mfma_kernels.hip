@@ -1,0 +1,328 @@
+// Matrix-core versions of the two products with F in the basis fit (bf16 features):
+//   project      Y[N x l] += F[:, slab]   * Q[slab, :]        (Q stationary in registers)
+//   backproject  Z[D x l] += F[rows, :]^T * Y[rows, :]         (Z accumulators stationary in registers)
+// Both stream F exactly once, in 16- or 32-row tiles, on v_mfma_f32_16x16x32_bf16
+// (operand layouts: see mfma_kernels.hip).  Partial results of different
+// workgroups are combined with float atomics, so Y and Z must be zero on entry.
+#include "svdc_device.h"
+#include "svdc_internal.h"
+
+namespace svdc {
+
+namespace {
+
+constexpr int kWaves = 4;
+constexpr int kProjTiles = 8;     // 16-row tiles per workgroup in project
+constexpr int kBackRows = 768;    // rows per workgroup in backproject (multiple of 32)
+
+__device__ __forceinline__ f32x4 mfma16(const u32x4& a, const u32x4& b, const f32x4& c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                 0, 0, 0);
+}
+
+// Q [B, D, l] float32 -> bf16 high / low operand tiles (projection layout):
+//   tile (cg, jt), lane (r, g), e  ->  Q[d = 32 cg + 8 g + e][j = 16 jt + r]   (0 for j >= l)
+// Per block: hi array of D * LP elements followed by the lo array, LP = 16 KT.
+__global__ __launch_bounds__(256) void pack_q_kernel(const float* __restrict__ Q, uint16_t* __restrict__ P, int D,
+                                                     int l, int KT) {
+  const int b = blockIdx.y;
+  const int64_t per = (int64_t)D * KT * 16;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= per) return;
+  const int e = idx & 7, lane = (idx >> 3) & 63, r = lane & 15, g = lane >> 4;
+  const int64_t tile = idx >> 9;
+  const int jt = tile % KT, cg = tile / KT;
+  const int d = 32 * cg + 8 * g + e, j = 16 * jt + r;
+  const float x = j < l ? Q[((int64_t)b * D + d) * l + j] : 0.f;
+  const bf16_t hi = (bf16_t)x;
+  const bf16_t lo = (bf16_t)(x - (float)hi);
+  uint16_t* p = P + (int64_t)b * 2 * per;
+  p[idx] = __builtin_bit_cast(uint16_t, hi);
+  p[per + idx] = __builtin_bit_cast(uint16_t, lo);
+}
+
+// ---------------------------------------------------------------------------
+// project: a wave keeps the Q operands of NCW chunks (32 channels each) for all
+// KT coefficient tiles in registers and streams 16-row tiles of F past them.
+//   A operand = F tile   (m = token row, kk = channel)   -- the natural 16-byte row pieces
+//   B operand = Q tile   (kk = channel, n = coefficient)
+//   D[m = 4 g + i][n = r]  ->  Y[row 16 tile + 4 g + i][16 jt + r]
+// FRO: also accumulate sum F^2 (for ||F||_F^2).
+// ---------------------------------------------------------------------------
+template <int NCW, int KT, bool SPLIT, bool FRO, int PD>
+__global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __restrict__ F,
+                                                               const uint16_t* __restrict__ Qp, float* Y,
+                                                               double* fro_acc, int N, int D, int l, int64_t ldf,
+                                                               int64_t bstride, int NS, int groups_per_block) {
+  const int slab = blockIdx.x % NS;
+  const int rgb = blockIdx.x / NS;
+  const int b = rgb / groups_per_block, rg = rgb % groups_per_block;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  const int64_t per = (int64_t)D * KT * 16;
+  const u32x4* Qhi = reinterpret_cast<const u32x4*>(Qp + (int64_t)b * 2 * per);
+  const u32x4* Qlo = reinterpret_cast<const u32x4*>(Qp + (int64_t)b * 2 * per + per);
+  const int cg0 = (slab * kWaves + wave) * NCW;
+  const bf16_t* fbase = F + (int64_t)b * bstride + 32 * cg0 + 8 * g;
+  float* ybase = Y + (int64_t)b * N * l;
+  const int tile0 = rg * kProjTiles;
+  const int ntiles = min(kProjTiles, (N + 15) / 16 - tile0);
+
+  u32x4 fin[PD][NCW];
+  auto load_tile = [&](int tile, u32x4(&fi)[NCW]) {
+    const int row = min(tile * 16 + r, N - 1);
+#pragma unroll
+    for (int c = 0; c < NCW; ++c) fi[c] = *reinterpret_cast<const u32x4*>(fbase + (int64_t)row * ldf + 32 * c);
+  };
+#pragma unroll
+  for (int u = 0; u < PD; ++u)
+    if (u < ntiles) load_tile(tile0 + u, fin[u]);
+
+  u32x4 q_hi[NCW][KT], q_lo[NCW][KT];
+#pragma unroll
+  for (int c = 0; c < NCW; ++c)
+#pragma unroll
+    for (int jt = 0; jt < KT; ++jt) {
+      const int64_t ti = (int64_t)(cg0 + c) * KT + jt;
+      q_hi[c][jt] = Qhi[ti * 64 + lane];
+      if (SPLIT) q_lo[c][jt] = Qlo[ti * 64 + lane];
+    }
+
+  float ssq = 0.f;
+  for (int it = 0; it < ntiles; it += PD) {
+#pragma unroll
+    for (int u = 0; u < PD; ++u) {
+      if (it + u >= ntiles) continue;
+      const int tile = tile0 + it + u;
+      f32x4 acc[KT];
+#pragma unroll
+      for (int jt = 0; jt < KT; ++jt) acc[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < NCW; ++c) {
+#pragma unroll
+        for (int jt = 0; jt < KT; ++jt) {
+          acc[jt] = mfma16(fin[u][c], q_hi[c][jt], acc[jt]);
+          if (SPLIT) acc[jt] = mfma16(fin[u][c], q_lo[c][jt], acc[jt]);
+        }
+        if (FRO && tile * 16 + r < N) {
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const float x0 = bf16_lo(fin[u][c][w]), x1 = bf16_hi(fin[u][c][w]);
+            ssq += x0 * x0 + x1 * x1;
+          }
+        }
+      }
+      if (it + u + PD < ntiles) load_tile(tile + PD, fin[u]);
+#pragma unroll
+      for (int jt = 0; jt < KT; ++jt) {
+        const int j = 16 * jt + r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = tile * 16 + 4 * g + i;
+          if (row < N && j < l) atomicAdd(ybase + (int64_t)row * l + j, acc[jt][i]);
+        }
+      }
+    }
+  }
+  if (FRO) {
+    const double s = wave_sum((double)ssq);
+    if (lane == 0) atomicAdd(fro_acc + b, s);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// backproject: Z[d][j] += sum_rows F[row][d] Y[row][j] over the workgroup's rows.
+// The contraction runs over token rows, so both operands need 8 consecutive
+// rows per lane:
+//   A operand (m = channel, kk = row): a lane loads, for each of its 8 rows, the
+//       32-bit word holding channels (2 r, 2 r + 1) of a 32-channel chunk and
+//       regroups the low / high halves with v_perm into the operands of the
+//       "even" (d = 2 r) and "odd" (d = 2 r + 1) channel tiles;
+//   B operand (kk = row, n = coefficient): Y[row 8 g + e][16 jt + r] converted to bf16.
+//   D[m = 4 g + i][n = r]  ->  Z[32 chunk + 2 (4 g + i) + parity][16 jt + r]
+// Accumulators (NCW chunks x 2 parities x KT tiles) stay in registers over all rows.
+// ---------------------------------------------------------------------------
+template <int NCW, int KT>
+__global__ __launch_bounds__(256) void fit_backproject_mfma_kernel(const bf16_t* __restrict__ F,
+                                                                   const float* __restrict__ Y, float* Z, int N,
+                                                                   int D, int l, int64_t ldf, int64_t bstride,
+                                                                   int NS, int groups_per_block) {
+  const int slab = blockIdx.x % NS;
+  const int rgb = blockIdx.x / NS;
+  const int b = rgb / groups_per_block, rg = rgb % groups_per_block;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  const int cg0 = (slab * kWaves + wave) * NCW;
+  const uint32_t* fbase = reinterpret_cast<const uint32_t*>(F + (int64_t)b * bstride + 32 * cg0) + r;
+  const int64_t ldw = ldf / 2;   // row stride in 32-bit words
+  const float* ybase = Y + (int64_t)b * N * l;
+  const int row_begin = rg * kBackRows;
+  const int row_end = min(N, row_begin + kBackRows);
+
+  f32x4 acc[NCW][2][KT];
+#pragma unroll
+  for (int c = 0; c < NCW; ++c)
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+      for (int jt = 0; jt < KT; ++jt) acc[c][p][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  uint32_t fw[NCW][8];
+  float yv[KT][8];
+  auto load_step = [&](int row0) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int row = row0 + 8 * g + e;
+      const int rowc = min(row, N - 1);
+#pragma unroll
+      for (int c = 0; c < NCW; ++c) fw[c][e] = fbase[(int64_t)rowc * ldw + 16 * c];
+#pragma unroll
+      for (int jt = 0; jt < KT; ++jt) {
+        const int j = 16 * jt + r;
+        yv[jt][e] = (row < row_end && j < l) ? ybase[(int64_t)row * l + j] : 0.f;
+      }
+    }
+  };
+  if (row_begin < row_end) load_step(row_begin);
+  for (int row0 = row_begin; row0 < row_end; row0 += 32) {
+    u32x4 yop[KT];
+#pragma unroll
+    for (int jt = 0; jt < KT; ++jt)
+      yop[jt] = u32x4{pack_bf16(yv[jt][0], yv[jt][1]), pack_bf16(yv[jt][2], yv[jt][3]),
+                      pack_bf16(yv[jt][4], yv[jt][5]), pack_bf16(yv[jt][6], yv[jt][7])};
+    u32x4 fop[NCW][2];
+#pragma unroll
+    for (int c = 0; c < NCW; ++c)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        fop[c][0][w] = __builtin_amdgcn_perm(fw[c][2 * w + 1], fw[c][2 * w], 0x05040100u);
+        fop[c][1][w] = __builtin_amdgcn_perm(fw[c][2 * w + 1], fw[c][2 * w], 0x07060302u);
+      }
+    if (row0 + 32 < row_end) load_step(row0 + 32);
+#pragma unroll
+    for (int c = 0; c < NCW; ++c)
+#pragma unroll
+      for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int jt = 0; jt < KT; ++jt) acc[c][p][jt] = mfma16(fop[c][p], yop[jt], acc[c][p][jt]);
+  }
+
+  float* zbase = Z + (int64_t)b * D * l;
+#pragma unroll
+  for (int c = 0; c < NCW; ++c)
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+      for (int jt = 0; jt < KT; ++jt) {
+        const int j = 16 * jt + r;
+        if (j >= l) continue;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int d = 32 * (cg0 + c) + 2 * (4 * g + i) + p;
+          atomicAdd(zbase + (int64_t)d * l + j, acc[c][p][jt][i]);
+        }
+      }
+}
+
+template <int KT>
+constexpr int width_for() { return KT <= 2 ? 12 : (KT == 4 ? 6 : 3); }
+
+template <int NCW, int KT>
+void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, double* fro_acc,
+                    bool split, hipStream_t st) {
+  const int NS = s.D / (128 * NCW);
+  const int ntile = (s.N + 15) / 16;
+  const int gpb = (ntile + kProjTiles - 1) / kProjTiles;
+  const unsigned grid = (unsigned)((int64_t)NS * gpb * s.B);
+  const bf16_t* f = (const bf16_t*)F;
+  const uint16_t* q = (const uint16_t*)Qp;
+  constexpr int PD = 2;
+  if (split) {
+    if (fro_acc)
+      fit_project_mfma_kernel<NCW, KT, true, true, PD><<<grid, 256, 0, st>>>(f, q, Y, fro_acc, s.N, s.D, l, s.ldf,
+                                                                           s.block_stride, NS, gpb);
+    else
+      fit_project_mfma_kernel<NCW, KT, true, false, PD><<<grid, 256, 0, st>>>(f, q, Y, fro_acc, s.N, s.D, l, s.ldf,
+                                                                            s.block_stride, NS, gpb);
+  } else {
+    fit_project_mfma_kernel<NCW, KT, false, false, PD><<<grid, 256, 0, st>>>(f, q, Y, fro_acc, s.N, s.D, l, s.ldf,
+                                                                           s.block_stride, NS, gpb);
+  }
+}
+
+template <int NCW, int KT>
+void backproject_launch(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, hipStream_t st) {
+  const int NS = s.D / (128 * NCW);
+  const int gpb = (s.N + kBackRows - 1) / kBackRows;
+  const unsigned grid = (unsigned)((int64_t)NS * gpb * s.B);
+  fit_backproject_mfma_kernel<NCW, KT><<<grid, 256, 0, st>>>((const bf16_t*)F, Y, Z, s.N, s.D, l, s.ldf,
+                                                            s.block_stride, NS, gpb);
+}
+
+// largest instantiated slab width (chunks per wave) that divides D / 128 and is at most `cap`
+template <int KT, typename Fn12, typename Fn6, typename Fn4, typename Fn3, typename Fn2, typename Fn1>
+void by_width(int m, Fn12 f12, Fn6 f6, Fn4 f4, Fn3 f3, Fn2 f2, Fn1 f1) {
+  constexpr int cap = width_for<KT>();
+  if constexpr (cap >= 12) { if (m % 12 == 0) return f12(); }
+  if constexpr (cap >= 6) { if (m % 6 == 0) return f6(); }
+  if constexpr (cap >= 4) { if (m % 4 == 0) return f4(); }
+  if (m % 3 == 0) return f3();
+  if (m % 2 == 0) return f2();
+  return f1();
+}
+
+template <int KT>
+void project_kt(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, double* fro, bool split,
+                hipStream_t st) {
+  constexpr int cap = width_for<KT>();
+  by_width<KT>(
+      s.D / 128, [&] { project_launch<(cap >= 12 ? 12 : 1), KT>(s, l, F, Qp, Y, fro, split, st); },
+      [&] { project_launch<(cap >= 6 ? 6 : 1), KT>(s, l, F, Qp, Y, fro, split, st); },
+      [&] { project_launch<(cap >= 4 ? 4 : 1), KT>(s, l, F, Qp, Y, fro, split, st); },
+      [&] { project_launch<3, KT>(s, l, F, Qp, Y, fro, split, st); },
+      [&] { project_launch<2, KT>(s, l, F, Qp, Y, fro, split, st); },
+      [&] { project_launch<1, KT>(s, l, F, Qp, Y, fro, split, st); });
+}
+
+template <int KT>
+void backproject_kt(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, hipStream_t st) {
+  constexpr int cap = width_for<KT>();
+  by_width<KT>(
+      s.D / 128, [&] { backproject_launch<(cap >= 12 ? 12 : 1), KT>(s, l, F, Y, Z, st); },
+      [&] { backproject_launch<(cap >= 6 ? 6 : 1), KT>(s, l, F, Y, Z, st); },
+      [&] { backproject_launch<(cap >= 4 ? 4 : 1), KT>(s, l, F, Y, Z, st); },
+      [&] { backproject_launch<3, KT>(s, l, F, Y, Z, st); }, [&] { backproject_launch<2, KT>(s, l, F, Y, Z, st); },
+      [&] { backproject_launch<1, KT>(s, l, F, Y, Z, st); });
+}
+
+}  // namespace
+
+bool fit_mfma_supported(const svdc_shape& s, int l) {
+  return s.dtype == SVDC_BF16 && s.D % 128 == 0 && l <= 128;
+}
+
+size_t fit_mfma_packed_q_bytes(const svdc_shape& s, int l) {
+  const int KT = l <= 16 ? 1 : (l <= 32 ? 2 : (l <= 64 ? 4 : 8));
+  return (size_t)s.B * 2 * s.D * KT * 16 * sizeof(uint16_t);
+}
+
+void fit_mfma_pack_q(const svdc_shape& s, int l, const float* Q, void* Qp, hipStream_t st) {
+  const int KT = l <= 16 ? 1 : (l <= 32 ? 2 : (l <= 64 ? 4 : 8));
+  const int64_t per = (int64_t)s.D * KT * 16;
+  pack_q_kernel<<<dim3((unsigned)((per + 255) / 256), s.B), 256, 0, st>>>(Q, (uint16_t*)Qp, s.D, l, KT);
+}
+
+void fit_mfma_project(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, double* fro_acc,
+                      bool split, hipStream_t st) {
+  if (l <= 16) project_kt<1>(s, l, F, Qp, Y, fro_acc, split, st);
+  else if (l <= 32) project_kt<2>(s, l, F, Qp, Y, fro_acc, split, st);
+  else if (l <= 64) project_kt<4>(s, l, F, Qp, Y, fro_acc, split, st);
+  else project_kt<8>(s, l, F, Qp, Y, fro_acc, split, st);
+}
+
+void fit_mfma_backproject(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, hipStream_t st) {
+  if (l <= 16) backproject_kt<1>(s, l, F, Y, Z, st);
+  else if (l <= 32) backproject_kt<2>(s, l, F, Y, Z, st);
+  else if (l <= 64) backproject_kt<4>(s, l, F, Y, Z, st);
+  else backproject_kt<8>(s, l, F, Y, Z, st);
+}
+
+}  // namespace svdc

@@ -30,10 +30,21 @@ struct FitPlan {
   int l;          // sketch width
   int q;          // power iterations
   uint64_t seed;
-  size_t off_Q, off_Z, off_Y, off_G, off_M, off_W, off_misc, total;
+  size_t off_Q, off_Z, off_Y, off_G, off_M, off_W, off_misc, off_Qp, total;
+  bool mfma;      // products with F on the matrix cores
 };
 bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan);
 int32_t run_fit(const svdc_shape& s, const FitPlan& plan, const void* F, float* V, float* sigma, float* fro2,
                 void* workspace, hipStream_t st);
+
+// ---- matrix-core products of the basis fit: fit_mfma_kernels.hip ------------------------
+bool fit_mfma_supported(const svdc_shape& s, int l);
+size_t fit_mfma_packed_q_bytes(const svdc_shape& s, int l);
+void fit_mfma_pack_q(const svdc_shape& s, int l, const float* Q, void* Qp, hipStream_t st);
+// Y (zeroed by the caller) += F Q;  fro_acc (nullable) += ||F||_F^2;  split: bf16 high + low parts of Q
+void fit_mfma_project(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, double* fro_acc,
+                      bool split, hipStream_t st);
+// Z (zeroed by the caller) += F^T Y
+void fit_mfma_backproject(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, hipStream_t st);
 
 }  // namespace svdc

@@ -286,3 +286,29 @@ def test_mfma_inplace_and_strided():
     for b in range(B):
         assert_close(to_np(R[b, :, :D]), ref_forecast(to_np(S[b]), to_np(V[b]), to_np(Rc[b, :, :D]), "bf16"),
                      "bf16", "Fhat in place")
+
+
+# ---------------------------------------------------------------------------------------------
+# basis fit with the products on the matrix cores (bf16 features, D % 128 == 0, k + p <= 128)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("N,D,k", [(300, 256, 16), (1000, 512, 32), (600, 3072, 32), (333, 384, 8), (700, 768, 64),
+                                   (200, 128, 4)])
+def test_fit_basis_mfma_path(N, D, k):
+    wl = WORKLOADS["flux1"].with_(N=N, D=D, k=k, signal_rank=min(96, D, N))
+    F = torch.stack([FeatureStream(wl, b).at(0) for b in range(2)])
+    # at these small sizes the trailing singular values sit in the noise bulk (sigma_{l+1} / sigma_k close
+    # to 1), where subspace iteration converges slowly: use more power iterations than the default
+    V, sigma, fro2 = pkg.fit_basis(F.to(DEV), k, q=10)
+    torch.cuda.synchronize()
+    for b in range(2):
+        _fit_checks(F[b], V[b], sigma[b], fro2[b], k, "bf16")
+
+
+def test_fit_basis_flux_block_full_size():
+    """One FLUX-shaped block (4608 x 3072 bf16, k = 32) at full size against the exact decomposition."""
+    wl = WORKLOADS["flux1"]
+    F = FeatureStream(wl, 0, work=torch.float32).at(0).unsqueeze(0)
+    V, sigma, fro2 = pkg.fit_basis(F.to(DEV), wl.k)
+    torch.cuda.synchronize()
+    _fit_checks(F[0], V[0], sigma[0], fro2[0], wl.k, "bf16")
