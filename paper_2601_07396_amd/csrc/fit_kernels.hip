@@ -278,6 +278,155 @@ __global__ __launch_bounds__(256) void rows_times_small_kernel(const float* __re
 }
 
 // ---------------------------------------------------------------------------
+// Register-blocked version of chol_inv_kernel for l <= 16 * BS (BS = 4 or 8):
+// thread (ti, tj) of a 16 x 16 grid owns the BS x BS block (ti, tj) of the matrix
+// in registers.  Right-looking Cholesky: per column c the owners publish the
+// column through LDS (double buffered, one barrier per column) and every thread
+// applies the rank-1 update to its block.  The inverse factor is then formed
+// column by column (one thread per column) from the factor in LDS.
+// ---------------------------------------------------------------------------
+template <int BS>
+__global__ __launch_bounds__(256) void chol_inv_reg_kernel(double* G, double* Minv, int l, double rel_shift) {
+  constexpr int LM = 16 * BS;          // padded matrix size
+  constexpr int LX = LM + 1;           // padded row stride of the inverse (bank spread)
+  extern __shared__ double dyn_lds[];
+  double* Ls = dyn_lds;                // [LM][LM] factor, row-major
+  double* Xs = dyn_lds + LM * LM;      // [LM][LX] row j = column j of L^-1
+  __shared__ double colbuf[2][LM];
+  __shared__ double s_shift;
+  const int b = blockIdx.x, t = threadIdx.x, ti = t >> 4, tj = t & 15;
+  double* g = G + (int64_t)b * l * l;
+  if (t < kWave) {
+    double mx = 0.0;
+    for (int i = t; i < l; i += kWave) mx = fmax(mx, g[(int64_t)i * l + i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o, kWave));
+    if (t == 0) s_shift = mx * rel_shift;
+  }
+  __syncthreads();
+  double a[BS][BS];
+#pragma unroll
+  for (int ii = 0; ii < BS; ++ii)
+#pragma unroll
+    for (int jj = 0; jj < BS; ++jj) {
+      const int i = BS * ti + ii, j = BS * tj + jj;
+      double v = (i < l && j < l) ? g[(int64_t)i * l + j] : (i == j ? 1.0 : 0.0);   // identity padding
+      if (i == j && i < l) v += s_shift;
+      a[ii][jj] = v;
+    }
+  for (int c = 0; c < l; ++c) {
+    double* col = colbuf[c & 1];
+    if (tj == c / BS) {
+      const int jj = c % BS;
+#pragma unroll
+      for (int ii = 0; ii < BS; ++ii)
+#pragma unroll
+        for (int q = 0; q < BS; ++q)
+          if (q == jj) col[BS * ti + ii] = a[ii][q];
+    }
+    __syncthreads();
+    const double piv2 = fmax(col[c], 1e-300);
+    const double piv = sqrt(piv2);
+    const double rs = 1.0 / piv, inv = rs * rs;
+    double ci[BS], cj[BS];
+#pragma unroll
+    for (int ii = 0; ii < BS; ++ii) ci[ii] = col[BS * ti + ii];
+#pragma unroll
+    for (int jj = 0; jj < BS; ++jj) cj[jj] = col[BS * tj + jj];
+#pragma unroll
+    for (int ii = 0; ii < BS; ++ii)
+#pragma unroll
+      for (int jj = 0; jj < BS; ++jj) {
+        const int i = BS * ti + ii, j = BS * tj + jj;
+        if (j > c && i >= j) a[ii][jj] -= ci[ii] * cj[jj] * inv;
+        else if (j == c && i >= c) a[ii][jj] = (i == c) ? piv : ci[ii] * rs;
+      }
+  }
+#pragma unroll
+  for (int ii = 0; ii < BS; ++ii)
+#pragma unroll
+    for (int jj = 0; jj < BS; ++jj) {
+      const int i = BS * ti + ii, j = BS * tj + jj;
+      const double v = (j <= i) ? a[ii][jj] : 0.0;
+      Ls[i * LM + j] = v;
+      if (i < l && j < l) g[(int64_t)i * l + j] = v;
+    }
+  __syncthreads();
+  if (!Minv) return;
+  // column j of L^-1 by forward substitution, one thread per column
+  for (int j = t; j < l; j += 256) {
+    double* xj = Xs + j * LX;
+    xj[j] = 1.0 / Ls[j * LM + j];
+    for (int i = j + 1; i < l; ++i) {
+      double sacc = 0.0;
+      for (int mm = j; mm < i; ++mm) sacc += Ls[i * LM + mm] * xj[mm];
+      xj[i] = -sacc / Ls[i * LM + i];
+    }
+  }
+  __syncthreads();
+  double* m = Minv + (int64_t)b * l * l;
+  for (int idx = t; idx < l * l; idx += 256) {
+    const int j = idx / l, i = idx % l;
+    m[idx] = (i >= j) ? Xs[j * LX + i] : 0.0;    // row j of Minv = column j of L^-1  (Minv = L^-T)
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Tiled version of rows_times_small_kernel for l <= 128: a workgroup computes a
+// 64-row x 64-column tile of Out = In * M with M (float64) and the rows of In
+// staged in LDS; every thread accumulates a 4 x 4 block in float64.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rows_times_small_tiled_kernel(const float* __restrict__ In,
+                                                                     const double* __restrict__ M, float* Out,
+                                                                     int rows, int l, int m, int ldm) {
+  extern __shared__ double dyn_lds[];
+  double* Ms = dyn_lds;                                        // [l][64]
+  float* tile = reinterpret_cast<float*>(dyn_lds + l * 64);    // [64][l + 1]
+  const int lt = l + 1;
+  const int b = blockIdx.z, t = threadIdx.x;
+  const float* in = In + (int64_t)b * rows * l;
+  const double* mm = M + (int64_t)b * l * ldm;
+  float* out = Out + (int64_t)b * rows * m;
+  const int r0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
+  for (int idx = t; idx < l * 64; idx += 256) {
+    const int i = idx >> 6, j = idx & 63;
+    Ms[idx] = (j0 + j < m) ? mm[(int64_t)i * ldm + j0 + j] : 0.0;
+  }
+  for (int idx = t; idx < 64 * l; idx += 256) {
+    const int rr = idx / l, c = idx % l;
+    tile[rr * lt + c] = (r0 + rr < rows) ? in[(int64_t)(r0 + rr) * l + c] : 0.f;
+  }
+  __syncthreads();
+  const int ty = t >> 4, tx = t & 15;
+  double acc[4][4];
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) acc[ii][jj] = 0.0;
+  for (int i = 0; i < l; ++i) {
+    double av[4], bv[4];
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii) av[ii] = (double)tile[(4 * ty + ii) * lt + i];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) bv[jj] = Ms[i * 64 + tx + 16 * jj];
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) acc[ii][jj] += av[ii] * bv[jj];
+  }
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii) {
+    const int row = r0 + 4 * ty + ii;
+    if (row >= rows) continue;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const int j = j0 + tx + 16 * jj;
+      if (j < m) out[(int64_t)row * m + j] = (float)acc[ii][jj];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // One-sided (Hestenes) Jacobi SVD of A = L^T (l x l, float64), one workgroup per
 // block: plane rotations on column pairs until all columns are orthogonal, with
 // a round-robin ordering so that l/2 disjoint pairs are rotated concurrently.
@@ -294,12 +443,13 @@ __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ 
   __shared__ int s_rot;
   const int b = blockIdx.x, t = threadIdx.x;
   const double* Lf = Lfac + (int64_t)b * l * l;
-  double* A = a_in_lds ? dyn_lds : gA + (int64_t)b * l * l;                       // column-major
-  double* W = w_in_lds ? dyn_lds + (a_in_lds ? l * l : 0) : gW + (int64_t)b * l * l;  // column-major
+  const int la = l + 1;   // column stride, padded so that concurrently rotated columns spread over the LDS banks
+  double* A = a_in_lds ? dyn_lds : gA + (int64_t)b * l * la;                        // column-major
+  double* W = w_in_lds ? dyn_lds + (a_in_lds ? l * la : 0) : gW + (int64_t)b * l * la;  // column-major
   for (int idx = t; idx < l * l; idx += 256) {
     const int c = idx / l, r = idx % l;
-    A[idx] = (r <= c) ? Lf[idx] : 0.0;   // A[r][c] = L[c][r]
-    W[idx] = (r == c) ? 1.0 : 0.0;
+    A[c * la + r] = (r <= c) ? Lf[idx] : 0.0;   // A[r][c] = L[c][r]
+    W[c * la + r] = (r == c) ? 1.0 : 0.0;
   }
   if (t == 0 && fro2) fro2[b] = (float)fro_acc[b];
   __syncthreads();
@@ -321,8 +471,8 @@ __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ 
         else { p = (step + group) % (le - 1); q = (step + (le - 1) - group) % (le - 1); }
       }
       if (active && p < l && q < l) {
-        double* ap = A + (int64_t)p * l;
-        double* aq = A + (int64_t)q * l;
+        double* ap = A + (int64_t)p * la;
+        double* aq = A + (int64_t)q * la;
         double al = 0.0, be = 0.0, ga = 0.0;
         for (int r = gl; r < l; r += tp) {
           const double x = ap[r], y = aq[r];
@@ -333,12 +483,12 @@ __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ 
           be += __shfl_xor(be, o, kWave);
           ga += __shfl_xor(ga, o, kWave);
         }
-        if (fabs(ga) > 1e-15 * sqrt(al * be) && ga != 0.0) {
+        if (fabs(ga) > 1e-13 * sqrt(al * be) && ga != 0.0) {
           const double zeta = (be - al) / (2.0 * ga);
           const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
           const double cs = 1.0 / sqrt(1.0 + tt * tt), sn = cs * tt;
-          double* wp = W + (int64_t)p * l;
-          double* wq = W + (int64_t)q * l;
+          double* wp = W + (int64_t)p * la;
+          double* wq = W + (int64_t)q * la;
           for (int r = gl; r < l; r += tp) {
             const double x = ap[r], y = aq[r];
             ap[r] = cs * x - sn * y;
@@ -359,7 +509,7 @@ __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ 
 
   for (int j = t; j < l; j += 256) {
     double s = 0.0;
-    for (int r = 0; r < l; ++r) s += A[(int64_t)j * l + r] * A[(int64_t)j * l + r];
+    for (int r = 0; r < l; ++r) s += A[(int64_t)j * la + r] * A[(int64_t)j * la + r];
     nrm[j] = s;
   }
   __syncthreads();
@@ -369,7 +519,7 @@ __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ 
     int rank = 0;
     for (int i = 0; i < l; ++i) rank += (nrm[i] > nj || (nrm[i] == nj && i < j)) ? 1 : 0;
     if (rank < k) sigma[(int64_t)b * k + rank] = (float)sqrt(nj);
-    for (int i = 0; i < l; ++i) wo[(int64_t)i * l + rank] = W[(int64_t)j * l + i];
+    for (int i = 0; i < l; ++i) wo[(int64_t)i * l + rank] = W[(int64_t)j * la + i];
   }
 }
 
@@ -422,7 +572,7 @@ bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan)
   plan->off_Y = off; off = align_up(off + B * (size_t)s.N * l * sizeof(float), 256);
   plan->off_G = off; off = align_up(off + B * l * l * sizeof(double), 256);
   plan->off_M = off; off = align_up(off + B * l * l * sizeof(double), 256);
-  plan->off_W = off; off = align_up(off + 2 * B * l * l * sizeof(double), 256);
+  plan->off_W = off; off = align_up(off + 2 * B * l * (l + 1) * sizeof(double), 256);
   plan->off_misc = off; off = align_up(off + B * sizeof(double), 256);
   plan->mfma = fit_mfma_supported(s, l);
   plan->off_Qp = off;
@@ -471,6 +621,13 @@ void gram(const float* A, double* G, int B, int rows, int l, hipStream_t st) {
 }
 
 int32_t chol_inv(double* G, double* Minv, int B, int l, hipStream_t st) {
+  if (l <= 64) {
+    constexpr int LM = 64;
+    const size_t bytes = ((size_t)LM * LM + (size_t)LM * (LM + 1)) * sizeof(double);
+    if (set_dyn_lds((const void*)chol_inv_reg_kernel<4>, bytes) != SVDC_OK) return SVDC_E_HIP;
+    chol_inv_reg_kernel<4><<<B, 256, bytes, st>>>(G, Minv, l, 1e-14);
+    return SVDC_OK;
+  }
   const size_t bytes = (size_t)l * l * sizeof(double);
   const int use_lds = bytes <= kLdsBudget;
   if (use_lds && set_dyn_lds((const void*)chol_inv_kernel, bytes) != SVDC_OK) return SVDC_E_HIP;
@@ -478,16 +635,33 @@ int32_t chol_inv(double* G, double* Minv, int B, int l, hipStream_t st) {
   return SVDC_OK;
 }
 
-// Q_out = orth(Z_in) by CholeskyQR2; Z_in is overwritten (used as the intermediate).
-int32_t orth(float* Zin, float* Qout, double* G, double* M, int B, int rows, int l, hipStream_t st) {
-  dim3 ag((rows + 15) / 16, B);
+// Out[rows x m] = In[rows x l] * M[l x m]
+int32_t rows_times_small(const float* In, const double* M, float* Out, int B, int rows, int l, int m, int ldm,
+                         hipStream_t st) {
+  if (l <= 128) {
+    const size_t bytes = (size_t)l * 64 * sizeof(double) + (size_t)64 * (l + 1) * sizeof(float);
+    if (set_dyn_lds((const void*)rows_times_small_tiled_kernel, bytes) != SVDC_OK) return SVDC_E_HIP;
+    dim3 grid((rows + 63) / 64, (m + 63) / 64, B);
+    rows_times_small_tiled_kernel<<<grid, 256, bytes, st>>>(In, M, Out, rows, l, m, ldm);
+  } else {
+    rows_times_small_kernel<<<dim3((rows + 15) / 16, B), 256, 0, st>>>(In, M, Out, rows, l, m, ldm);
+  }
+  return SVDC_OK;
+}
+
+// Orthonormalise the columns of Zin by CholeskyQR (Gram matrix and Cholesky factor in float64).
+// One pass leaves the result in Qout and is accurate to about eps32 * cond(Zin): enough to keep the
+// power iteration well conditioned.  two_pass repeats the step on the result (CholeskyQR2), giving
+// orthonormality at float32 round-off; the result is then back in Zin.
+int32_t orth(float* Zin, float* Qout, double* G, double* M, int B, int rows, int l, bool two_pass,
+             hipStream_t st) {
   gram(Zin, G, B, rows, l, st);
   if (chol_inv(G, M, B, l, st) != SVDC_OK) return SVDC_E_HIP;
-  rows_times_small_kernel<<<ag, 256, 0, st>>>(Zin, M, Qout, rows, l, l, l);
+  if (rows_times_small(Zin, M, Qout, B, rows, l, l, l, st) != SVDC_OK) return SVDC_E_HIP;
+  if (!two_pass) return SVDC_OK;
   gram(Qout, G, B, rows, l, st);
   if (chol_inv(G, M, B, l, st) != SVDC_OK) return SVDC_E_HIP;
-  rows_times_small_kernel<<<ag, 256, 0, st>>>(Qout, M, Zin, rows, l, l, l);
-  return SVDC_OK;
+  return rows_times_small(Qout, M, Zin, B, rows, l, l, l, st);
 }
 
 template <typename T>
@@ -504,9 +678,14 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
 
   const int64_t nq = (int64_t)B * s.D * l;
   init_omega_kernel<<<(unsigned)((nq + 255) / 256), 256, 0, st>>>(Z, (int64_t)s.D * l, nq, pl.seed);
-  // orth() leaves its result in its first argument after the second pass
-  if (orth(Z, Q, G, M, B, s.D, l, st) != SVDC_OK) return SVDC_E_HIP;
-  std::swap(Q, Z);  // Q now names the orthonormal basis
+  // Q <- orth(Omega).  With no power iteration this Q goes straight into the Rayleigh-Ritz step and
+  // must be orthonormal to round-off (two passes, result back in the first argument).
+  if (pl.q == 0) {
+    if (orth(Z, Q, G, M, B, s.D, l, true, st) != SVDC_OK) return SVDC_E_HIP;
+    std::swap(Q, Z);
+  } else {
+    if (orth(Z, Q, G, M, B, s.D, l, false, st) != SVDC_OK) return SVDC_E_HIP;
+  }
 
   void* Qp = ws + pl.off_Qp;
   const bool want_fro = fro2 != nullptr;
@@ -516,7 +695,6 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   auto project = [&](bool last) {
     if (pl.mfma) {
       fit_mfma_pack_q(s, l, Q, Qp, st);
-      zero_f32(Y, (int64_t)B * s.N * l, st);
       fit_mfma_project(s, l, F, Qp, Y, (last && want_fro) ? misc : nullptr, last, st);
       if (last && want_fro) fro_done = true;
     } else {
@@ -531,8 +709,9 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
     } else {
       gemm_fty<T>(s, l, F, Y, Z, st);
     }
-    if (orth(Z, Q, G, M, B, s.D, l, st) != SVDC_OK) return SVDC_E_HIP;
-    std::swap(Q, Z);
+    const bool last_it = it + 1 == pl.q;
+    if (orth(Z, Q, G, M, B, s.D, l, last_it, st) != SVDC_OK) return SVDC_E_HIP;
+    if (last_it) std::swap(Q, Z);
   }
 
   // Rayleigh-Ritz on span(Q)
@@ -543,14 +722,14 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
     const int rpg = 64;
     sumsq_kernel<T><<<dim3((s.N + rpg - 1) / rpg, B), 256, 0, st>>>(F, misc, s.N, s.D, s.ldf, s.block_stride, rpg);
   }
-  const size_t mat = (size_t)l * l * sizeof(double);
+  const size_t mat = (size_t)l * (l + 1) * sizeof(double);
   const int a_in_lds = mat <= kLdsBudget;
   const int w_in_lds = 2 * mat <= kLdsBudget;
   const size_t lds = (a_in_lds ? mat : 0) + (w_in_lds ? mat : 0);
   if (set_dyn_lds((const void*)jacobi_kernel, lds) != SVDC_OK) return SVDC_E_HIP;
-  jacobi_kernel<<<B, 256, lds, st>>>(G, M, sigma, Wg, Wg + (int64_t)B * l * l, l, s.k, a_in_lds, w_in_lds, misc,
+  jacobi_kernel<<<B, 256, lds, st>>>(G, M, sigma, Wg, Wg + (int64_t)B * l * (l + 1), l, s.k, a_in_lds, w_in_lds, misc,
                                      fro2);
-  rows_times_small_kernel<<<dim3((s.D + 15) / 16, B), 256, 0, st>>>(Q, M, V, s.D, l, s.k, l);
+  if (rows_times_small(Q, M, V, B, s.D, l, s.k, l, st) != SVDC_OK) return SVDC_E_HIP;
   return launch_status();
 }
 

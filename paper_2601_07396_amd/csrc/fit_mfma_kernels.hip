@@ -2,8 +2,9 @@
 //   project      Y[N x l] += F[:, slab]   * Q[slab, :]        (Q stationary in registers)
 //   backproject  Z[D x l] += F[rows, :]^T * Y[rows, :]         (Z accumulators stationary in registers)
 // Both stream F exactly once, in 16- or 32-row tiles, on v_mfma_f32_16x16x32_bf16
-// (operand layouts: see mfma_kernels.hip).  Partial results of different
-// workgroups are combined with float atomics, so Y and Z must be zero on entry.
+// (operand layouts: see mfma_kernels.hip).  project stores Y directly; backproject
+// combines the partial results of different row groups with float atomics, so Z
+// must be zero on entry.
 #include "svdc_device.h"
 #include "svdc_internal.h"
 
@@ -12,7 +13,6 @@ namespace svdc {
 namespace {
 
 constexpr int kWaves = 4;
-constexpr int kProjTiles = 8;     // 16-row tiles per workgroup in project
 constexpr int kBackRows = 768;    // rows per workgroup in backproject (multiple of 32)
 
 __device__ __forceinline__ f32x4 mfma16(const u32x4& a, const u32x4& b, const f32x4& c) {
@@ -42,90 +42,124 @@ __global__ __launch_bounds__(256) void pack_q_kernel(const float* __restrict__ Q
 }
 
 // ---------------------------------------------------------------------------
-// project: a wave keeps the Q operands of NCW chunks (32 channels each) for all
-// KT coefficient tiles in registers and streams 16-row tiles of F past them.
+// project: Y = F Q for a group of TG 16-row tiles per workgroup, no atomics.
+// The workgroup walks over the channel slabs (128 * NCW channels each); for one
+// slab wave w keeps the Q operands of its NCW chunks (all KT coefficient tiles)
+// in registers and streams the group's row tiles of that slab past them.  The
+// partial products of all slabs accumulate in registers (TG x KT accumulators per
+// wave); at the end the four waves' partial sums are added through LDS in a
+// fixed order and stored once.
 //   A operand = F tile   (m = token row, kk = channel)   -- the natural 16-byte row pieces
 //   B operand = Q tile   (kk = channel, n = coefficient)
 //   D[m = 4 g + i][n = r]  ->  Y[row 16 tile + 4 g + i][16 jt + r]
 // FRO: also accumulate sum F^2 (for ||F||_F^2).
 // ---------------------------------------------------------------------------
-template <int NCW, int KT, bool SPLIT, bool FRO, int PD>
+template <int NCW, int KT, int TG, bool SPLIT, bool FRO>
 __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __restrict__ F,
                                                                const uint16_t* __restrict__ Qp, float* Y,
                                                                double* fro_acc, int N, int D, int l, int64_t ldf,
                                                                int64_t bstride, int NS, int groups_per_block) {
-  const int slab = blockIdx.x % NS;
-  const int rgb = blockIdx.x / NS;
-  const int b = rgb / groups_per_block, rg = rgb % groups_per_block;
+  constexpr int PD = 2;
+  static_assert(TG % PD == 0, "prefetch ring must divide the tile group");
+  __shared__ f32x4 part[kWaves][2][KT][64];
+  const int b = blockIdx.x / groups_per_block, rg = blockIdx.x % groups_per_block;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
   const int64_t per = (int64_t)D * KT * 16;
   const u32x4* Qhi = reinterpret_cast<const u32x4*>(Qp + (int64_t)b * 2 * per);
   const u32x4* Qlo = reinterpret_cast<const u32x4*>(Qp + (int64_t)b * 2 * per + per);
-  const int cg0 = (slab * kWaves + wave) * NCW;
-  const bf16_t* fbase = F + (int64_t)b * bstride + 32 * cg0 + 8 * g;
-  float* ybase = Y + (int64_t)b * N * l;
-  const int tile0 = rg * kProjTiles;
-  const int ntiles = min(kProjTiles, (N + 15) / 16 - tile0);
+  const bf16_t* fbase = F + (int64_t)b * bstride + 8 * g;
+  const int tile0 = rg * TG;
+  const int ntiles = min(TG, (N + 15) / 16 - tile0);
+
+  f32x4 acc[TG][KT];
+#pragma unroll
+  for (int t = 0; t < TG; ++t)
+#pragma unroll
+    for (int jt = 0; jt < KT; ++jt) acc[t][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   u32x4 fin[PD][NCW];
-  auto load_tile = [&](int tile, u32x4(&fi)[NCW]) {
-    const int row = min(tile * 16 + r, N - 1);
+  auto load_tile = [&](int slab, int t, u32x4(&fi)[NCW]) {
+    const int row = min((tile0 + t) * 16 + r, N - 1);
+    const int cg0 = (slab * kWaves + wave) * NCW;
 #pragma unroll
-    for (int c = 0; c < NCW; ++c) fi[c] = *reinterpret_cast<const u32x4*>(fbase + (int64_t)row * ldf + 32 * c);
+    for (int c = 0; c < NCW; ++c)
+      fi[c] = *reinterpret_cast<const u32x4*>(fbase + (int64_t)row * ldf + 32 * (cg0 + c));
   };
 #pragma unroll
-  for (int u = 0; u < PD; ++u)
-    if (u < ntiles) load_tile(tile0 + u, fin[u]);
-
-  u32x4 q_hi[NCW][KT], q_lo[NCW][KT];
-#pragma unroll
-  for (int c = 0; c < NCW; ++c)
-#pragma unroll
-    for (int jt = 0; jt < KT; ++jt) {
-      const int64_t ti = (int64_t)(cg0 + c) * KT + jt;
-      q_hi[c][jt] = Qhi[ti * 64 + lane];
-      if (SPLIT) q_lo[c][jt] = Qlo[ti * 64 + lane];
-    }
+  for (int u = 0; u < PD; ++u) load_tile(0, u, fin[u]);
 
   float ssq = 0.f;
-  for (int it = 0; it < ntiles; it += PD) {
+  for (int slab = 0; slab < NS; ++slab) {
+    const int cg0 = (slab * kWaves + wave) * NCW;
+    u32x4 q_hi[NCW][KT], q_lo[NCW][KT];
 #pragma unroll
-    for (int u = 0; u < PD; ++u) {
-      if (it + u >= ntiles) continue;
-      const int tile = tile0 + it + u;
-      f32x4 acc[KT];
+    for (int c = 0; c < NCW; ++c)
 #pragma unroll
-      for (int jt = 0; jt < KT; ++jt) acc[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int jt = 0; jt < KT; ++jt) {
+        const int64_t ti = (int64_t)(cg0 + c) * KT + jt;
+        q_hi[c][jt] = Qhi[ti * 64 + lane];
+        if (SPLIT) q_lo[c][jt] = Qlo[ti * 64 + lane];
+      }
 #pragma unroll
-      for (int c = 0; c < NCW; ++c) {
+    for (int t = 0; t < TG; ++t) {
+      const int u = t % PD;
+      if (t < ntiles) {
 #pragma unroll
-        for (int jt = 0; jt < KT; ++jt) {
-          acc[jt] = mfma16(fin[u][c], q_hi[c][jt], acc[jt]);
-          if (SPLIT) acc[jt] = mfma16(fin[u][c], q_lo[c][jt], acc[jt]);
-        }
-        if (FRO && tile * 16 + r < N) {
+        for (int c = 0; c < NCW; ++c) {
 #pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            const float x0 = bf16_lo(fin[u][c][w]), x1 = bf16_hi(fin[u][c][w]);
-            ssq += x0 * x0 + x1 * x1;
+          for (int jt = 0; jt < KT; ++jt) {
+            acc[t][jt] = mfma16(fin[u][c], q_hi[c][jt], acc[t][jt]);
+            if (SPLIT) acc[t][jt] = mfma16(fin[u][c], q_lo[c][jt], acc[t][jt]);
+          }
+          if (FRO && (tile0 + t) * 16 + r < N) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+              const float x0 = bf16_lo(fin[u][c][w]), x1 = bf16_hi(fin[u][c][w]);
+              ssq += x0 * x0 + x1 * x1;
+            }
           }
         }
       }
-      if (it + u + PD < ntiles) load_tile(tile + PD, fin[u]);
-#pragma unroll
-      for (int jt = 0; jt < KT; ++jt) {
-        const int j = 16 * jt + r;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int row = tile * 16 + 4 * g + i;
-          if (row < N && j < l) atomicAdd(ybase + (int64_t)row * l + j, acc[jt][i]);
-        }
+      // refill this ring slot with the tile PD steps ahead (possibly in the next slab)
+      if (t + PD < TG) {
+        if (t + PD < ntiles) load_tile(slab, t + PD, fin[u]);
+      } else if (slab + 1 < NS) {
+        load_tile(slab + 1, t + PD - TG, fin[u]);
       }
     }
   }
   if (FRO) {
     const double s = wave_sum((double)ssq);
     if (lane == 0) atomicAdd(fro_acc + b, s);
+  }
+
+  // add the four waves' partial sums, two row tiles per round
+  float* ybase = Y + (int64_t)b * N * l;
+#pragma unroll
+  for (int rd = 0; rd < TG / 2; ++rd) {
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int jt = 0; jt < KT; ++jt) part[wave][tt][jt][lane] = acc[2 * rd + tt][jt];
+    __syncthreads();
+#pragma unroll
+    for (int item = 0; item < 2 * KT; ++item) {
+      if ((item % kWaves) != wave) continue;
+      const int tt = item / KT, jt = item % KT;
+      f32x4 s = part[0][tt][jt][lane];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) {
+        const f32x4 p = part[w][tt][jt][lane];
+        s[0] += p[0]; s[1] += p[1]; s[2] += p[2]; s[3] += p[3];
+      }
+      const int j = 16 * jt + r;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = (tile0 + 2 * rd + tt) * 16 + 4 * g + i;
+        if (row < N && j < l) ybase[(int64_t)row * l + j] = s[i];
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -228,22 +262,25 @@ constexpr int width_for() { return KT <= 2 ? 12 : (KT == 4 ? 6 : 3); }
 template <int NCW, int KT>
 void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, double* fro_acc,
                     bool split, hipStream_t st) {
-  const int NS = s.D / (128 * NCW);
+  constexpr int TG = KT <= 4 ? 8 : 4;
+  // the split operand doubles the Q registers: halve the slab width when it is wide
+  constexpr int NCWS = (NCW * KT > 12 && NCW % 2 == 0) ? NCW / 2 : NCW;
   const int ntile = (s.N + 15) / 16;
-  const int gpb = (ntile + kProjTiles - 1) / kProjTiles;
-  const unsigned grid = (unsigned)((int64_t)NS * gpb * s.B);
+  const int gpb = (ntile + TG - 1) / TG;
+  const unsigned grid = (unsigned)((int64_t)gpb * s.B);
   const bf16_t* f = (const bf16_t*)F;
   const uint16_t* q = (const uint16_t*)Qp;
-  constexpr int PD = 2;
   if (split) {
+    const int NS = s.D / (128 * NCWS);
     if (fro_acc)
-      fit_project_mfma_kernel<NCW, KT, true, true, PD><<<grid, 256, 0, st>>>(f, q, Y, fro_acc, s.N, s.D, l, s.ldf,
-                                                                           s.block_stride, NS, gpb);
-    else
-      fit_project_mfma_kernel<NCW, KT, true, false, PD><<<grid, 256, 0, st>>>(f, q, Y, fro_acc, s.N, s.D, l, s.ldf,
+      fit_project_mfma_kernel<NCWS, KT, TG, true, true><<<grid, 256, 0, st>>>(f, q, Y, fro_acc, s.N, s.D, l, s.ldf,
                                                                             s.block_stride, NS, gpb);
+    else
+      fit_project_mfma_kernel<NCWS, KT, TG, true, false><<<grid, 256, 0, st>>>(f, q, Y, fro_acc, s.N, s.D, l, s.ldf,
+                                                                             s.block_stride, NS, gpb);
   } else {
-    fit_project_mfma_kernel<NCW, KT, false, false, PD><<<grid, 256, 0, st>>>(f, q, Y, fro_acc, s.N, s.D, l, s.ldf,
+    const int NS = s.D / (128 * NCW);
+    fit_project_mfma_kernel<NCW, KT, TG, false, false><<<grid, 256, 0, st>>>(f, q, Y, fro_acc, s.N, s.D, l, s.ldf,
                                                                            s.block_stride, NS, gpb);
   }
 }

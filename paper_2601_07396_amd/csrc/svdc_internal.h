@@ -41,7 +41,7 @@ int32_t run_fit(const svdc_shape& s, const FitPlan& plan, const void* F, float* 
 bool fit_mfma_supported(const svdc_shape& s, int l);
 size_t fit_mfma_packed_q_bytes(const svdc_shape& s, int l);
 void fit_mfma_pack_q(const svdc_shape& s, int l, const float* Q, void* Qp, hipStream_t st);
-// Y (zeroed by the caller) += F Q;  fro_acc (nullable) += ||F||_F^2;  split: bf16 high + low parts of Q
+// Y = F Q;  fro_acc (nullable) += ||F||_F^2;  split: bf16 high + low parts of Q
 void fit_mfma_project(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, double* fro_acc,
                       bool split, hipStream_t st);
 // Z (zeroed by the caller) += F^T Y
