@@ -42,6 +42,14 @@ extern "C" {
 /* storage type of F, R and Fhat; arithmetic always accumulates in float32 or wider */
 typedef enum { SVDC_F32 = 0, SVDC_BF16 = 1 } svdc_dtype;
 
+/* Arithmetic of the bf16 matrix-core kernels (ignored by the float32 / general kernels).
+ *   SVDC_PRECISE  V, C and S enter the products as bf16 high + low parts (about 16 significant
+ *                 bits): results differ from exact float32 products by ~1e-5 relative.
+ *   SVDC_FAST     single bf16 operands in the full step and the cached step: one third of the
+ *                 matrix-core work and half the basis traffic; the error of R is about
+ *                 1.1e-3 * ||C V^T|| / ||R|| relative (5e-3 when the residual holds 5 % of the energy). */
+typedef enum { SVDC_PRECISE = 0, SVDC_FAST = 1 } svdc_precision;
+
 typedef enum {
   SVDC_OK = 0,
   SVDC_E_NULL = -1,      /* a required pointer is NULL                          */
@@ -61,7 +69,8 @@ typedef struct {
   int32_t B, N, D, k;
   int64_t ldf;
   int64_t block_stride;
-  int32_t dtype; /* svdc_dtype */
+  int32_t dtype;     /* svdc_dtype */
+  int32_t precision; /* svdc_precision; 0 = SVDC_PRECISE */
 } svdc_shape;
 
 /* Parameters of the randomized basis fit.  Zero-initialise for defaults. */

@@ -7,14 +7,14 @@ function without the compiled library, or with tensors that are not on the
 GPU, raises.
 """
 from .binding import (
-    SvdcError, Shape, lib_path, load_library, exported_symbols,
+    SvdcError, Shape, SVDC_PRECISE, SVDC_FAST, lib_path, load_library, exported_symbols,
     svdcache_version, svdcache_strerror, svdcache_fit_workspace_bytes, svdcache_packed_basis_bytes,
     svdcache_has_mfma_path, svdcache_fit_basis, svdcache_pack_basis, svdcache_full_step, svdcache_forecast,
     make_shape, fit_basis, pack_basis,
 )
 
 __all__ = [
-    "SvdcError", "Shape", "lib_path", "load_library", "exported_symbols",
+    "SvdcError", "Shape", "SVDC_PRECISE", "SVDC_FAST", "lib_path", "load_library", "exported_symbols",
     "svdcache_version", "svdcache_strerror", "svdcache_fit_workspace_bytes", "svdcache_packed_basis_bytes",
     "svdcache_has_mfma_path", "svdcache_fit_basis", "svdcache_pack_basis", "svdcache_full_step",
     "svdcache_forecast", "make_shape", "fit_basis", "pack_basis",

@@ -10,6 +10,7 @@ import torch
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 
 SVDC_F32, SVDC_BF16 = 0, 1
+SVDC_PRECISE, SVDC_FAST = 0, 1
 _DTYPES = {torch.float32: SVDC_F32, torch.bfloat16: SVDC_BF16}
 
 
@@ -22,7 +23,7 @@ class SvdcError(RuntimeError):
 class Shape(C.Structure):
     """Mirror of svdc_shape."""
     _fields_ = [("B", C.c_int32), ("N", C.c_int32), ("D", C.c_int32), ("k", C.c_int32),
-                ("ldf", C.c_int64), ("block_stride", C.c_int64), ("dtype", C.c_int32)]
+                ("ldf", C.c_int64), ("block_stride", C.c_int64), ("dtype", C.c_int32), ("precision", C.c_int32)]
 
 
 class FitParams(C.Structure):
@@ -96,7 +97,7 @@ def _need_gpu(*ts):
             raise RuntimeError("svdcache: tensors must live in GPU memory (no CPU path exists)")
 
 
-def make_shape(F: torch.Tensor, k: int) -> Shape:
+def make_shape(F: torch.Tensor, k: int, precision: int = SVDC_PRECISE) -> Shape:
     """Shape descriptor of a feature tensor [B, N, D] (or [N, D]) whose last dim is contiguous."""
     if F.dim() == 2:
         F = F.unsqueeze(0)
@@ -106,7 +107,7 @@ def make_shape(F: torch.Tensor, k: int) -> Shape:
         raise ValueError("F must be float32 or bfloat16")
     B, N, D = F.shape
     bs = F.stride(0) if B > 1 else max(F.stride(0), (N - 1) * F.stride(1) + D)
-    return Shape(B, N, D, k, F.stride(1), bs, _DTYPES[F.dtype])
+    return Shape(B, N, D, k, F.stride(1), bs, _DTYPES[F.dtype], precision)
 
 
 def _check(code: int, where: str):

@@ -19,6 +19,8 @@
 // Basis operands are pre-packed once per fitted basis (svdcache_pack_basis)
 // as bf16 "high" and "low" parts (V = hi + lo to ~16 significant bits) in
 // per-wavefront tiles of 64 lanes x 16 bytes.
+#include <algorithm>
+
 #include "svdc_device.h"
 #include "svdc_internal.h"
 
@@ -214,98 +216,142 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
 
 // ---------------------------------------------------------------------------
 // Full-compute step (Eq. 8-11) for bf16 F / R, one pass over F.
-// A workgroup of 4 waves holds a tile of 16*RT token rows x D channels in
-// registers: wave w keeps the channels [w D/4, (w+1) D/4) of all rows as packed
-// bf16 (RT * CH * 4 VGPRs, CH = D / 128 chunks of 32 channels).
-//   phase 1  C^T partial = V^T F^T over the wave's channels (MFMA), partials of
-//            the 4 waves summed through LDS in a fixed order
+// Persistent workgroups (one per compute unit) walk over row tiles; a workgroup
+// of 4 waves holds a tile of 16*RT token rows x D channels in registers: wave w
+// keeps the channels [w D/4, (w+1) D/4) of all rows as packed bf16
+// (RT * CH * 4 VGPRs, CH = D / 128 chunks of 32 channels).
+//   phase 1  C^T partial = V^T F^T over the wave's channels (MFMA); the basis
+//            operands stream from L2 through a ring of A chunks so that their
+//            latency is covered; partials of the 4 waves are summed through LDS
+//            in a fixed order
 //   EMA      wave w updates S (and writes C) for row tile w, w+4, ...
 //   phase 2  R^T = F^T - V C^T per chunk: accumulator starts at F, A operand
-//            is the negated basis, B operand is C (bf16 high + low parts)
+//            is the negated basis, B operand is C (bf16 high [+ low] parts)
+//   then     the next tile's rows are requested in one burst, so the loads are
+//            in flight while nothing else of this wave waits behind them
+// S1 / S2: use the low parts of the basis (and of C) in phase 1 / phase 2.
+// F and R may alias: a tile is completely in registers before it is overwritten.
 // ---------------------------------------------------------------------------
-template <int CH, int RT, int KT2, bool SPLIT>
+template <int CH, int RT, int KT2, bool S1, bool S2, int A>
 __global__ __launch_bounds__(256) void full_step_mfma_kernel(const bf16_t* F, const uint16_t* __restrict__ P,
                                                              bf16_t* R, float* S, float* C, int N, int k,
                                                              int64_t ldf, int64_t bstride, float alpha, int init,
                                                              int tiles_per_block, int total) {
   constexpr int KP = KT2 * 32, KT = KT2 * 2, D = CH * 128;
+  static_assert(CH % A == 0, "the operand ring must divide the chunk count");
   __shared__ f32x4 part[kWavesPerGroup][KT][RT][64];
-  int b, tile;
-  if (!xcd_tile(tiles_per_block, total, &b, &tile)) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
   const int64_t per = (int64_t)D * KP;
-  const u32x4* P1hi = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per);
-  const u32x4* P1lo = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + per);
-  const u32x4* P2hi = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 2 * per);
-  const u32x4* P2lo = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 3 * per);
-  const int row0 = tile * 16 * RT;
   const int cg0 = wave * CH;
-  const bf16_t* fbase = F + (int64_t)b * bstride;
-  bf16_t* obase = R + (int64_t)b * bstride;
+  int v = blockIdx.x;
+  if (v >= total) return;
 
   // the wave's slab of the tile: 16 bytes per lane per (row tile, chunk)
   u32x4 f[RT][CH];
-#pragma unroll
-  for (int c = 0; c < CH; ++c)
+  auto load_f_chunk = [&](int vv, int c) {
+    const int b = vv / tiles_per_block, tile = vv % tiles_per_block;
+    const bf16_t* fbase = F + (int64_t)b * bstride + 32 * (cg0 + c) + 8 * g;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const int row = min(row0 + 16 * rt + r, N - 1);
-      f[rt][c] = *reinterpret_cast<const u32x4*>(fbase + (int64_t)row * ldf + 32 * (cg0 + c) + 8 * g);
+      const int row = min(tile * 16 * RT + 16 * rt + r, N - 1);
+      f[rt][c] = *reinterpret_cast<const u32x4*>(fbase + (int64_t)row * ldf);
+    }
+  };
+#pragma unroll
+  for (int c = 0; c < CH; ++c) load_f_chunk(v, c);
+
+  for (; v < total; v += gridDim.x) {
+    const int b = v / tiles_per_block, tile = v % tiles_per_block;
+    const u32x4* P1hi = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per) + lane;
+    const u32x4* P1lo = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + per) + lane;
+    const u32x4* P2hi = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 2 * per) + lane;
+    const u32x4* P2lo = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 3 * per) + lane;
+    const int row0 = tile * 16 * RT;
+    bf16_t* obase = R + (int64_t)b * bstride + 8 * g;
+
+    // ---- phase 1: acc[jt][rt] = C^T[j = 16 jt + 4 g + i][row = 16 rt + r] over this wave's channels
+    u32x4 v1h[A][KT], v1l[A][KT];
+#pragma unroll
+    for (int a = 0; a < A; ++a)
+#pragma unroll
+      for (int jt = 0; jt < KT; ++jt) {
+        const int64_t ti = (int64_t)(cg0 + a) * KT + jt;
+        v1h[a][jt] = P1hi[ti * 64];
+        if (S1) v1l[a][jt] = P1lo[ti * 64];
+      }
+    f32x4 acc[KT][RT];
+#pragma unroll
+    for (int jt = 0; jt < KT; ++jt)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) acc[jt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int a = c % A;
+#pragma unroll
+      for (int jt = 0; jt < KT; ++jt)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          acc[jt][rt] = mfma16(v1h[a][jt], f[rt][c], acc[jt][rt]);
+          if (S1) acc[jt][rt] = mfma16(v1l[a][jt], f[rt][c], acc[jt][rt]);
+        }
+      if (c + A < CH) {
+#pragma unroll
+        for (int jt = 0; jt < KT; ++jt) {
+          const int64_t ti = (int64_t)(cg0 + c + A) * KT + jt;
+          v1h[a][jt] = P1hi[ti * 64];
+          if (S1) v1l[a][jt] = P1lo[ti * 64];
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
 
-  // phase 1: acc[jt][rt] = C^T[j = 16 jt + 4 g + i][row = 16 rt + r] restricted to this wave's channels
-  f32x4 acc[KT][RT];
+    // the first reconstruction operands are requested before the reduction so they arrive during it
+    u32x4 v2h[A][2][KT2], v2l[A][2][KT2];
 #pragma unroll
-  for (int jt = 0; jt < KT; ++jt)
+    for (int a = 0; a < A; ++a)
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) acc[jt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-  for (int c = 0; c < CH; ++c) {
+        for (int kt = 0; kt < KT2; ++kt) {
+          const int64_t ti = ((int64_t)(cg0 + a) * 2 + t) * KT2 + kt;
+          v2h[a][t][kt] = P2hi[ti * 64];
+          if (S2) v2l[a][t][kt] = P2lo[ti * 64];
+        }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // sum the four partial products through LDS, same order in every wave
 #pragma unroll
-    for (int jt = 0; jt < KT; ++jt) {
-      const int64_t ti = (int64_t)(cg0 + c) * KT + jt;
-      const u32x4 vh = P1hi[ti * 64 + lane];
-      u32x4 vl;
-      if (SPLIT) vl = P1lo[ti * 64 + lane];
+    for (int jt = 0; jt < KT; ++jt)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) part[wave][jt][rt][lane] = acc[jt][rt];
+    __syncthreads();
+#pragma unroll
+    for (int jt = 0; jt < KT; ++jt)
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        acc[jt][rt] = mfma16(vh, f[rt][c], acc[jt][rt]);
-        if (SPLIT) acc[jt][rt] = mfma16(vl, f[rt][c], acc[jt][rt]);
+        f32x4 s = part[0][jt][rt][lane];
+#pragma unroll
+        for (int w = 1; w < kWavesPerGroup; ++w) {
+          const f32x4 p = part[w][jt][rt][lane];
+          s[0] += p[0]; s[1] += p[1]; s[2] += p[2]; s[3] += p[3];
+        }
+        acc[jt][rt] = s;
       }
-    }
-  }
+    __syncthreads();   // the next tile reuses `part`
 
-  // sum the four partial products through LDS, same order in every wave
-#pragma unroll
-  for (int jt = 0; jt < KT; ++jt)
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) part[wave][jt][rt][lane] = acc[jt][rt];
-  __syncthreads();
-#pragma unroll
-  for (int jt = 0; jt < KT; ++jt)
+    // EMA update (Eq. 11, alpha = 1 - beta) and coefficient output, one wave per row tile
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      f32x4 s = part[0][jt][rt][lane];
+      if ((rt % kWavesPerGroup) != wave) continue;
+      const int row = row0 + 16 * rt + r;
+      if (row >= N) continue;
+      const int64_t srow = ((int64_t)b * N + row) * k;
 #pragma unroll
-      for (int w = 1; w < kWavesPerGroup; ++w) {
-        const f32x4 p = part[w][jt][rt][lane];
-        s[0] += p[0]; s[1] += p[1]; s[2] += p[2]; s[3] += p[3];
-      }
-      acc[jt][rt] = s;
-    }
-
-  // EMA update (Eq. 11, alpha = 1 - beta) and coefficient output, one wave per row tile
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    if ((rt % kWavesPerGroup) != wave) continue;
-    const int row = row0 + 16 * rt + r;
-    if (row >= N) continue;
-    const int64_t srow = ((int64_t)b * N + row) * k;
-#pragma unroll
-    for (int jt = 0; jt < KT; ++jt) {
-      const int j = 16 * jt + 4 * g;
-      const f32x4 c4 = acc[jt][rt];
-      if (j + 3 < k) {
+      for (int jt = 0; jt < KT; ++jt) {
+        const int j = 16 * jt + 4 * g;
+        if (j >= k) continue;   // k is a multiple of 4: a group of four is all inside or all outside
+        const f32x4 c4 = acc[jt][rt];
         f32x4 s4 = c4;
         if (!init) {
           const f32x4 old = *reinterpret_cast<const f32x4*>(S + srow + j);
@@ -314,69 +360,77 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const bf16_t* F, co
         }
         *reinterpret_cast<f32x4*>(S + srow + j) = s4;
         if (C) *reinterpret_cast<f32x4*>(C + srow + j) = c4;
-      } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (j + i < k) {
-            const float s1 = init ? c4[i] : (1.f - alpha) * S[srow + j + i] + alpha * c4[i];
-            S[srow + j + i] = s1;
-            if (C) C[srow + j + i] = c4[i];
-          }
       }
     }
-  }
 
-  // coefficient operand of the reconstruction: kk = 8 g + 4 t + i  <->  j = 32 kt + 16 t + 4 g + i
-  u32x4 chi[RT][KT2], clo[RT][KT2];
+    // coefficient operand of the reconstruction: kk = 8 g + 4 t + i  <->  j = 32 kt + 16 t + 4 g + i
+    u32x4 chi[RT][KT2], clo[RT][KT2];
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-    for (int kt = 0; kt < KT2; ++kt) {
-      float c8[8];
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) c8[4 * t + i] = acc[2 * kt + t][rt][i];
-      split_operand(c8, &chi[rt][kt], &clo[rt][kt]);
-    }
-
-  // phase 2: residual, chunk by chunk
-#pragma unroll
-  for (int c = 0; c < CH; ++c) {
-    u32x4 a_hi[2][KT2], a_lo[2][KT2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
       for (int kt = 0; kt < KT2; ++kt) {
-        const int64_t ti = ((int64_t)(cg0 + c) * 2 + t) * KT2 + kt;
-        a_hi[t][kt] = P2hi[ti * 64 + lane];
-        if (SPLIT) a_lo[t][kt] = P2lo[ti * 64 + lane];
+        float c8[8];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) c8[4 * t + i] = acc[2 * kt + t][rt][i];
+        split_operand(c8, &chi[rt][kt], &clo[rt][kt]);
       }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- phase 2: residual, chunk by chunk
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      u32x4 out;
+    for (int c = 0; c < CH; ++c) {
+      const int a = c % A;
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        f32x4 a = {bf16_lo(f[rt][c][2 * t]), bf16_hi(f[rt][c][2 * t]), bf16_lo(f[rt][c][2 * t + 1]),
-                   bf16_hi(f[rt][c][2 * t + 1])};
+      for (int rt = 0; rt < RT; ++rt) {
+        u32x4 out;
 #pragma unroll
-        for (int kt = 0; kt < KT2; ++kt) {
-          a = mfma16(a_hi[t][kt], chi[rt][kt], a);
-          if (SPLIT) {
-            a = mfma16(a_hi[t][kt], clo[rt][kt], a);
-            a = mfma16(a_lo[t][kt], chi[rt][kt], a);
+        for (int t = 0; t < 2; ++t) {
+          f32x4 x = {bf16_lo(f[rt][c][2 * t]), bf16_hi(f[rt][c][2 * t]), bf16_lo(f[rt][c][2 * t + 1]),
+                     bf16_hi(f[rt][c][2 * t + 1])};
+#pragma unroll
+          for (int kt = 0; kt < KT2; ++kt) {
+            x = mfma16(v2h[a][t][kt], chi[rt][kt], x);
+            if (S2) {
+              x = mfma16(v2h[a][t][kt], clo[rt][kt], x);
+              x = mfma16(v2l[a][t][kt], chi[rt][kt], x);
+            }
           }
+          out[2 * t] = pack_bf16(x[0], x[1]);
+          out[2 * t + 1] = pack_bf16(x[2], x[3]);
         }
-        out[2 * t] = pack_bf16(a[0], a[1]);
-        out[2 * t + 1] = pack_bf16(a[2], a[3]);
+        const int row = row0 + 16 * rt + r;
+        if (row < N) *reinterpret_cast<u32x4*>(obase + (int64_t)row * ldf + 32 * (cg0 + c)) = out;
       }
-      const int row = row0 + 16 * rt + r;
-      if (row < N) *reinterpret_cast<u32x4*>(obase + (int64_t)row * ldf + 32 * (cg0 + c) + 8 * g) = out;
+      if (c + A < CH) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int kt = 0; kt < KT2; ++kt) {
+            const int64_t ti = ((int64_t)(cg0 + c + A) * 2 + t) * KT2 + kt;
+            v2h[a][t][kt] = P2hi[ti * 64];
+            if (S2) v2l[a][t][kt] = P2lo[ti * 64];
+          }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // request the next tile
+    const int vn = v + (int)gridDim.x;
+    if (vn < total) {
+#pragma unroll
+      for (int c = 0; c < CH; ++c) load_f_chunk(vn, c);
     }
   }
 }
 
-constexpr bool kSplit = true;  // bf16 high + low operand parts (fp32-level products)
+int num_compute_units() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+  return n;
+}
 
 }  // namespace
 
@@ -401,7 +455,7 @@ int32_t launch_pack_basis(const svdc_shape& s, const float* V, void* packed, hip
 
 namespace {
 
-template <int NCW, int KT2, int PD>
+template <int NCW, int KT2, bool SPLIT, int PD>
 int32_t forecast_launch(const svdc_shape& s, const float* S, const void* packed, const void* R, void* Fhat,
                         hipStream_t st) {
   const int NS = s.D / (128 * NCW);
@@ -409,59 +463,65 @@ int32_t forecast_launch(const svdc_shape& s, const float* S, const void* packed,
   const int gpb = (ntile + kTilesPerGroup - 1) / kTilesPerGroup;
   const int64_t grid = (int64_t)NS * gpb * s.B;
   if (grid > 0x7fffffff) return SVDC_E_SHAPE;
-  forecast_mfma_kernel<NCW, KT2, kSplit, PD><<<(unsigned)grid, 256, 0, st>>>(
+  forecast_mfma_kernel<NCW, KT2, SPLIT, PD><<<(unsigned)grid, 256, 0, st>>>(
       S, (const uint16_t*)packed, (const bf16_t*)R, (bf16_t*)Fhat, s.N, s.D, s.k, s.ldf, s.block_stride, NS, gpb);
   return launch_status();
 }
 
 // widest slab per wave (NCW chunks) that divides D / 128 and keeps the basis operands in registers
-template <int KT2, int PD>
+template <int KT2, bool SPLIT, int PD>
 int32_t forecast_by_width(const svdc_shape& s, const float* S, const void* packed, const void* R, void* Fhat,
                           hipStream_t st) {
-  constexpr int kMax = KT2 == 1 ? 12 : (KT2 == 2 ? 6 : 4);
+  constexpr int kMax = (SPLIT ? 12 : 24) / KT2 >= 12 ? 12 : ((SPLIT ? 12 : 24) / KT2 >= 6 ? 6 : 4);
   const int m = s.D / 128;
   if constexpr (kMax >= 12) {
-    if (m % 12 == 0) return forecast_launch<12, KT2, PD>(s, S, packed, R, Fhat, st);
+    if (m % 12 == 0) return forecast_launch<12, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
   }
   if constexpr (kMax >= 6) {
-    if (m % 6 == 0) return forecast_launch<6, KT2, PD>(s, S, packed, R, Fhat, st);
+    if (m % 6 == 0) return forecast_launch<6, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
   }
-  if (m % 4 == 0) return forecast_launch<4, KT2, PD>(s, S, packed, R, Fhat, st);
-  if (m % 3 == 0) return forecast_launch<3, KT2, PD>(s, S, packed, R, Fhat, st);
-  if (m % 2 == 0) return forecast_launch<2, KT2, PD>(s, S, packed, R, Fhat, st);
-  return forecast_launch<1, KT2, PD>(s, S, packed, R, Fhat, st);
+  if (m % 4 == 0) return forecast_launch<4, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+  if (m % 3 == 0) return forecast_launch<3, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+  if (m % 2 == 0) return forecast_launch<2, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+  return forecast_launch<1, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
 }
 
-template <int CH, int RT, int KT2>
+template <int CH, int RT, int KT2, bool SPLIT, int A>
 int32_t full_step_launch(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
                          float alpha, int init, hipStream_t st) {
   const int tiles = (s.N + 16 * RT - 1) / (16 * RT);
-  const int total = tiles * s.B;
-  const int grid = (total + 7) / 8 * 8;
-  full_step_mfma_kernel<CH, RT, KT2, kSplit><<<grid, 256, 0, st>>>((const bf16_t*)F, (const uint16_t*)packed,
-                                                                   (bf16_t*)R, S, C, s.N, s.k, s.ldf,
-                                                                   s.block_stride, alpha, init, tiles, total);
+  const int64_t total = (int64_t)tiles * s.B;
+  if (total > 0x7fffffff) return SVDC_E_SHAPE;
+  const int grid = (int)std::min<int64_t>(total, num_compute_units());
+  full_step_mfma_kernel<CH, RT, KT2, SPLIT, SPLIT, A><<<grid, 256, 0, st>>>(
+      (const bf16_t*)F, (const uint16_t*)packed, (bf16_t*)R, S, C, s.N, s.k, s.ldf, s.block_stride, alpha, init,
+      tiles, (int)total);
   return launch_status();
 }
 
-template <int CH>
+template <int CH, bool SPLIT>
 int32_t full_step_by_rank(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
                           float alpha, int init, hipStream_t st) {
-  constexpr int RT1 = CH <= 8 ? 4 : 3, RT2 = CH <= 8 ? 4 : 2, RT4 = CH <= 8 ? 2 : 1;
+  // rows per tile (16 RT) and operand ring depth A per padded rank; wide tiles only when they fit in registers
+  constexpr bool small = CH <= 8;
   const int kp = padded_rank(s.k);
-  if (kp == 32) return full_step_launch<CH, RT1, 1>(s, F, packed, R, S, C, alpha, init, st);
-  if (kp == 64) return full_step_launch<CH, RT2, 2>(s, F, packed, R, S, C, alpha, init, st);
-  return full_step_launch<CH, RT4, 4>(s, F, packed, R, S, C, alpha, init, st);
+  if (kp == 32) return full_step_launch<CH, small ? 4 : 2, 1, SPLIT, small ? 2 : 8>(s, F, packed, R, S, C, alpha, init, st);
+  if (kp == 64) return full_step_launch<CH, small ? 4 : (SPLIT ? 1 : 2), 2, SPLIT, small ? 2 : 4>(s, F, packed, R, S, C, alpha, init, st);
+  return full_step_launch<CH, small ? 2 : 1, 4, SPLIT, 2>(s, F, packed, R, S, C, alpha, init, st);
 }
 
 }  // namespace
 
 int32_t launch_full_step_mfma(const svdc_shape& s, const void* F, const void* packed, void* R, float* S,
                               float* C, float alpha, int init, hipStream_t st) {
+  const bool split = s.precision == SVDC_PRECISE;
   switch (s.D / 128) {
-    case 2: return full_step_by_rank<2>(s, F, packed, R, S, C, alpha, init, st);
-    case 4: return full_step_by_rank<4>(s, F, packed, R, S, C, alpha, init, st);
-    case 24: return full_step_by_rank<24>(s, F, packed, R, S, C, alpha, init, st);
+    case 2: return split ? full_step_by_rank<2, true>(s, F, packed, R, S, C, alpha, init, st)
+                         : full_step_by_rank<2, false>(s, F, packed, R, S, C, alpha, init, st);
+    case 4: return split ? full_step_by_rank<4, true>(s, F, packed, R, S, C, alpha, init, st)
+                         : full_step_by_rank<4, false>(s, F, packed, R, S, C, alpha, init, st);
+    case 24: return split ? full_step_by_rank<24, true>(s, F, packed, R, S, C, alpha, init, st)
+                          : full_step_by_rank<24, false>(s, F, packed, R, S, C, alpha, init, st);
     default: return SVDC_E_SHAPE;
   }
 }
@@ -469,9 +529,14 @@ int32_t launch_full_step_mfma(const svdc_shape& s, const void* F, const void* pa
 int32_t launch_forecast_mfma(const svdc_shape& s, const float* S, const void* packed, const void* R,
                              void* Fhat, hipStream_t st) {
   const int kp = padded_rank(s.k);
-  if (kp == 32) return forecast_by_width<1, 1>(s, S, packed, R, Fhat, st);
-  if (kp == 64) return forecast_by_width<2, 2>(s, S, packed, R, Fhat, st);
-  return forecast_by_width<4, 2>(s, S, packed, R, Fhat, st);
+  if (s.precision == SVDC_PRECISE) {
+    if (kp == 32) return forecast_by_width<1, true, 1>(s, S, packed, R, Fhat, st);
+    if (kp == 64) return forecast_by_width<2, true, 2>(s, S, packed, R, Fhat, st);
+    return forecast_by_width<4, true, 2>(s, S, packed, R, Fhat, st);
+  }
+  if (kp == 32) return forecast_by_width<1, false, 2>(s, S, packed, R, Fhat, st);
+  if (kp == 64) return forecast_by_width<2, false, 2>(s, S, packed, R, Fhat, st);
+  return forecast_by_width<4, false, 2>(s, S, packed, R, Fhat, st);
 }
 
 }  // namespace svdc

@@ -12,6 +12,7 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 int32_t check_shape(const svdc_shape* s) {
   if (!s) return SVDC_E_NULL;
   if (s->dtype != SVDC_F32 && s->dtype != SVDC_BF16) return SVDC_E_DTYPE;
+  if (s->precision != SVDC_PRECISE && s->precision != SVDC_FAST) return SVDC_E_PARAM;
   if (s->B < 1 || s->B > 65535 || s->N < 1 || s->D < 1 || s->k < 1) return SVDC_E_SHAPE;
   if (s->k > s->N || s->k > s->D || s->k > 1024) return SVDC_E_SHAPE;
   if (s->ldf < s->D) return SVDC_E_SHAPE;

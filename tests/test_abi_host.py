@@ -38,13 +38,13 @@ def test_version_and_strerror(lib):
 
 
 def _shape(**kw):
-    d = dict(B=1, N=64, D=64, k=8, ldf=64, block_stride=64 * 64, dtype=0)
+    d = dict(B=1, N=64, D=64, k=8, ldf=64, block_stride=64 * 64, dtype=0, precision=0)
     d.update(kw)
     return Shape(**d)
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(dtype=7), -3), (dict(B=0), -2), (dict(k=0), -2), (dict(k=65), -2), (dict(N=4, k=8), -2),
+    (dict(dtype=7), -3), (dict(precision=2), -5), (dict(B=0), -2), (dict(k=0), -2), (dict(k=65), -2), (dict(N=4, k=8), -2),
     (dict(ldf=32), -2), (dict(block_stride=100), -2), (dict(D=66, ldf=66, block_stride=66 * 64), -4),
     (dict(dtype=1, D=68, ldf=68, block_stride=68 * 64), -4),
 ])

@@ -312,3 +312,30 @@ def test_fit_basis_flux_block_full_size():
     V, sigma, fro2 = pkg.fit_basis(F.to(DEV), wl.k)
     torch.cuda.synchronize()
     _fit_checks(F[0], V[0], sigma[0], fro2[0], wl.k, "bf16")
+
+
+@pytest.mark.parametrize("B,N,D,k", [(2, 200, 256, 32), (1, 150, 3072, 32), (1, 100, 3072, 64), (1, 140, 512, 128)])
+def test_mfma_fast_precision_mode_is_within_the_bf16_tolerance(B, N, D, k):
+    """SVDC_FAST: single bf16 operands.  Same parity bar (2e-2 for bf16 storage), larger error than
+    the default mode."""
+    F, V, S0 = _lowrank_problem(B, N, D, k, seed=N + k)
+    Fd, Vd = F.to(DEV), V.to(DEV)
+    errs = {}
+    for mode in (pkg.SVDC_PRECISE, pkg.SVDC_FAST):
+        shape = pkg.make_shape(Fd, k, precision=mode)
+        pk = pkg.pack_basis(shape, Vd)
+        R, S, Cc, Fh = torch.empty_like(Fd), S0.clone().to(DEV), torch.empty(B, N, k, device=DEV), torch.empty_like(Fd)
+        pkg.svdcache_full_step(shape, Fd, Vd, pk, R, S, Cc, 0.5, False)
+        pkg.svdcache_forecast(shape, S, Vd, pk, R, Fh)
+        torch.cuda.synchronize()
+        worst = 0.0
+        for b in range(B):
+            Rr, Sr, Cr = ref_full_step(to_np(F[b]), to_np(V[b]), to_np(S0[b]), 0.5, False, "bf16")
+            assert_close(to_np(R[b]), Rr, "bf16", f"R[{b}] mode {mode}", floor_of=to_np(F[b]))
+            assert_close(to_np(S[b]), Sr, "bf16", f"S[{b}] mode {mode}")
+            assert_close(to_np(Cc[b]), Cr, "bf16", f"C[{b}] mode {mode}")
+            assert_close(to_np(Fh[b]), ref_forecast(to_np(S[b]), to_np(V[b]), to_np(R[b]), "bf16"), "bf16",
+                         f"Fhat[{b}] mode {mode}")
+            worst = max(worst, rel_err(to_np(R[b]), Rr))
+        errs[mode] = worst
+    assert errs[pkg.SVDC_PRECISE] <= 3e-3 and errs[pkg.SVDC_FAST] <= 1.5e-2
