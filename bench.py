@@ -26,9 +26,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TF = 2500.0     # dense bf16, published
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by a
-# copy kernel of known size (see profiles/); None until measured for the kernel that dominates.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command (workload flux57,
+# k = 32, SVDC_PRECISE), each scaled by what the same counter reads for a plain 1 GiB device copy
+# (profiles/flux57_k32_hbm_traffic.md).  Only valid for that configuration.
+MEASURED_TRAFFIC = {
+    ("flux57", 32, False, "forecast_mfma_kernel"): 3411313312,
+    ("flux57", 32, False, "full_step_mfma_kernel"): 3911251403,
+}
 
 
 def algorithmic_bytes(wl, q_passes):
@@ -49,6 +53,9 @@ def main():
     ap.add_argument("--k", type=int, default=0, help="override the rank")
     ap.add_argument("--blocks", type=int, default=0, help="override the number of blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fast", action="store_true", help="SVDC_FAST arithmetic (single bf16 operands)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); nothing here shards across GPUs",
@@ -90,7 +97,7 @@ def main():
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 
-    shape = pkg.make_shape(feats[0], k)
+    shape = pkg.make_shape(feats[0], k, precision=pkg.SVDC_FAST if args.fast else pkg.SVDC_PRECISE)
     V = torch.empty(B, D, k, device=dev)
     sigma = torch.empty(B, k, device=dev)
     fro2 = torch.empty(B, device=dev)
@@ -132,6 +139,12 @@ def main():
                 if record:
                     times["fore"].append((a, bb))
 
+    if args.calibrate_copy:
+        ca = torch.empty(1 << 30, device=dev, dtype=torch.uint8)
+        cb = torch.empty_like(ca)
+        cb.copy_(ca)
+        torch.cuda.synchronize()
+        del ca, cb
     for _ in range(args.warmup):
         trajectory(False)
     torch.cuda.synchronize()
@@ -172,7 +185,7 @@ def main():
         dom_kernel = dom_kernel.replace("mfma", "general")
     ach = kernels[dom]["GBps"]
     roofline = {"kernel": dom_kernel, "entry_point": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(dom_kernel),
+                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((wl.name, k, bool(args.fast), dom_kernel)) if B == WORKLOADS[wl.name].B else None,
                 "avg_launch_ms": kernels[dom]["avg_ms"], "algorithmic_bytes_per_launch": kernels[dom]["bytes"]}
 
     # ---- CPU oracle on a bounded sample ----------------------------------------------------------
@@ -184,18 +197,22 @@ def main():
             threads = max(i["num_threads"] for i in threadpoolctl.threadpool_info()) if threadpoolctl.threadpool_info() else 1
         except Exception:
             threads = os.cpu_count() or 1
-        F0 = feats[0][0].to("cpu").double().numpy()
         store = wl.dtype
-        t0 = time.perf_counter()
-        Vr, _, _ = ref_fit_basis(F0, k)
-        Rr, Sr, _ = ref_full_step(F0, Vr, None, wl.alpha, True, store)
-        ref_forecast(Sr, Vr, Rr, store)
-        cpu_s = time.perf_counter() - t0
+        cpu_s, nb = 0.0, 0
+        while nb < B and cpu_s < 10.0:       # bounded sample: whole blocks until >= 10 s of CPU work
+            F0 = feats[0][nb].to("cpu").double().numpy()
+            t0 = time.perf_counter()
+            Vr, _, _ = ref_fit_basis(F0, k)
+            Rr, Sr, _ = ref_full_step(F0, Vr, None, wl.alpha, True, store)
+            ref_forecast(Sr, Vr, Rr, store)
+            cpu_s += time.perf_counter() - t0
+            nb += 1
         one_block = (by_fit + by_full + by_fore) / B
-        cpu = {"value": one_block / cpu_s / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+        cpu = {"value": nb * one_block / cpu_s / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
                "seconds": cpu_s,
-               "sample": f"1 of {B} blocks ({N}x{D} {wl.dtype}, k={k}): one exact basis fit + one full step + one "
-                         f"cached step, numpy float64; bytes counted as for the GPU path"}
+               "sample": f"{nb} of {B} blocks ({N}x{D} {wl.dtype}, k={k}), per block one exact basis fit + one full "
+                         f"step + one cached step, numpy float64; bytes counted as for one GPU fit + full step + "
+                         f"cached step of those blocks"}
 
     out = {
         "metric": "SVD-Cache hot path (basis fit + full steps + cached steps) algorithmic HBM GB/s",
