@@ -339,3 +339,77 @@ def test_mfma_fast_precision_mode_is_within_the_bf16_tolerance(B, N, D, k):
             worst = max(worst, rel_err(to_np(R[b]), Rr))
         errs[mode] = worst
     assert errs[pkg.SVDC_PRECISE] <= 3e-3 and errs[pkg.SVDC_FAST] <= 1.5e-2
+
+
+# ---------------------------------------------------------------------------------------------
+# full-size launches (the configurations bench.py times), checked on sampled rows
+# ---------------------------------------------------------------------------------------------
+
+def _sampled_row_parity(wl, B, blocks_to_check, n_rows, precision=0):
+    """Run fit + pack + two full steps + one cached step at full size on GPU-generated features and
+    recompute sampled token rows with the oracle (rows are independent given V and S)."""
+    feats = []
+    for t in (0, wl.interval):
+        Ft = torch.empty(B, wl.N, wl.D, device=DEV, dtype=torch.bfloat16)
+        for b in range(B):
+            Ft[b] = FeatureStream(wl, b, device=DEV).at(t)
+        feats.append(Ft)
+    shape = pkg.make_shape(feats[0], wl.k, precision=precision)
+    assert pkg.svdcache_has_mfma_path(shape)
+    V, sigma, fro2 = pkg.fit_basis(feats[0], wl.k)
+    pk = pkg.pack_basis(shape, V)
+    R = torch.empty_like(feats[0])
+    S = torch.empty(B, wl.N, wl.k, device=DEV)
+    Cc = torch.empty_like(S)
+    Fh = torch.empty_like(R)
+    pkg.svdcache_full_step(shape, feats[0], V, pk, R, S, None, wl.alpha, True)
+    S0 = S.clone()
+    pkg.svdcache_full_step(shape, feats[1], V, pk, R, S, Cc, wl.alpha, False)
+    pkg.svdcache_forecast(shape, S, V, pk, R, Fh)
+    torch.cuda.synchronize()
+    assert torch.isfinite(R.float()).all() and torch.isfinite(Fh.float()).all() and torch.isfinite(S).all()
+    g = torch.Generator().manual_seed(wl.config_id)
+    for b in blocks_to_check:
+        rows = torch.cat([torch.tensor([0, 1, 15, 16, 31, 32, wl.N - 17, wl.N - 16, wl.N - 1]),
+                          torch.randint(0, wl.N, (n_rows,), generator=g)]).unique()
+        Vb = to_np(V[b])
+        assert np.abs(Vb.T @ Vb - np.eye(wl.k)).max() <= 1e-5
+        F0r, F1r = to_np(feats[0][b][rows]), to_np(feats[1][b][rows])
+        _, S0r, _ = ref_full_step(F0r, Vb, None, wl.alpha, True, "bf16")
+        coef_store = "f32" if precision == 0 else "bf16"   # SVDC_FAST rounds V to bf16 in the projection
+        assert_close(to_np(S0[b][rows]), S0r, coef_store, f"S after init, block {b}")
+        Rr, S1r, C1r = ref_full_step(F1r, Vb, to_np(S0[b][rows]), wl.alpha, False, "bf16")
+        assert_close(to_np(R[b][rows]), Rr, "bf16", f"R block {b}", floor_of=F1r)
+        assert_close(to_np(S[b][rows]), S1r, coef_store, f"S block {b}")
+        assert_close(to_np(Cc[b][rows]), C1r, coef_store, f"C block {b}")
+        Fr = ref_forecast(to_np(S[b][rows]), Vb, to_np(R[b][rows]), "bf16")
+        assert_close(to_np(Fh[b][rows]), Fr, "bf16", f"Fhat block {b}")
+    return sigma, fro2, feats
+
+
+def test_flux57_full_size_launch_sampled_rows():
+    """Config 3 as bench.py launches it: 57 blocks x 4608 x 3072 bf16, k = 32, one launch per kernel."""
+    wl = WORKLOADS["flux57"]
+    sigma, fro2, feats = _sampled_row_parity(wl, wl.B, blocks_to_check=[0, 28, 56], n_rows=96)
+    # the fitted singular values of one block against the exact ones
+    _, sr, fr = ref_fit_basis(to_np(feats[0][56]), wl.k)
+    assert np.abs(to_np(sigma[56]) / sr - 1).max() <= TOL["bf16"]
+    assert abs(float(fro2[56]) / fr - 1) <= 1e-5
+
+
+def test_flux57_full_size_launch_fast_mode():
+    wl = WORKLOADS["flux57"].with_(B=8)
+    _sampled_row_parity(wl, wl.B, blocks_to_check=[0, 7], n_rows=64, precision=pkg.SVDC_FAST)
+
+
+def test_hunyuan_shape_two_blocks_sampled_rows():
+    """Config 4 shape (119056 tokens x 3072, k = 64) on 2 of its 60 blocks; rows sampled."""
+    wl = WORKLOADS["hyv60"]
+    _sampled_row_parity(wl, 2, blocks_to_check=[0, 1], n_rows=96)
+
+
+def test_rank_sweep_at_stacked_prompt_shape():
+    """Config 5 shape: 4 prompts stacked along N with one shared basis, k in {16, 64, 128}."""
+    for k in (16, 64, 128):
+        wl = WORKLOADS["sweep"].with_(k=k)
+        _sampled_row_parity(wl, 1, blocks_to_check=[0], n_rows=64)
