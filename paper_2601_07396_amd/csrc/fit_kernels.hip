@@ -326,8 +326,12 @@ __global__ __launch_bounds__(256) void chol_inv_reg_kernel(double* G, double* Mi
     }
     __syncthreads();
     const double piv2 = fmax(col[c], 1e-300);
-    const double piv = sqrt(piv2);
-    const double rs = 1.0 / piv, inv = rs * rs;
+    // 1 / sqrt(piv2): hardware estimate refined by two Newton steps (an exact sqrt and a division per
+    // column would dominate this kernel)
+    double rs = __builtin_amdgcn_rsq(piv2);
+    rs = rs * (1.5 - 0.5 * piv2 * rs * rs);
+    rs = rs * (1.5 - 0.5 * piv2 * rs * rs);
+    const double piv = piv2 * rs, inv = rs * rs;
     double ci[BS], cj[BS];
 #pragma unroll
     for (int ii = 0; ii < BS; ++ii) ci[ii] = col[BS * ti + ii];
@@ -435,9 +439,10 @@ __global__ __launch_bounds__(256) void rows_times_small_tiled_kernel(const float
 //   Wout  out  [l x l] row-major, column r = right singular vector of rank r
 //   sigma out  [k] leading singular values
 // ---------------------------------------------------------------------------
+template <bool a_in_lds, bool w_in_lds>   // compile-time so that LDS accesses are ds_* instructions, not flat ones
 __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ Lfac, double* Wout, float* sigma,
-                                                     double* gA, double* gW, int l, int k, int a_in_lds,
-                                                     int w_in_lds, const double* fro_acc, float* fro2) {
+                                                     double* gA, double* gW, int l, int k,
+                                                     const double* fro_acc, float* fro2) {
   extern __shared__ double dyn_lds[];
   __shared__ double nrm[256];
   __shared__ int s_rot;
@@ -483,10 +488,23 @@ __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ 
           be += __shfl_xor(be, o, kWave);
           ga += __shfl_xor(ga, o, kWave);
         }
-        if (fabs(ga) > 1e-13 * sqrt(al * be) && ga != 0.0) {
-          const double zeta = (be - al) / (2.0 * ga);
-          const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-          const double cs = 1.0 / sqrt(1.0 + tt * tt), sn = cs * tt;
+        // rotate when the columns are not yet orthogonal to 1e-13 (compared in squares, no sqrt)
+        if (ga * ga > 1e-26 * al * be) {
+          // The rotation ANGLE only steers convergence, so tan(theta) is computed in float32; cos and sin
+          // are then formed in float64 so that the rotation is orthogonal to double round-off.
+          const double zd = (be - al) * 0.5 * __builtin_amdgcn_rcp(ga);     // approximate reciprocal is enough
+          double tt;
+          if (fabs(zd) < 1e15) {
+            const float zeta = (float)zd;
+            tt = (double)((zeta >= 0.f ? 1.f : -1.f) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta)));
+          } else {
+            tt = 0.5 * __builtin_amdgcn_rcp(zd);
+          }
+          const double n2 = 1.0 + tt * tt;
+          double cs = __builtin_amdgcn_rsq(n2);
+          cs = cs * (1.5 - 0.5 * n2 * cs * cs);
+          cs = cs * (1.5 - 0.5 * n2 * cs * cs);
+          const double sn = cs * tt;
           double* wp = W + (int64_t)p * la;
           double* wq = W + (int64_t)q * la;
           for (int r = gl; r < l; r += tp) {
@@ -726,9 +744,16 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   const int a_in_lds = mat <= kLdsBudget;
   const int w_in_lds = 2 * mat <= kLdsBudget;
   const size_t lds = (a_in_lds ? mat : 0) + (w_in_lds ? mat : 0);
-  if (set_dyn_lds((const void*)jacobi_kernel, lds) != SVDC_OK) return SVDC_E_HIP;
-  jacobi_kernel<<<B, 256, lds, st>>>(G, M, sigma, Wg, Wg + (int64_t)B * l * (l + 1), l, s.k, a_in_lds, w_in_lds, misc,
-                                     fro2);
+  double* gW = Wg + (int64_t)B * l * (l + 1);
+  if (a_in_lds && w_in_lds) {
+    if (set_dyn_lds((const void*)jacobi_kernel<true, true>, lds) != SVDC_OK) return SVDC_E_HIP;
+    jacobi_kernel<true, true><<<B, 256, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+  } else if (a_in_lds) {
+    if (set_dyn_lds((const void*)jacobi_kernel<true, false>, lds) != SVDC_OK) return SVDC_E_HIP;
+    jacobi_kernel<true, false><<<B, 256, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+  } else {
+    jacobi_kernel<false, false><<<B, 256, 0, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+  }
   if (rows_times_small(Q, M, V, B, s.D, l, s.k, l, st) != SVDC_OK) return SVDC_E_HIP;
   return launch_status();
 }

@@ -20,6 +20,7 @@
 // as bf16 "high" and "low" parts (V = hi + lo to ~16 significant bits) in
 // per-wavefront tiles of 64 lanes x 16 bytes.
 #include <algorithm>
+#include <cmath>
 
 #include "svdc_device.h"
 #include "svdc_internal.h"
@@ -33,6 +34,13 @@ constexpr int kWavesPerGroup = 4;
 __device__ __forceinline__ f32x4 mfma16(const u32x4& a, const u32x4& b, const f32x4& c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
                                                  0, 0, 0);
+}
+
+int num_compute_units() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+  return n;
 }
 
 // rank padded to 32, 64 or 128 (one reconstruction MFMA contracts 32 coefficients)
@@ -114,18 +122,18 @@ __device__ __forceinline__ void split_operand(const float (&c)[8], u32x4* hi, u3
 // consecutive 32-channel chunks in registers and streams 16-row tiles of R past
 // them, so the basis is read from L2 once per workgroup, not once per tile.
 // A workgroup of 4 waves covers 4*NCW chunks (a "slab" of 128*NCW channels) and
-// kTilesPerGroup row tiles; adjacent workgroup ids are adjacent slabs of the same
+// tiles_per_group row tiles; adjacent workgroup ids are adjacent slabs of the same
 // rows.  Per tile and chunk: two MFMAs per 32 coefficients whose accumulator
 // starts at R; the coefficient operand is -S (bf16 high + low parts), so the
 // MFMA computes Fhat^T = R^T + (-V)(-S)^T.  PD tiles are kept in flight.
 // ---------------------------------------------------------------------------
-constexpr int kTilesPerGroup = 8;
 
 template <int NCW, int KT2, bool SPLIT, int PD>
 __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restrict__ S,
                                                             const uint16_t* __restrict__ P, const bf16_t* R,
                                                             bf16_t* Fh, int N, int D, int k, int64_t ldf,
-                                                            int64_t bstride, int NS, int groups_per_block) {
+                                                            int64_t bstride, int NS, int groups_per_block,
+                                                            int tiles_per_group) {
   const int slab = blockIdx.x % NS;
   const int rgb = blockIdx.x / NS;
   const int b = rgb / groups_per_block, rg = rgb % groups_per_block;
@@ -138,8 +146,8 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
   const bf16_t* rbase = R + (int64_t)b * bstride + 32 * cg0 + 8 * g;
   bf16_t* obase = Fh + (int64_t)b * bstride + 32 * cg0 + 8 * g;
   const float* sbase = S + (int64_t)b * N * k;
-  const int tile0 = rg * kTilesPerGroup;
-  const int ntiles = min(kTilesPerGroup, (N + 15) / 16 - tile0);
+  const int tile0 = rg * tiles_per_group;
+  const int ntiles = min(tiles_per_group, (N + 15) / 16 - tile0);
 
   u32x4 rin[PD][NCW];
   f32x4 sraw[PD][KT2][2];
@@ -425,12 +433,6 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const bf16_t* F, co
   }
 }
 
-int num_compute_units() {
-  int dev = 0, n = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 256;
-  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
-  return n;
-}
 
 }  // namespace
 
@@ -460,11 +462,23 @@ int32_t forecast_launch(const svdc_shape& s, const float* S, const void* packed,
                         hipStream_t st) {
   const int NS = s.D / (128 * NCW);
   const int ntile = (s.N + 15) / 16;
-  const int gpb = (ntile + kTilesPerGroup - 1) / kTilesPerGroup;
+  // Row tiles per workgroup: 6..16, chosen so that the workgroups fill whole rounds of the machine
+  // (a grid of e.g. 16.03 x the number of compute units costs a 17th, nearly empty round).
+  const int cus = num_compute_units();
+  int tpg = 8;
+  double best = 0.0;
+  for (int cand = 16; cand >= 6; --cand) {
+    const int64_t w = (int64_t)NS * ((ntile + cand - 1) / cand) * s.B;
+    const double rounds = (double)w / cus;
+    const double eff = rounds / std::ceil(rounds) * ((double)ntile / (cand * ((ntile + cand - 1) / cand)));
+    if (eff > best + 1e-9) { best = eff; tpg = cand; }
+  }
+  const int gpb = (ntile + tpg - 1) / tpg;
   const int64_t grid = (int64_t)NS * gpb * s.B;
   if (grid > 0x7fffffff) return SVDC_E_SHAPE;
   forecast_mfma_kernel<NCW, KT2, SPLIT, PD><<<(unsigned)grid, 256, 0, st>>>(
-      S, (const uint16_t*)packed, (const bf16_t*)R, (bf16_t*)Fhat, s.N, s.D, s.k, s.ldf, s.block_stride, NS, gpb);
+      S, (const uint16_t*)packed, (const bf16_t*)R, (bf16_t*)Fhat, s.N, s.D, s.k, s.ldf, s.block_stride, NS, gpb,
+      tpg);
   return launch_status();
 }
 
