@@ -44,6 +44,54 @@ def algorithmic_bytes(wl, q_passes):
     return full, fore, fit
 
 
+def sweep(args):
+    """Rank / precision sweep at the stacked-prompt shape (4 prompts x 4608 tokens, one shared basis):
+    per-launch time and algorithmic GB/s of the full step and the cached step for k in {8..128},
+    bf16 (matrix-core kernels, both arithmetic modes) and float32 (general vector-ALU kernels).
+    Prints one JSON line per case; not the headline benchmark."""
+    import torch
+    import paper_2601_07396_amd as pkg
+    from synth import WORKLOADS, FeatureStream
+    dev = torch.device("cuda:0")
+    base = WORKLOADS["sweep"]
+    ring = 8     # distinct buffers per case so that repetitions do not hit the 256 MB Infinity Cache
+    for dtype in ("bf16", "f32"):
+        wl0 = base.with_(dtype=dtype)
+        F0 = FeatureStream(wl0, 0, device=dev).at(0)
+        Fs = [F0.clone().unsqueeze(0) for _ in range(ring)]
+        Rs = [torch.empty_like(f) for f in Fs]
+        Fh = [torch.empty_like(f) for f in Fs]
+        for k in (8, 16, 32, 64, 128):
+            for mode in ((pkg.SVDC_PRECISE, pkg.SVDC_FAST) if dtype == "bf16" else (pkg.SVDC_PRECISE,)):
+                shape = pkg.make_shape(Fs[0], k, precision=mode)
+                V, _, _ = pkg.fit_basis(Fs[0], k)
+                pk = pkg.pack_basis(shape, V)
+                S = torch.zeros(1, wl0.N, k, device=dev)
+                reps = 24 if dtype == "bf16" else 8
+                res = {}
+                for name, call in (("full_step", lambda i: pkg.svdcache_full_step(shape, Fs[i], V, pk, Rs[i], S, None, 0.5, False)),
+                                   ("forecast", lambda i: pkg.svdcache_forecast(shape, S, V, pk, Rs[i], Fh[i]))):
+                    for i in range(ring):
+                        call(i)
+                    torch.cuda.synchronize()
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    for i in range(reps):
+                        call(i % ring)
+                    b.record()
+                    torch.cuda.synchronize()
+                    res[name] = a.elapsed_time(b) / reps
+                eb = wl0.elem_bytes
+                by_full = 2 * wl0.N * wl0.D * eb + 2 * wl0.N * k * 4 + wl0.D * k * 4
+                by_fore = 2 * wl0.N * wl0.D * eb + wl0.N * k * 4 + wl0.D * k * 4
+                print(json.dumps({"sweep": "stacked 18432x3072", "dtype": dtype, "k": k,
+                                  "mode": "fast" if mode else "precise", "mfma_path": pk is not None,
+                                  "full_step_ms": res["full_step"], "full_step_GBps": by_full / res["full_step"] / 1e6,
+                                  "forecast_ms": res["forecast"], "forecast_GBps": by_fore / res["forecast"] / 1e6}),
+                      flush=True)
+        del Fs, Rs, Fh
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +121,9 @@ def main():
     if not os.path.exists(pkg.lib_path()):
         from paper_2601_07396_amd import build
         build.build()
+    if args.workload == "sweep":
+        sweep(args)
+        return
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 

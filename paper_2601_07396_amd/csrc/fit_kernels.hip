@@ -1,7 +1,7 @@
 // Basis fit (Sec. 3.2, Eq. 4-5): the k leading right singular vectors of F by
 // randomized subspace iteration followed by a Rayleigh-Ritz step.
 //
-//   Q <- orth(Omega)                       Omega: D x l Gaussian, l = k + p
+//   Q <- Omega                             Omega: D x l Gaussian, l = k + p
 //   repeat q times:  Y = F Q;  Z = F^T Y;  Q <- orth(Z)       (one application of F^T F)
 //   Y = F Q;  H = Y^T Y = L L^T;  L^T = U diag(sigma) W^T     (one-sided Jacobi, fp64)
 //   V_k = Q W[:, :k],  sigma_k = sigma[:k]
@@ -286,7 +286,8 @@ __global__ __launch_bounds__(256) void rows_times_small_kernel(const float* __re
 // column by column (one thread per column) from the factor in LDS.
 // ---------------------------------------------------------------------------
 template <int BS>
-__global__ __launch_bounds__(256) void chol_inv_reg_kernel(double* G, double* Minv, int l, double rel_shift) {
+__global__ __launch_bounds__(256) void chol_inv_reg_kernel(double* G, double* Minv, double* rdiag, int l,
+                                                         double rel_shift) {
   constexpr int LM = 16 * BS;          // padded matrix size
   constexpr int LX = LM + 1;           // padded row stride of the inverse (bank spread)
   extern __shared__ double dyn_lds[];
@@ -354,6 +355,7 @@ __global__ __launch_bounds__(256) void chol_inv_reg_kernel(double* G, double* Mi
       const double v = (j <= i) ? a[ii][jj] : 0.0;
       Ls[i * LM + j] = v;
       if (i < l && j < l) g[(int64_t)i * l + j] = v;
+      if (rdiag && i == j && i < l) rdiag[(int64_t)b * l + i] = 1.0 / v;
     }
   __syncthreads();
   if (!Minv) return;
@@ -427,6 +429,59 @@ __global__ __launch_bounds__(256) void rows_times_small_tiled_kernel(const float
       const int j = j0 + tx + 16 * jj;
       if (j < m) out[(int64_t)row * m + j] = (float)acc[ii][jj];
     }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Out = In * L^-T by forward substitution, one thread per row:
+//   q_j = (z_j - sum_{i<j} q_i L[j][i]) / L[j][j]
+// L (float64 Cholesky factor, lower) and the reciprocals of its diagonal are read
+// at wave-uniform addresses (scalar loads); the row lives in registers.  Replaces the
+// explicit inverse factor plus a product for l <= LMAX.
+// ---------------------------------------------------------------------------
+template <int LMAX>
+__global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* __restrict__ In,
+                                                             const double* __restrict__ Lfac,
+                                                             const double* __restrict__ rdiag, float* Out,
+                                                             int rows, int l) {
+  const int b = blockIdx.y, t = threadIdx.x;
+  // every thread reads the same element of L at the same time: wave-uniform addresses, scalar loads
+  const double* Lf = Lfac + (int64_t)b * l * l;
+  const double* rd = rdiag + (int64_t)b * l;
+  const int64_t row = (int64_t)blockIdx.x * 256 + t;
+  if (row >= rows) return;
+  const float* in = In + ((int64_t)b * rows + row) * l;
+  float* out = Out + ((int64_t)b * rows + row) * l;
+  double q[LMAX];
+  const bool vec = (l & 3) == 0;   // rows are then 16-byte aligned
+  if (vec) {
+#pragma unroll
+    for (int j = 0; j < LMAX; j += 4) {
+      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (j < l) x = *reinterpret_cast<const float4*>(in + j);
+      q[j] = x.x; q[j + 1] = x.y; q[j + 2] = x.z; q[j + 3] = x.w;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < LMAX; ++j) q[j] = (j < l) ? (double)in[j] : 0.0;
+  }
+#pragma unroll
+  for (int j = 0; j < LMAX; ++j) {
+    if (j < l) {
+      double s = q[j];
+#pragma unroll
+      for (int i = 0; i < j; ++i) s -= q[i] * Lf[j * l + i];
+      q[j] = s * rd[j];
+    }
+  }
+  if (vec) {
+#pragma unroll
+    for (int j = 0; j < LMAX; j += 4)
+      if (j < l) *reinterpret_cast<float4*>(out + j) = make_float4((float)q[j], (float)q[j + 1], (float)q[j + 2], (float)q[j + 3]);
+  } else {
+#pragma unroll
+    for (int j = 0; j < LMAX; ++j)
+      if (j < l) out[j] = (float)q[j];
   }
 }
 
@@ -638,12 +693,12 @@ void gram(const float* A, double* G, int B, int rows, int l, hipStream_t st) {
   gram_f64_kernel<<<grid, 256, 0, st>>>(A, G, rows, l, rows_per_slice, ntile);
 }
 
-int32_t chol_inv(double* G, double* Minv, int B, int l, hipStream_t st) {
+int32_t chol_inv(double* G, double* Minv, int B, int l, hipStream_t st, double* rdiag = nullptr) {
   if (l <= 64) {
     constexpr int LM = 64;
     const size_t bytes = ((size_t)LM * LM + (size_t)LM * (LM + 1)) * sizeof(double);
     if (set_dyn_lds((const void*)chol_inv_reg_kernel<4>, bytes) != SVDC_OK) return SVDC_E_HIP;
-    chol_inv_reg_kernel<4><<<B, 256, bytes, st>>>(G, Minv, l, 1e-14);
+    chol_inv_reg_kernel<4><<<B, 256, bytes, st>>>(G, Minv, rdiag, l, 1e-14);
     return SVDC_OK;
   }
   const size_t bytes = (size_t)l * l * sizeof(double);
@@ -671,15 +726,28 @@ int32_t rows_times_small(const float* In, const double* M, float* Out, int B, in
 // One pass leaves the result in Qout and is accurate to about eps32 * cond(Zin): enough to keep the
 // power iteration well conditioned.  two_pass repeats the step on the result (CholeskyQR2), giving
 // orthonormality at float32 round-off; the result is then back in Zin.
+// Out = In * L^-T with L the Cholesky factor of In^T In (left in G by chol_inv)
+int32_t cholqr_apply(const float* In, float* Out, double* G, double* M, int B, int rows, int l, hipStream_t st) {
+  if (l <= 64) {
+    // M receives the reciprocal diagonal of L (its first l entries per block)
+    if (chol_inv(G, nullptr, B, l, st, M) != SVDC_OK) return SVDC_E_HIP;
+    dim3 grid((rows + 255) / 256, B);
+    if (l <= 16) tri_solve_rows_kernel<16><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
+    else if (l <= 32) tri_solve_rows_kernel<32><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
+    else tri_solve_rows_kernel<64><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
+    return SVDC_OK;
+  }
+  if (chol_inv(G, M, B, l, st) != SVDC_OK) return SVDC_E_HIP;
+  return rows_times_small(In, M, Out, B, rows, l, l, l, st);
+}
+
 int32_t orth(float* Zin, float* Qout, double* G, double* M, int B, int rows, int l, bool two_pass,
              hipStream_t st) {
   gram(Zin, G, B, rows, l, st);
-  if (chol_inv(G, M, B, l, st) != SVDC_OK) return SVDC_E_HIP;
-  if (rows_times_small(Zin, M, Qout, B, rows, l, l, l, st) != SVDC_OK) return SVDC_E_HIP;
+  if (cholqr_apply(Zin, Qout, G, M, B, rows, l, st) != SVDC_OK) return SVDC_E_HIP;
   if (!two_pass) return SVDC_OK;
   gram(Qout, G, B, rows, l, st);
-  if (chol_inv(G, M, B, l, st) != SVDC_OK) return SVDC_E_HIP;
-  return rows_times_small(Qout, M, Zin, B, rows, l, l, l, st);
+  return cholqr_apply(Qout, Zin, G, M, B, rows, l, st);
 }
 
 template <typename T>
@@ -695,14 +763,15 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   double* misc = (double*)(ws + pl.off_misc);
 
   const int64_t nq = (int64_t)B * s.D * l;
-  init_omega_kernel<<<(unsigned)((nq + 255) / 256), 256, 0, st>>>(Z, (int64_t)s.D * l, nq, pl.seed);
-  // Q <- orth(Omega).  With no power iteration this Q goes straight into the Rayleigh-Ritz step and
-  // must be orthonormal to round-off (two passes, result back in the first argument).
+  // With power iterations the Gaussian test matrix is used as it is (its columns are well conditioned
+  // and every product F^T F Q is re-orthonormalised afterwards).  With none, Q goes straight into the
+  // Rayleigh-Ritz step and must be orthonormal to round-off: Q <- orth(Omega), two passes.
   if (pl.q == 0) {
+    init_omega_kernel<<<(unsigned)((nq + 255) / 256), 256, 0, st>>>(Z, (int64_t)s.D * l, nq, pl.seed);
     if (orth(Z, Q, G, M, B, s.D, l, true, st) != SVDC_OK) return SVDC_E_HIP;
     std::swap(Q, Z);
   } else {
-    if (orth(Z, Q, G, M, B, s.D, l, false, st) != SVDC_OK) return SVDC_E_HIP;
+    init_omega_kernel<<<(unsigned)((nq + 255) / 256), 256, 0, st>>>(Q, (int64_t)s.D * l, nq, pl.seed);
   }
 
   void* Qp = ws + pl.off_Qp;
