@@ -115,6 +115,36 @@ __device__ __forceinline__ void split_operand(const float (&c)[8], u32x4* hi, u3
               pack_bf16(rem[6], rem[7])};
 }
 
+// Eight consecutive channels of one token as they sit in memory and in registers.  bf16: 16 bytes,
+// exact as an MFMA operand.  float32: 32 bytes; as an MFMA operand it is split into bf16 high + low parts.
+template <typename T>
+struct RowPiece;
+template <>
+struct RowPiece<bf16_t> {
+  u32x4 w;
+  __device__ __forceinline__ void load(const bf16_t* p) { w = *reinterpret_cast<const u32x4*>(p); }
+  __device__ __forceinline__ f32x4 half(int t) const {
+    return f32x4{bf16_lo(w[2 * t]), bf16_hi(w[2 * t]), bf16_lo(w[2 * t + 1]), bf16_hi(w[2 * t + 1])};
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const f32x4& x0, const f32x4& x1) {
+    *reinterpret_cast<u32x4*>(p) =
+        u32x4{pack_bf16(x0[0], x0[1]), pack_bf16(x0[2], x0[3]), pack_bf16(x1[0], x1[1]), pack_bf16(x1[2], x1[3])};
+  }
+};
+template <>
+struct RowPiece<float> {
+  f32x4 x[2];
+  __device__ __forceinline__ void load(const float* p) {
+    x[0] = *reinterpret_cast<const f32x4*>(p);
+    x[1] = *reinterpret_cast<const f32x4*>(p + 4);
+  }
+  __device__ __forceinline__ f32x4 half(int t) const { return x[t]; }
+  static __device__ __forceinline__ void store(float* p, const f32x4& x0, const f32x4& x1) {
+    *reinterpret_cast<f32x4*>(p) = x0;
+    *reinterpret_cast<f32x4*>(p + 4) = x1;
+  }
+};
+
 // ---------------------------------------------------------------------------
 // Cached step (Sec. 3.5):  Fhat = S V^T + R   for bf16 R / Fhat.
 //
@@ -128,10 +158,10 @@ __device__ __forceinline__ void split_operand(const float (&c)[8], u32x4* hi, u3
 // MFMA computes Fhat^T = R^T + (-V)(-S)^T.  PD tiles are kept in flight.
 // ---------------------------------------------------------------------------
 
-template <int NCW, int KT2, bool SPLIT, int PD>
+template <typename T, int NCW, int KT2, bool SPLIT, int PD>
 __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restrict__ S,
-                                                            const uint16_t* __restrict__ P, const bf16_t* R,
-                                                            bf16_t* Fh, int N, int D, int k, int64_t ldf,
+                                                            const uint16_t* __restrict__ P, const T* R,
+                                                            T* Fh, int N, int D, int k, int64_t ldf,
                                                             int64_t bstride, int NS, int groups_per_block,
                                                             int tiles_per_group) {
   const int slab = blockIdx.x % NS;
@@ -143,16 +173,16 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
   const u32x4* P2hi = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 2 * per);
   const u32x4* P2lo = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 3 * per);
   const int cg0 = (slab * kWavesPerGroup + wave) * NCW;
-  const bf16_t* rbase = R + (int64_t)b * bstride + 32 * cg0 + 8 * g;
-  bf16_t* obase = Fh + (int64_t)b * bstride + 32 * cg0 + 8 * g;
+  const T* rbase = R + (int64_t)b * bstride + 32 * cg0 + 8 * g;
+  T* obase = Fh + (int64_t)b * bstride + 32 * cg0 + 8 * g;
   const float* sbase = S + (int64_t)b * N * k;
   const int tile0 = rg * tiles_per_group;
   const int ntiles = min(tiles_per_group, (N + 15) / 16 - tile0);
 
-  u32x4 rin[PD][NCW];
+  RowPiece<T> rin[PD][NCW];
   f32x4 sraw[PD][KT2][2];
   // lane (r, g) needs S[row][j = 32 kt + 16 t + 4 g + i], i = 0..3 (zero beyond k)
-  auto load_tile = [&](int tile, u32x4(&ri)[NCW], f32x4(&sr)[KT2][2]) {
+  auto load_tile = [&](int tile, RowPiece<T>(&ri)[NCW], f32x4(&sr)[KT2][2]) {
     const int row = min(tile * 16 + r, N - 1);
 #pragma unroll
     for (int kt = 0; kt < KT2; ++kt)
@@ -163,7 +193,7 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
                             : f32x4{0.f, 0.f, 0.f, 0.f};
       }
 #pragma unroll
-    for (int c = 0; c < NCW; ++c) ri[c] = *reinterpret_cast<const u32x4*>(rbase + (int64_t)row * ldf + 32 * c);
+    for (int c = 0; c < NCW; ++c) ri[c].load(rbase + (int64_t)row * ldf + 32 * c);
   };
 #pragma unroll
   for (int u = 0; u < PD; ++u)
@@ -199,11 +229,10 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
       const int row = tile * 16 + r;
 #pragma unroll
       for (int c = 0; c < NCW; ++c) {
-        u32x4 out;
+        f32x4 res[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-          f32x4 acc = {bf16_lo(rin[u][c][2 * t]), bf16_hi(rin[u][c][2 * t]), bf16_lo(rin[u][c][2 * t + 1]),
-                       bf16_hi(rin[u][c][2 * t + 1])};
+          f32x4 acc = rin[u][c].half(t);
 #pragma unroll
           for (int kt = 0; kt < KT2; ++kt) {
             acc = mfma16(a_hi[c][t][kt], shi[kt], acc);
@@ -212,10 +241,9 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
               acc = mfma16(a_lo[c][t][kt], shi[kt], acc);
             }
           }
-          out[2 * t] = pack_bf16(acc[0], acc[1]);
-          out[2 * t + 1] = pack_bf16(acc[2], acc[3]);
+          res[t] = acc;
         }
-        if (row < N) *reinterpret_cast<u32x4*>(obase + (int64_t)row * ldf + 32 * c) = out;
+        if (row < N) RowPiece<T>::store(obase + (int64_t)row * ldf + 32 * c, res[0], res[1]);
       }
       if (it + u + PD < ntiles) load_tile(tile + PD, rin[u], sraw[u]);
     }
@@ -240,9 +268,9 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
 // S1 / S2: use the low parts of the basis (and of C) in phase 1 / phase 2.
 // F and R may alias: a tile is completely in registers before it is overwritten.
 // ---------------------------------------------------------------------------
-template <int CH, int RT, int KT2, bool S1, bool S2, int A>
-__global__ __launch_bounds__(256) void full_step_mfma_kernel(const bf16_t* F, const uint16_t* __restrict__ P,
-                                                             bf16_t* R, float* S, float* C, int N, int k,
+template <typename T, int CH, int RT, int KT2, bool S1, bool S2, int A>
+__global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const uint16_t* __restrict__ P,
+                                                             T* R, float* S, float* C, int N, int k,
                                                              int64_t ldf, int64_t bstride, float alpha, int init,
                                                              int tiles_per_block, int total) {
   constexpr int KP = KT2 * 32, KT = KT2 * 2, D = CH * 128;
@@ -254,15 +282,16 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const bf16_t* F, co
   int v = blockIdx.x;
   if (v >= total) return;
 
-  // the wave's slab of the tile: 16 bytes per lane per (row tile, chunk)
-  u32x4 f[RT][CH];
+  // the wave's slab of the tile: 8 channels per lane per (row tile, chunk)
+  constexpr bool kF32 = sizeof(T) == 4;
+  RowPiece<T> f[RT][CH];
   auto load_f_chunk = [&](int vv, int c) {
     const int b = vv / tiles_per_block, tile = vv % tiles_per_block;
-    const bf16_t* fbase = F + (int64_t)b * bstride + 32 * (cg0 + c) + 8 * g;
+    const T* fbase = F + (int64_t)b * bstride + 32 * (cg0 + c) + 8 * g;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       const int row = min(tile * 16 * RT + 16 * rt + r, N - 1);
-      f[rt][c] = *reinterpret_cast<const u32x4*>(fbase + (int64_t)row * ldf);
+      f[rt][c].load(fbase + (int64_t)row * ldf);
     }
   };
 #pragma unroll
@@ -275,7 +304,7 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const bf16_t* F, co
     const u32x4* P2hi = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 2 * per) + lane;
     const u32x4* P2lo = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 3 * per) + lane;
     const int row0 = tile * 16 * RT;
-    bf16_t* obase = R + (int64_t)b * bstride + 8 * g;
+    T* obase = R + (int64_t)b * bstride + 8 * g;
 
     // ---- phase 1: acc[jt][rt] = C^T[j = 16 jt + 4 g + i][row = 16 rt + r] over this wave's channels
     u32x4 v1h[A][KT], v1l[A][KT];
@@ -297,12 +326,23 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const bf16_t* F, co
     for (int c = 0; c < CH; ++c) {
       const int a = c % A;
 #pragma unroll
-      for (int jt = 0; jt < KT; ++jt)
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-          acc[jt][rt] = mfma16(v1h[a][jt], f[rt][c], acc[jt][rt]);
-          if (S1) acc[jt][rt] = mfma16(v1l[a][jt], f[rt][c], acc[jt][rt]);
+      for (int rt = 0; rt < RT; ++rt) {
+        // feature operand: exact for bf16; bf16 high + low parts for float32
+        u32x4 bh, bl;
+        if constexpr (kF32) {
+          const f32x4 x0 = f[rt][c].half(0), x1 = f[rt][c].half(1);
+          const float x8[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+          split_operand(x8, &bh, &bl);
+        } else {
+          bh = f[rt][c].w;
         }
+#pragma unroll
+        for (int jt = 0; jt < KT; ++jt) {
+          acc[jt][rt] = mfma16(v1h[a][jt], bh, acc[jt][rt]);
+          if (kF32) acc[jt][rt] = mfma16(v1h[a][jt], bl, acc[jt][rt]);
+          if (S1) acc[jt][rt] = mfma16(v1l[a][jt], bh, acc[jt][rt]);
+        }
+      }
       if (c + A < CH) {
 #pragma unroll
         for (int jt = 0; jt < KT; ++jt) {
@@ -392,11 +432,10 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const bf16_t* F, co
       const int a = c % A;
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        u32x4 out;
+        f32x4 res[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-          f32x4 x = {bf16_lo(f[rt][c][2 * t]), bf16_hi(f[rt][c][2 * t]), bf16_lo(f[rt][c][2 * t + 1]),
-                     bf16_hi(f[rt][c][2 * t + 1])};
+          f32x4 x = f[rt][c].half(t);
 #pragma unroll
           for (int kt = 0; kt < KT2; ++kt) {
             x = mfma16(v2h[a][t][kt], chi[rt][kt], x);
@@ -405,11 +444,10 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const bf16_t* F, co
               x = mfma16(v2l[a][t][kt], chi[rt][kt], x);
             }
           }
-          out[2 * t] = pack_bf16(x[0], x[1]);
-          out[2 * t + 1] = pack_bf16(x[2], x[3]);
+          res[t] = x;
         }
         const int row = row0 + 16 * rt + r;
-        if (row < N) *reinterpret_cast<u32x4*>(obase + (int64_t)row * ldf + 32 * (cg0 + c)) = out;
+        if (row < N) RowPiece<T>::store(obase + (int64_t)row * ldf + 32 * (cg0 + c), res[0], res[1]);
       }
       if (c + A < CH) {
 #pragma unroll
@@ -437,7 +475,6 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const bf16_t* F, co
 }  // namespace
 
 bool mfma_shape_supported(const svdc_shape& s) {
-  if (s.dtype != SVDC_BF16) return false;
   if (s.D % 128 != 0 || s.k > 128 || s.k % 4 != 0) return false;
   const int ch = s.D / 128;
   return ch == 2 || ch == 4 || ch == 24;
@@ -457,7 +494,7 @@ int32_t launch_pack_basis(const svdc_shape& s, const float* V, void* packed, hip
 
 namespace {
 
-template <int NCW, int KT2, bool SPLIT, int PD>
+template <typename T, int NCW, int KT2, bool SPLIT, int PD>
 int32_t forecast_launch(const svdc_shape& s, const float* S, const void* packed, const void* R, void* Fhat,
                         hipStream_t st) {
   const int NS = s.D / (128 * NCW);
@@ -476,81 +513,100 @@ int32_t forecast_launch(const svdc_shape& s, const float* S, const void* packed,
   const int gpb = (ntile + tpg - 1) / tpg;
   const int64_t grid = (int64_t)NS * gpb * s.B;
   if (grid > 0x7fffffff) return SVDC_E_SHAPE;
-  forecast_mfma_kernel<NCW, KT2, SPLIT, PD><<<(unsigned)grid, 256, 0, st>>>(
-      S, (const uint16_t*)packed, (const bf16_t*)R, (bf16_t*)Fhat, s.N, s.D, s.k, s.ldf, s.block_stride, NS, gpb,
-      tpg);
+  forecast_mfma_kernel<T, NCW, KT2, SPLIT, PD><<<(unsigned)grid, 256, 0, st>>>(
+      S, (const uint16_t*)packed, (const T*)R, (T*)Fhat, s.N, s.D, s.k, s.ldf, s.block_stride, NS, gpb, tpg);
   return launch_status();
 }
 
 // widest slab per wave (NCW chunks) that divides D / 128 and keeps the basis operands in registers
-template <int KT2, bool SPLIT, int PD>
+template <typename T, int KT2, bool SPLIT, int PD>
 int32_t forecast_by_width(const svdc_shape& s, const float* S, const void* packed, const void* R, void* Fhat,
                           hipStream_t st) {
-  constexpr int kMax = (SPLIT ? 12 : 24) / KT2 >= 12 ? 12 : ((SPLIT ? 12 : 24) / KT2 >= 6 ? 6 : 4);
+  // registers: basis operands 8 (16 with the low parts) per chunk and 32 coefficients, row pieces 4 (8 for f32)
+  constexpr int kBudget = (SPLIT ? 12 : 24) / KT2 / (sizeof(T) == 4 ? 2 : 1);
+  constexpr int kMax = kBudget >= 12 ? 12 : (kBudget >= 6 ? 6 : (kBudget >= 4 ? 4 : (kBudget >= 3 ? 3 : 2)));
   const int m = s.D / 128;
   if constexpr (kMax >= 12) {
-    if (m % 12 == 0) return forecast_launch<12, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+    if (m % 12 == 0) return forecast_launch<T, 12, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
   }
   if constexpr (kMax >= 6) {
-    if (m % 6 == 0) return forecast_launch<6, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+    if (m % 6 == 0) return forecast_launch<T, 6, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
   }
-  if (m % 4 == 0) return forecast_launch<4, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
-  if (m % 3 == 0) return forecast_launch<3, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
-  if (m % 2 == 0) return forecast_launch<2, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
-  return forecast_launch<1, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+  if constexpr (kMax >= 4) {
+    if (m % 4 == 0) return forecast_launch<T, 4, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+  }
+  if constexpr (kMax >= 3) {
+    if (m % 3 == 0) return forecast_launch<T, 3, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+  }
+  if (m % 2 == 0) return forecast_launch<T, 2, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+  return forecast_launch<T, 1, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
 }
 
-template <int CH, int RT, int KT2, bool SPLIT, int A>
+template <typename T, int CH, int RT, int KT2, bool SPLIT, int A>
 int32_t full_step_launch(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
                          float alpha, int init, hipStream_t st) {
   const int tiles = (s.N + 16 * RT - 1) / (16 * RT);
   const int64_t total = (int64_t)tiles * s.B;
   if (total > 0x7fffffff) return SVDC_E_SHAPE;
   const int grid = (int)std::min<int64_t>(total, num_compute_units());
-  full_step_mfma_kernel<CH, RT, KT2, SPLIT, SPLIT, A><<<grid, 256, 0, st>>>(
-      (const bf16_t*)F, (const uint16_t*)packed, (bf16_t*)R, S, C, s.N, s.k, s.ldf, s.block_stride, alpha, init,
-      tiles, (int)total);
+  full_step_mfma_kernel<T, CH, RT, KT2, SPLIT, SPLIT, A><<<grid, 256, 0, st>>>(
+      (const T*)F, (const uint16_t*)packed, (T*)R, S, C, s.N, s.k, s.ldf, s.block_stride, alpha, init, tiles,
+      (int)total);
   return launch_status();
 }
 
-template <int CH, bool SPLIT>
+template <typename T, int CH, bool SPLIT>
 int32_t full_step_by_rank(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
                           float alpha, int init, hipStream_t st) {
   // rows per tile (16 RT) and operand ring depth A per padded rank; wide tiles only when they fit in registers
+  // (a float32 row piece takes twice the registers of a bf16 one)
   constexpr bool small = CH <= 8;
+  constexpr int W = sizeof(T) == 4 ? 2 : 1;
   const int kp = padded_rank(s.k);
-  if (kp == 32) return full_step_launch<CH, small ? 4 : 2, 1, SPLIT, small ? 2 : 8>(s, F, packed, R, S, C, alpha, init, st);
-  if (kp == 64) return full_step_launch<CH, small ? 4 : (SPLIT ? 1 : 2), 2, SPLIT, small ? 2 : 4>(s, F, packed, R, S, C, alpha, init, st);
-  return full_step_launch<CH, small ? 2 : 1, 4, SPLIT, 2>(s, F, packed, R, S, C, alpha, init, st);
+  if (kp == 32)
+    return full_step_launch<T, CH, small ? 4 / W : 2 / W, 1, SPLIT, small ? 2 : 8 / W>(s, F, packed, R, S, C, alpha, init, st);
+  if (kp == 64)
+    return full_step_launch<T, CH, small ? 4 / W : (SPLIT || W == 2 ? 1 : 2), 2, SPLIT, small ? 2 : 4 / W>(s, F, packed, R, S, C, alpha, init, st);
+  return full_step_launch<T, CH, small ? 2 / W : 1, 4, SPLIT, small ? 2 : 2 / W>(s, F, packed, R, S, C, alpha, init, st);
+}
+
+template <typename T, bool SPLIT>
+int32_t full_step_by_width(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
+                           float alpha, int init, hipStream_t st) {
+  switch (s.D / 128) {
+    case 2: return full_step_by_rank<T, 2, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
+    case 4: return full_step_by_rank<T, 4, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
+    case 24: return full_step_by_rank<T, 24, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
+    default: return SVDC_E_SHAPE;
+  }
 }
 
 }  // namespace
 
 int32_t launch_full_step_mfma(const svdc_shape& s, const void* F, const void* packed, void* R, float* S,
                               float* C, float alpha, int init, hipStream_t st) {
-  const bool split = s.precision == SVDC_PRECISE;
-  switch (s.D / 128) {
-    case 2: return split ? full_step_by_rank<2, true>(s, F, packed, R, S, C, alpha, init, st)
-                         : full_step_by_rank<2, false>(s, F, packed, R, S, C, alpha, init, st);
-    case 4: return split ? full_step_by_rank<4, true>(s, F, packed, R, S, C, alpha, init, st)
-                         : full_step_by_rank<4, false>(s, F, packed, R, S, C, alpha, init, st);
-    case 24: return split ? full_step_by_rank<24, true>(s, F, packed, R, S, C, alpha, init, st)
-                          : full_step_by_rank<24, false>(s, F, packed, R, S, C, alpha, init, st);
-    default: return SVDC_E_SHAPE;
-  }
+  // float32 features always use the full operand split (a single bf16 operand would cost 8 of their 24 bits)
+  if (s.dtype == SVDC_F32) return full_step_by_width<float, true>(s, F, packed, R, S, C, alpha, init, st);
+  return s.precision == SVDC_PRECISE ? full_step_by_width<bf16_t, true>(s, F, packed, R, S, C, alpha, init, st)
+                                     : full_step_by_width<bf16_t, false>(s, F, packed, R, S, C, alpha, init, st);
 }
 
 int32_t launch_forecast_mfma(const svdc_shape& s, const float* S, const void* packed, const void* R,
                              void* Fhat, hipStream_t st) {
   const int kp = padded_rank(s.k);
-  if (s.precision == SVDC_PRECISE) {
-    if (kp == 32) return forecast_by_width<1, true, 1>(s, S, packed, R, Fhat, st);
-    if (kp == 64) return forecast_by_width<2, true, 2>(s, S, packed, R, Fhat, st);
-    return forecast_by_width<4, true, 2>(s, S, packed, R, Fhat, st);
+  if (s.dtype == SVDC_F32) {
+    if (kp == 32) return forecast_by_width<float, 1, true, 1>(s, S, packed, R, Fhat, st);
+    if (kp == 64) return forecast_by_width<float, 2, true, 2>(s, S, packed, R, Fhat, st);
+    return forecast_by_width<float, 4, true, 2>(s, S, packed, R, Fhat, st);
   }
-  if (kp == 32) return forecast_by_width<1, false, 2>(s, S, packed, R, Fhat, st);
-  if (kp == 64) return forecast_by_width<2, false, 2>(s, S, packed, R, Fhat, st);
-  return forecast_by_width<4, false, 2>(s, S, packed, R, Fhat, st);
+  if (s.precision == SVDC_PRECISE) {
+    if (kp == 32) return forecast_by_width<bf16_t, 1, true, 1>(s, S, packed, R, Fhat, st);
+    if (kp == 64) return forecast_by_width<bf16_t, 2, true, 2>(s, S, packed, R, Fhat, st);
+    return forecast_by_width<bf16_t, 4, true, 2>(s, S, packed, R, Fhat, st);
+  }
+  if (kp == 32) return forecast_by_width<bf16_t, 1, false, 2>(s, S, packed, R, Fhat, st);
+  if (kp == 64) return forecast_by_width<bf16_t, 2, false, 2>(s, S, packed, R, Fhat, st);
+  return forecast_by_width<bf16_t, 4, false, 2>(s, S, packed, R, Fhat, st);
 }
 
 }  // namespace svdc

@@ -413,3 +413,30 @@ def test_rank_sweep_at_stacked_prompt_shape():
     for k in (16, 64, 128):
         wl = WORKLOADS["sweep"].with_(k=k)
         _sampled_row_parity(wl, 1, blocks_to_check=[0], n_rows=64)
+
+
+# ---------------------------------------------------------------------------------------------
+# float32 features on the matrix cores (operands split into bf16 high + low parts)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("B,N,D,k", [(2, 200, 256, 32), (1, 77, 512, 8), (1, 131, 512, 128), (1, 150, 3072, 32),
+                                     (1, 70, 3072, 64), (2, 49, 256, 20)])
+def test_mfma_float32_features(B, N, D, k):
+    Fb, V, S0 = _lowrank_problem(B, N, D, k, seed=N * 3 + k)
+    g = torch.Generator().manual_seed(N)
+    F = Fb.float() + 1e-3 * torch.randn(B, N, D, generator=g)      # not bf16-representable
+    shape = pkg.make_shape(F, k)
+    assert pkg.svdcache_has_mfma_path(shape)
+    for init in (True, False):
+        R, S, Cc, shape, pk = _run_full(F, D, V, S0, 0.5, init)
+        assert pk is not None
+        Fh = torch.empty_like(R)
+        pkg.svdcache_forecast(shape, S, V.to(DEV), pk, R, Fh)
+        torch.cuda.synchronize()
+        for b in range(B):
+            Rr, Sr, Cr = ref_full_step(to_np(F[b]), to_np(V[b]), to_np(S0[b]), 0.5, init, "f32")
+            assert_close(to_np(R[b]), Rr, "f32", f"R[{b}]", floor_of=to_np(F[b]))
+            assert_close(to_np(S[b]), Sr, "f32", f"S[{b}]")
+            assert_close(to_np(Cc[b]), Cr, "f32", f"C[{b}]")
+            Fr = ref_forecast(to_np(S[b]), to_np(V[b]), to_np(R[b]), "f32")
+            assert_close(to_np(Fh[b]), Fr, "f32", f"Fhat[{b}]")
