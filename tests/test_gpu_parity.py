@@ -268,18 +268,21 @@ def test_mfma_and_general_paths_agree():
     assert rel_err(to_np(Fa), to_np(Fb)) <= 3e-3
 
 
-def test_mfma_inplace_and_strided():
-    B, N, D, k, ldf = 2, 90, 256, 32, 384
+@pytest.mark.parametrize("k", [32, 64, 128])
+def test_mfma_inplace_and_strided(k):
+    """In-place residual (R aliases F), padded row stride, no coefficient output."""
+    B, N, D, ldf = 2, 150, 256, 384
     F, V, S0 = _lowrank_problem(B, N, D, k, seed=11)
     buf = torch.zeros(B, N, ldf, dtype=torch.bfloat16)
     buf[:, :, :D] = F
-    R, S, _, shape, pk = _run_full(buf, D, V, S0, 0.5, False, want_C=False, inplace=True)
-    assert pk is not None and shape.ldf == ldf
-    for b in range(B):
-        Rr, Sr, _ = ref_full_step(to_np(F[b]), to_np(V[b]), to_np(S0[b]), 0.5, False, "bf16")
-        assert_close(to_np(R[b, :, :D]), Rr, "bf16", "R in place", floor_of=to_np(F[b]))
-        assert_close(to_np(S[b]), Sr, "f32", "S")
-    assert torch.equal(R[:, :, D:].cpu(), buf[:, :, D:])
+    for init in (True, False):
+        R, S, _, shape, pk = _run_full(buf, D, V, S0, 0.5, init, want_C=False, inplace=True)
+        assert pk is not None and shape.ldf == ldf
+        for b in range(B):
+            Rr, Sr, _ = ref_full_step(to_np(F[b]), to_np(V[b]), to_np(S0[b]), 0.5, init, "bf16")
+            assert_close(to_np(R[b, :, :D]), Rr, "bf16", "R in place", floor_of=to_np(F[b]))
+            assert_close(to_np(S[b]), Sr, "f32", "S")
+        assert torch.equal(R[:, :, D:].cpu(), buf[:, :, D:])
     Rc = R.clone()
     pkg.svdcache_forecast(shape, S, V.to(DEV), pk, R[:, :, :D], R[:, :, :D])
     torch.cuda.synchronize()
