@@ -476,8 +476,8 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
 
 bool mfma_shape_supported(const svdc_shape& s) {
   if (s.D % 128 != 0 || s.k > 128 || s.k % 4 != 0) return false;
-  const int ch = s.D / 128;
-  return ch == 2 || ch == 4 || ch == 24;
+  const int ch = s.D / 128;   // hidden sizes 256, 512, 1024, 1536, 2048, 3072, 4096
+  return ch == 2 || ch == 4 || ch == 8 || ch == 12 || ch == 16 || ch == 24 || ch == 32;
 }
 
 size_t mfma_packed_bytes(const svdc_shape& s) {
@@ -555,19 +555,35 @@ int32_t full_step_launch(const svdc_shape& s, const void* F, const void* packed,
   return launch_status();
 }
 
+// Row tiles per workgroup tile (RT) and depth of the basis-operand ring (A) for a feature width of CH * 128
+// channels, W = 1 (bf16) or 2 (float32) registers per channel pair, and KT2 = padded rank / 32.  The row
+// pieces of the tile take RT * CH * 4 * W registers per lane; about 192 are affordable next to the
+// accumulators, the coefficient operands and the rings.
+constexpr int tile_rows(int CH, int W, int KT2) {
+  int rt = 48 / (CH * W);
+  rt = rt > 4 ? 4 : rt;
+  if (KT2 >= 2 && rt > 1) rt = (CH <= 8 ? rt : rt / 2);
+  if (KT2 >= 4 && rt > 1) rt = rt / 2;
+  return rt < 1 ? 1 : rt;
+}
+constexpr int ring_depth(int CH, int W, int KT2) {
+  int a = 8 / (W * KT2);
+  if (CH <= 8 && a > 2) a = 2;
+  if (a < 1) a = 1;
+  while (CH % a) --a;
+  return a;
+}
+
 template <typename T, int CH, bool SPLIT>
 int32_t full_step_by_rank(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
                           float alpha, int init, hipStream_t st) {
-  // rows per tile (16 RT) and operand ring depth A per padded rank; wide tiles only when they fit in registers
-  // (a float32 row piece takes twice the registers of a bf16 one)
-  constexpr bool small = CH <= 8;
   constexpr int W = sizeof(T) == 4 ? 2 : 1;
   const int kp = padded_rank(s.k);
   if (kp == 32)
-    return full_step_launch<T, CH, small ? 4 / W : 2 / W, 1, SPLIT, small ? 2 : 8 / W>(s, F, packed, R, S, C, alpha, init, st);
+    return full_step_launch<T, CH, tile_rows(CH, W, 1), 1, SPLIT, ring_depth(CH, W, 1)>(s, F, packed, R, S, C, alpha, init, st);
   if (kp == 64)
-    return full_step_launch<T, CH, small ? 4 / W : (SPLIT || W == 2 ? 1 : 2), 2, SPLIT, small ? 2 : 4 / W>(s, F, packed, R, S, C, alpha, init, st);
-  return full_step_launch<T, CH, small ? 2 / W : 1, 4, SPLIT, small ? 2 : 2 / W>(s, F, packed, R, S, C, alpha, init, st);
+    return full_step_launch<T, CH, tile_rows(CH, W, 2), 2, SPLIT, ring_depth(CH, W, 2)>(s, F, packed, R, S, C, alpha, init, st);
+  return full_step_launch<T, CH, tile_rows(CH, W, 4), 4, SPLIT, ring_depth(CH, W, 4)>(s, F, packed, R, S, C, alpha, init, st);
 }
 
 template <typename T, bool SPLIT>
@@ -576,7 +592,11 @@ int32_t full_step_by_width(const svdc_shape& s, const void* F, const void* packe
   switch (s.D / 128) {
     case 2: return full_step_by_rank<T, 2, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
     case 4: return full_step_by_rank<T, 4, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
+    case 8: return full_step_by_rank<T, 8, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
+    case 12: return full_step_by_rank<T, 12, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
+    case 16: return full_step_by_rank<T, 16, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
     case 24: return full_step_by_rank<T, 24, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
+    case 32: return full_step_by_rank<T, 32, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
     default: return SVDC_E_SHAPE;
   }
 }
