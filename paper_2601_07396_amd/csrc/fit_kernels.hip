@@ -494,19 +494,22 @@ __global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* __rest
 //   Wout  out  [l x l] row-major, column r = right singular vector of rank r
 //   sigma out  [k] leading singular values
 // ---------------------------------------------------------------------------
+constexpr int kJacobiThreads = 512;
+
 template <bool a_in_lds, bool w_in_lds>   // compile-time so that LDS accesses are ds_* instructions, not flat ones
-__global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ Lfac, double* Wout, float* sigma,
+__global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __restrict__ Lfac, double* Wout, float* sigma,
                                                      double* gA, double* gW, int l, int k,
                                                      const double* fro_acc, float* fro2) {
   extern __shared__ double dyn_lds[];
   __shared__ double nrm[256];
+  constexpr int NT = kJacobiThreads;
   __shared__ int s_rot;
   const int b = blockIdx.x, t = threadIdx.x;
   const double* Lf = Lfac + (int64_t)b * l * l;
   const int la = l + 1;   // column stride, padded so that concurrently rotated columns spread over the LDS banks
   double* A = a_in_lds ? dyn_lds : gA + (int64_t)b * l * la;                        // column-major
   double* W = w_in_lds ? dyn_lds + (a_in_lds ? l * la : 0) : gW + (int64_t)b * l * la;  // column-major
-  for (int idx = t; idx < l * l; idx += 256) {
+  for (int idx = t; idx < l * l; idx += NT) {
     const int c = idx / l, r = idx % l;
     A[c * la + r] = (r <= c) ? Lf[idx] : 0.0;   // A[r][c] = L[c][r]
     W[c * la + r] = (r == c) ? 1.0 : 0.0;
@@ -517,7 +520,7 @@ __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ 
   const int le = (l + 1) & ~1;         // players in the round-robin (one dummy if l is odd)
   const int npairs = le / 2;           // <= 128
   int tp = 64;
-  while (tp > 1 && tp * npairs > 256) tp >>= 1;
+  while (tp > 1 && tp * npairs > NT) tp >>= 1;
   const int group = t / tp, gl = t % tp;
   const bool active = group < npairs;
 
@@ -580,14 +583,14 @@ __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ 
     if (rot == 0) break;
   }
 
-  for (int j = t; j < l; j += 256) {
+  for (int j = t; j < l; j += NT) {
     double s = 0.0;
     for (int r = 0; r < l; ++r) s += A[(int64_t)j * la + r] * A[(int64_t)j * la + r];
     nrm[j] = s;
   }
   __syncthreads();
   double* wo = Wout + (int64_t)b * l * l;
-  for (int j = t; j < l; j += 256) {
+  for (int j = t; j < l; j += NT) {
     const double nj = nrm[j];
     int rank = 0;
     for (int i = 0; i < l; ++i) rank += (nrm[i] > nj || (nrm[i] == nj && i < j)) ? 1 : 0;
@@ -816,12 +819,12 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   double* gW = Wg + (int64_t)B * l * (l + 1);
   if (a_in_lds && w_in_lds) {
     if (set_dyn_lds((const void*)jacobi_kernel<true, true>, lds) != SVDC_OK) return SVDC_E_HIP;
-    jacobi_kernel<true, true><<<B, 256, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+    jacobi_kernel<true, true><<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
   } else if (a_in_lds) {
     if (set_dyn_lds((const void*)jacobi_kernel<true, false>, lds) != SVDC_OK) return SVDC_E_HIP;
-    jacobi_kernel<true, false><<<B, 256, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+    jacobi_kernel<true, false><<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
   } else {
-    jacobi_kernel<false, false><<<B, 256, 0, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+    jacobi_kernel<false, false><<<B, kJacobiThreads, 0, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
   }
   if (rows_times_small(Q, M, V, B, s.D, l, s.k, l, st) != SVDC_OK) return SVDC_E_HIP;
   return launch_status();
