@@ -30,8 +30,8 @@ MFMA_BF16_PEAK_TF = 2500.0     # dense bf16, published
 # k = 32, SVDC_PRECISE), each scaled by what the same counter reads for a plain 1 GiB device copy
 # (profiles/flux57_k32_hbm_traffic.md).  Only valid for that configuration.
 MEASURED_TRAFFIC = {
-    ("flux57", 32, False, "forecast_mfma_kernel"): 3411313312,
-    ("flux57", 32, False, "full_step_mfma_kernel"): 3911251403,
+    ("flux57", 32, False, "forecast_mfma_kernel"): 3407418763,
+    ("flux57", 32, False, "full_step_mfma_kernel"): 3909389261,
 }
 
 
@@ -230,7 +230,7 @@ def main():
         "svdcache_full_step": {"launches_per_step": n_full, "avg_ms": avg["full"], "min_ms": lo["full"],
                                "GBps": by_full / avg["full"] / 1e6, "bytes": by_full},
         "svdcache_fit_basis": {"launches_per_step": 1, "avg_ms": avg["fit"], "min_ms": lo["fit"],
-                               "GBps": by_fit / avg["fit"] / 1e6, "TFLOPs": fit_flops / avg["fit"] / 1e9,
+                               "GBps": by_fit / avg["fit"] / 1e6, "bytes": by_fit, "TFLOPs": fit_flops / avg["fit"] / 1e9,
                                "mfma_frac": fit_flops / avg["fit"] / 1e9 / MFMA_BF16_PEAK_TF,
                                "sketch_width": l, "power_iters": q, "products_with_F": passes},
     }

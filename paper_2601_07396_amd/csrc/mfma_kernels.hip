@@ -624,7 +624,8 @@ int32_t launch_forecast_mfma(const svdc_shape& s, const float* S, const void* pa
     if (kp == 64) return forecast_by_width<bf16_t, 2, true, 2>(s, S, packed, R, Fhat, st);
     return forecast_by_width<bf16_t, 4, true, 2>(s, S, packed, R, Fhat, st);
   }
-  if (kp == 32) return forecast_by_width<bf16_t, 1, false, 2>(s, S, packed, R, Fhat, st);
+  // at rank <= 32 the split-operand kernel is the faster one (its matrix-core work is hidden anyway)
+  if (kp == 32) return forecast_by_width<bf16_t, 1, true, 1>(s, S, packed, R, Fhat, st);
   if (kp == 64) return forecast_by_width<bf16_t, 2, false, 2>(s, S, packed, R, Fhat, st);
   return forecast_by_width<bf16_t, 4, false, 2>(s, S, packed, R, Fhat, st);
 }
