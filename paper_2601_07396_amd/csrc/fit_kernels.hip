@@ -794,7 +794,6 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   for (int it = 0; it < pl.q; ++it) {
     project(false);
     if (pl.mfma) {
-      zero_f32(Z, (int64_t)B * s.D * l, st);
       fit_mfma_backproject(s, l, F, Y, Z, st);
     } else {
       gemm_fty<T>(s, l, F, Y, Z, st);

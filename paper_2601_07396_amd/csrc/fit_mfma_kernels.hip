@@ -3,8 +3,8 @@
 //   backproject  Z[D x l] += F[rows, :]^T * Y[rows, :]         (Z accumulators stationary in registers)
 // Both stream F exactly once, in 16- or 32-row tiles, on v_mfma_f32_16x16x32_bf16
 // (operand layouts: see mfma_kernels.hip).  project stores Y directly; backproject
-// combines the partial results of different row groups with float atomics, so Z
-// must be zero on entry.
+// stores Z directly when one workgroup covers all rows of a block and otherwise
+// combines the partial results of its row groups with float atomics (it clears Z itself).
 #include "svdc_device.h"
 #include "svdc_internal.h"
 
@@ -13,7 +13,6 @@ namespace svdc {
 namespace {
 
 constexpr int kWaves = 4;
-constexpr int kBackRows = 768;    // rows per workgroup in backproject (multiple of 32)
 
 __device__ __forceinline__ f32x4 mfma16(const u32x4& a, const u32x4& b, const f32x4& c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
@@ -179,7 +178,8 @@ template <int NCW, int KT>
 __global__ __launch_bounds__(256) void fit_backproject_mfma_kernel(const bf16_t* __restrict__ F,
                                                                    const float* __restrict__ Y, float* Z, int N,
                                                                    int D, int l, int64_t ldf, int64_t bstride,
-                                                                   int NS, int groups_per_block) {
+                                                                   int NS, int groups_per_block,
+                                                                   int rows_per_group) {
   const int slab = blockIdx.x % NS;
   const int rgb = blockIdx.x / NS;
   const int b = rgb / groups_per_block, rg = rgb % groups_per_block;
@@ -188,8 +188,8 @@ __global__ __launch_bounds__(256) void fit_backproject_mfma_kernel(const bf16_t*
   const uint32_t* fbase = reinterpret_cast<const uint32_t*>(F + (int64_t)b * bstride + 32 * cg0) + r;
   const int64_t ldw = ldf / 2;   // row stride in 32-bit words
   const float* ybase = Y + (int64_t)b * N * l;
-  const int row_begin = rg * kBackRows;
-  const int row_end = min(N, row_begin + kBackRows);
+  const int row_begin = rg * rows_per_group;
+  const int row_end = min(N, row_begin + rows_per_group);
 
   f32x4 acc[NCW][2][KT];
 #pragma unroll
@@ -251,7 +251,9 @@ __global__ __launch_bounds__(256) void fit_backproject_mfma_kernel(const bf16_t*
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int d = 32 * (cg0 + c) + 2 * (4 * g + i) + p;
-          atomicAdd(zbase + (int64_t)d * l + j, acc[c][p][jt][i]);
+          // one row group per block: every element has a single writer
+          if (groups_per_block == 1) zbase[(int64_t)d * l + j] = acc[c][p][jt][i];
+          else atomicAdd(zbase + (int64_t)d * l + j, acc[c][p][jt][i]);
         }
       }
 }
@@ -286,12 +288,33 @@ void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, f
 }
 
 template <int NCW, int KT>
-void backproject_launch(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, hipStream_t st) {
+void backproject_launch(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, int gpb, int rows,
+                        hipStream_t st) {
   const int NS = s.D / (128 * NCW);
-  const int gpb = (s.N + kBackRows - 1) / kBackRows;
   const unsigned grid = (unsigned)((int64_t)NS * gpb * s.B);
   fit_backproject_mfma_kernel<NCW, KT><<<grid, 256, 0, st>>>((const bf16_t*)F, Y, Z, s.N, s.D, l, s.ldf,
-                                                            s.block_stride, NS, gpb);
+                                                            s.block_stride, NS, gpb, rows);
+}
+
+__global__ void clear_f32_kernel(float* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.0f;
+}
+
+// Row groups per block in backproject.  Partial sums of different groups meet in float atomics, which cost
+// more than the parallelism they buy: one group per block as soon as the slabs of all blocks give about one
+// workgroup per compute unit, otherwise just enough groups to reach that.
+template <int NCW>
+void backproject_groups(const svdc_shape& s, int* gpb, int* rows) {
+  int dev = 0, cus = 256;
+  if (hipGetDevice(&dev) == hipSuccess) hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  const int64_t slabs = (int64_t)(s.D / (128 * NCW)) * s.B;
+  int g = (int)((cus + slabs / 2) / slabs);
+  if (g < 1) g = 1;
+  int r = ((s.N + g - 1) / g + 31) / 32 * 32;
+  if (r < 32) r = 32;
+  *rows = r;
+  *gpb = (s.N + r - 1) / r;
 }
 
 // largest instantiated slab width (chunks per wave) that divides D / 128 and is at most `cap`
@@ -319,15 +342,26 @@ void project_kt(const svdc_shape& s, int l, const void* F, const void* Qp, float
       [&] { project_launch<1, KT>(s, l, F, Qp, Y, fro, split, st); });
 }
 
+template <int NCW, int KT>
+void backproject_one(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, hipStream_t st) {
+  int gpb, rows;
+  backproject_groups<NCW>(s, &gpb, &rows);
+  if (gpb > 1) {   // atomics accumulate into Z
+    const int64_t n = (int64_t)s.B * s.D * l;
+    clear_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(Z, n);
+  }
+  backproject_launch<NCW, KT>(s, l, F, Y, Z, gpb, rows, st);
+}
+
 template <int KT>
 void backproject_kt(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, hipStream_t st) {
   constexpr int cap = width_for<KT>();
   by_width<KT>(
-      s.D / 128, [&] { backproject_launch<(cap >= 12 ? 12 : 1), KT>(s, l, F, Y, Z, st); },
-      [&] { backproject_launch<(cap >= 6 ? 6 : 1), KT>(s, l, F, Y, Z, st); },
-      [&] { backproject_launch<(cap >= 4 ? 4 : 1), KT>(s, l, F, Y, Z, st); },
-      [&] { backproject_launch<3, KT>(s, l, F, Y, Z, st); }, [&] { backproject_launch<2, KT>(s, l, F, Y, Z, st); },
-      [&] { backproject_launch<1, KT>(s, l, F, Y, Z, st); });
+      s.D / 128, [&] { backproject_one<(cap >= 12 ? 12 : 1), KT>(s, l, F, Y, Z, st); },
+      [&] { backproject_one<(cap >= 6 ? 6 : 1), KT>(s, l, F, Y, Z, st); },
+      [&] { backproject_one<(cap >= 4 ? 4 : 1), KT>(s, l, F, Y, Z, st); },
+      [&] { backproject_one<3, KT>(s, l, F, Y, Z, st); }, [&] { backproject_one<2, KT>(s, l, F, Y, Z, st); },
+      [&] { backproject_one<1, KT>(s, l, F, Y, Z, st); });
 }
 
 }  // namespace

@@ -44,7 +44,7 @@ void fit_mfma_pack_q(const svdc_shape& s, int l, const float* Q, void* Qp, hipSt
 // Y = F Q;  fro_acc (nullable) += ||F||_F^2;  split: bf16 high + low parts of Q
 void fit_mfma_project(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, double* fro_acc,
                       bool split, hipStream_t st);
-// Z (zeroed by the caller) += F^T Y
+// Z = F^T Y
 void fit_mfma_backproject(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, hipStream_t st);
 
 }  // namespace svdc
