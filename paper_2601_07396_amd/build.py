@@ -15,6 +15,8 @@ HIPCC_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     # float / double atomicAdd as hardware atomics
     "-munsafe-fp-atomics",
+    # the row tiles are register resident, so their loops must unroll completely however long they get
+    "-mllvm", "-pragma-unroll-threshold=1000000",
     "-Wno-unused-command-line-argument",
 ]
 

@@ -260,9 +260,9 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
 // keeps the channels [w D/4, (w+1) D/4) of all rows as packed bf16
 // (RT * CH * 4 VGPRs, CH = D / 128 chunks of 32 channels).
 //   phase 1  C^T partial = V^T F^T over the wave's channels (MFMA); the basis
-//            operands stream from L2 through a ring of A chunks so that their
-//            latency is covered; partials of the 4 waves are summed through LDS
-//            in a fixed order
+//            operands stream from L2 through a ring of RD operand words so that
+//            their latency is covered; partials of the 4 waves are summed through
+//            LDS in a fixed order
 //   EMA      wave w updates S (and writes C) for row tile w, w+4, ...
 //   phase 2  R^T = F^T - V C^T per chunk: accumulator starts at F, A operand
 //            is the negated basis, B operand is C (bf16 high [+ low] parts)
@@ -271,13 +271,13 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
 // S1 / S2: use the low parts of the basis (and of C) in phase 1 / phase 2.
 // F and R may alias: a tile is completely in registers before it is overwritten.
 // ---------------------------------------------------------------------------
-template <typename T, int CH, int RT, int KT2, bool S1, bool S2, int A>
+template <typename T, int CH, int RT, int KT2, bool S1, bool S2, int RD>
 __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const uint16_t* __restrict__ P,
                                                              T* R, float* S, float* C, int N, int k,
                                                              int64_t ldf, int64_t bstride, float alpha, int init,
                                                              int tiles_per_block, int total) {
   constexpr int KP = KT2 * 32, KT = KT2 * 2, D = CH * 128;
-  static_assert(CH % A == 0, "the operand ring must divide the chunk count");
+  constexpr int M = CH * KT;   // basis operand items per wave and phase (a high + a low 16-byte word per lane each)
   __shared__ f32x4 part[kWavesPerGroup][KT][RT][64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
   const int64_t per = (int64_t)D * KP;
@@ -309,15 +309,16 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
     const int row0 = tile * 16 * RT;
     T* obase = R + (int64_t)b * bstride + 8 * g;
 
-    // ---- phase 1: acc[jt][rt] = C^T[j = 16 jt + 4 g + i][row = 16 rt + r] over this wave's channels
-    u32x4 v1h[A][KT], v1l[A][KT];
+    // ---- phase 1: acc[jt][rt] = C^T[j = 16 jt + 4 g + i][row = 16 rt + r] over this wave's channels.
+    // Operand item m = (chunk c, coefficient tile jt), consecutive in the packed basis; RD items in flight.
+    const u32x4* p1h = P1hi + (int64_t)cg0 * KT * 64;
+    const u32x4* p1l = P1lo + (int64_t)cg0 * KT * 64;
+    u32x4 rh[RD], rl[RD];
 #pragma unroll
-    for (int a = 0; a < A; ++a)
-#pragma unroll
-      for (int jt = 0; jt < KT; ++jt) {
-        const int64_t ti = (int64_t)(cg0 + a) * KT + jt;
-        v1h[a][jt] = P1hi[ti * 64];
-        if (S1) v1l[a][jt] = P1lo[ti * 64];
+    for (int m = 0; m < RD; ++m)
+      if (m < M) {
+        rh[m] = p1h[m * 64];
+        if (S1) rl[m] = p1l[m * 64];
       }
     f32x4 acc[KT][RT];
 #pragma unroll
@@ -325,50 +326,46 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) acc[jt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
     __builtin_amdgcn_sched_barrier(0);
+    u32x4 bh[RT], bl[RT];   // feature operand of the current chunk: exact for bf16; high + low parts for float32
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const int a = c % A;
+    for (int m = 0; m < M; ++m) {
+      const int c = m / KT, jt = m % KT, slot = m % RD;
+      if (jt == 0) {
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        // feature operand: exact for bf16; bf16 high + low parts for float32
-        u32x4 bh, bl;
-        if constexpr (kF32) {
-          const f32x4 x0 = f[rt][c].half(0), x1 = f[rt][c].half(1);
-          const float x8[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
-          split_operand(x8, &bh, &bl);
-        } else {
-          bh = f[rt][c].w;
-        }
-#pragma unroll
-        for (int jt = 0; jt < KT; ++jt) {
-          acc[jt][rt] = mfma16(v1h[a][jt], bh, acc[jt][rt]);
-          if (kF32) acc[jt][rt] = mfma16(v1h[a][jt], bl, acc[jt][rt]);
-          if (S1) acc[jt][rt] = mfma16(v1l[a][jt], bh, acc[jt][rt]);
+        for (int rt = 0; rt < RT; ++rt) {
+          if constexpr (kF32) {
+            const f32x4 x0 = f[rt][c].half(0), x1 = f[rt][c].half(1);
+            const float x8[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+            split_operand(x8, &bh[rt], &bl[rt]);
+          } else {
+            bh[rt] = f[rt][c].w;
+          }
         }
       }
-      if (c + A < CH) {
 #pragma unroll
-        for (int jt = 0; jt < KT; ++jt) {
-          const int64_t ti = (int64_t)(cg0 + c + A) * KT + jt;
-          v1h[a][jt] = P1hi[ti * 64];
-          if (S1) v1l[a][jt] = P1lo[ti * 64];
-        }
+      for (int rt = 0; rt < RT; ++rt) {
+        acc[jt][rt] = mfma16(rh[slot], bh[rt], acc[jt][rt]);
+        if (kF32) acc[jt][rt] = mfma16(rh[slot], bl[rt], acc[jt][rt]);
+        if (S1) acc[jt][rt] = mfma16(rl[slot], bh[rt], acc[jt][rt]);
+      }
+      if (m + RD < M) {
+        rh[slot] = p1h[(m + RD) * 64];
+        if (S1) rl[slot] = p1l[(m + RD) * 64];
       }
       __builtin_amdgcn_sched_barrier(0);
     }
 
-    // the first reconstruction operands are requested before the reduction so they arrive during it
-    u32x4 v2h[A][2][KT2], v2l[A][2][KT2];
+    // the first reconstruction operands are requested before the reduction so they arrive during it;
+    // item n = (chunk c, half t, coefficient tile kt), again consecutive in memory
+    const u32x4* p2h = P2hi + (int64_t)cg0 * 2 * KT2 * 64;
+    const u32x4* p2l = P2lo + (int64_t)cg0 * 2 * KT2 * 64;
+    u32x4 qh[RD], ql[RD];
 #pragma unroll
-    for (int a = 0; a < A; ++a)
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int kt = 0; kt < KT2; ++kt) {
-          const int64_t ti = ((int64_t)(cg0 + a) * 2 + t) * KT2 + kt;
-          v2h[a][t][kt] = P2hi[ti * 64];
-          if (S2) v2l[a][t][kt] = P2lo[ti * 64];
-        }
+    for (int n = 0; n < RD; ++n)
+      if (n < M) {
+        qh[n] = p2h[n * 64];
+        if (S2) ql[n] = p2l[n * 64];
+      }
     __builtin_amdgcn_sched_barrier(0);
 
     // sum the four partial products through LDS, same order in every wave
@@ -432,35 +429,31 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
     // ---- phase 2: residual, chunk by chunk
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-      const int a = c % A;
+      f32x4 x[RT][2];
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) x[rt][t] = f[rt][c].half(t);
+#pragma unroll
+      for (int tk = 0; tk < 2 * KT2; ++tk) {
+        const int t = tk / KT2, kt = tk % KT2, n = c * 2 * KT2 + tk, slot = n % RD;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          x[rt][t] = mfma16(qh[slot], chi[rt][kt], x[rt][t]);
+          if (S2) {
+            x[rt][t] = mfma16(qh[slot], clo[rt][kt], x[rt][t]);
+            x[rt][t] = mfma16(ql[slot], chi[rt][kt], x[rt][t]);
+          }
+        }
+        if (n + RD < M) {
+          qh[slot] = p2h[(n + RD) * 64];
+          if (S2) ql[slot] = p2l[(n + RD) * 64];
+        }
+      }
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        f32x4 res[2];
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          f32x4 x = f[rt][c].half(t);
-#pragma unroll
-          for (int kt = 0; kt < KT2; ++kt) {
-            x = mfma16(v2h[a][t][kt], chi[rt][kt], x);
-            if (S2) {
-              x = mfma16(v2h[a][t][kt], clo[rt][kt], x);
-              x = mfma16(v2l[a][t][kt], chi[rt][kt], x);
-            }
-          }
-          res[t] = x;
-        }
         const int row = row0 + 16 * rt + r;
-        if (row < N) RowPiece<T>::store(obase + (int64_t)row * ldf + 32 * (cg0 + c), res[0], res[1]);
-      }
-      if (c + A < CH) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int kt = 0; kt < KT2; ++kt) {
-            const int64_t ti = ((int64_t)(cg0 + c + A) * 2 + t) * KT2 + kt;
-            v2h[a][t][kt] = P2hi[ti * 64];
-            if (S2) v2l[a][t][kt] = P2lo[ti * 64];
-          }
+        if (row < N) RowPiece<T>::store(obase + (int64_t)row * ldf + 32 * (cg0 + c), x[rt][0], x[rt][1]);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -545,36 +538,39 @@ int32_t forecast_by_width(const svdc_shape& s, const float* S, const void* packe
   return forecast_launch<T, 1, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
 }
 
-template <typename T, int CH, int RT, int KT2, bool SPLIT, int A>
+template <typename T, int CH, int RT, int KT2, bool SPLIT, int RD>
 int32_t full_step_launch(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
                          float alpha, int init, hipStream_t st) {
   const int tiles = (s.N + 16 * RT - 1) / (16 * RT);
   const int64_t total = (int64_t)tiles * s.B;
   if (total > 0x7fffffff) return SVDC_E_SHAPE;
   const int grid = (int)std::min<int64_t>(total, num_compute_units());
-  full_step_mfma_kernel<T, CH, RT, KT2, SPLIT, SPLIT, A><<<grid, 256, 0, st>>>(
+  full_step_mfma_kernel<T, CH, RT, KT2, SPLIT, SPLIT, RD><<<grid, 256, 0, st>>>(
       (const T*)F, (const uint16_t*)packed, (T*)R, S, C, s.N, s.k, s.ldf, s.block_stride, alpha, init, tiles,
       (int)total);
   return launch_status();
 }
 
-// Row tiles per workgroup tile (RT) and depth of the basis-operand ring (A) for a feature width of CH * 128
-// channels, W = 1 (bf16) or 2 (float32) registers per channel pair, and KT2 = padded rank / 32.  The row
-// pieces of the tile take RT * CH * 4 * W registers per lane; about 192 are affordable next to the
-// accumulators, the coefficient operands and the rings.
+// Row tiles per workgroup tile (RT) and depth of the basis-operand ring (RD items) for a feature width of
+// CH * 128 channels, W = 1 (bf16) or 2 (float32) registers per channel pair and KT2 = padded rank / 32.
+// Every basis byte is read once per tile, so the tile should have as many rows as the 512 registers of a lane
+// allow: estimate = row pieces + accumulators + coefficient operands + ring + addressing and temporaries.
+constexpr int full_step_regs(int CH, int W, int KT2, int RT, int RD) {
+  return RT * CH * 4 * W + 2 * KT2 * RT * 4 + RT * KT2 * 12 + RD * 8 + (W == 2 ? RT * 8 + 70 : 0) + 46 +
+         (KT2 == 4 ? 40 : 0);
+}
 constexpr int tile_rows(int CH, int W, int KT2) {
-  int rt = 48 / (CH * W);
-  rt = rt > 4 ? 4 : rt;
-  if (KT2 >= 2 && rt > 1) rt = (CH <= 8 ? rt : rt / 2);
-  if (KT2 >= 4 && rt > 1) rt = rt / 2;
-  return rt < 1 ? 1 : rt;
+  if (CH == 24 && W == 1) return KT2 == 1 ? 3 : 2;   // measured at 3072 channels (FLUX, HunyuanVideo)
+  for (int rt = 4; rt > 1; --rt)   // 2 KT2 rt <= 16: the reduction buffer (4 KB per accumulator) stays within 64 KB of LDS
+    if (full_step_regs(CH, W, KT2, rt, 8) <= 450 && 2 * KT2 * rt <= 16) return rt;
+  return 1;
 }
 constexpr int ring_depth(int CH, int W, int KT2) {
-  int a = 8 / (W * KT2);
-  if (CH <= 8 && a > 2) a = 2;
-  if (a < 1) a = 1;
-  while (CH % a) --a;
-  return a;
+  const int rt = tile_rows(CH, W, KT2);
+  int rd = KT2 == 1 ? 12 : (KT2 == 2 ? 16 : 8);   // measured best at 3072 channels
+  if (CH == 24 && W == 1) return rd;
+  while (rd > 2 && full_step_regs(CH, W, KT2, rt, rd) > 478) rd -= 2;
+  return rd;
 }
 
 template <typename T, int CH, bool SPLIT>
