@@ -114,6 +114,40 @@ def ref_rank_for_energy(sigma_all: np.ndarray, tau: float) -> int:
     return int(np.searchsorted(frac, tau, side="left") + 1) if tau > 0 else 1
 
 
+def ref_select_rank(sigma_lead, fro2: float, tau: float):
+    """Energy rule of Eq. 6 when only the k leading singular values and the
+    total energy ||F||_F^2 = sum over ALL sigma_i^2 are known (what a truncated
+    fit returns): the smallest k* <= k with sum_{i<=k*} sigma_i^2 >= tau * fro2.
+
+    Returns (k_star, reached).  If even all k values hold less than tau of the
+    energy, k_star = k and reached = False (the fitted rank is too small).
+
+    The decision is taken in float64 on the float32 inputs, the partial sums
+    formed left to right, the threshold formed as float64(tau32) * float64(fro2),
+    so that an implementation doing the same arithmetic gets the same integer."""
+    sig = np.asarray(sigma_lead, dtype=np.float32).astype(np.float64)
+    thr = float(np.float32(tau)) * float(np.float32(fro2))
+    acc = 0.0
+    for i, s_i in enumerate(sig):
+        acc = acc + s_i * s_i
+        if acc >= thr:
+            return i + 1, True
+    return len(sig), False
+
+
+def ref_truncate_basis(V, sigma, k_star: int):
+    """Rank-k* basis stored in the frame of a rank-k one: columns (and singular
+    values) from k* on are set to zero.  A step taken with this basis is the
+    rank-k* step: the extra coefficients are identically zero."""
+    V = np.array(V, dtype=np.float64, copy=True)
+    V[:, k_star:] = 0.0
+    if sigma is None:
+        return V, None
+    sigma = np.array(sigma, dtype=np.float64, copy=True)
+    sigma[k_star:] = 0.0
+    return V, sigma
+
+
 # ----------------------------------------------------------------------------
 # full-compute step (Eq. 8-11)
 # ----------------------------------------------------------------------------
@@ -162,6 +196,66 @@ def ref_forecast(S, V, R, store: str = "f64"):
     V = np.asarray(V, dtype=np.float64)
     R = np.asarray(R, dtype=np.float64)
     return round_store(S @ V.T + R, store)
+
+
+def ref_extrapolation_weights(order: int, offset: float, interval: float):
+    """Weights w_0..w_order on the states observed at times t, t - interval, ...,
+    t - order*interval such that sum_m w_m x(t - m*interval) is the value at
+    t + offset of the polynomial of degree `order` through those states
+    (Lagrange form; order 0 is plain reuse of the latest state).  This is how a
+    finite-difference / Taylor-type forecaster in the principal subspace
+    (Sec. 5.3, Fig. 5(b)) is expressed as a
+    linear combination of stored coefficient states."""
+    from fractions import Fraction
+    x = Fraction(offset).limit_denominator(1 << 20) / Fraction(interval).limit_denominator(1 << 20)
+    nodes = [Fraction(-m) for m in range(order + 1)]
+    w = []
+    for m, xm in enumerate(nodes):
+        num, den = Fraction(1), Fraction(1)
+        for i, xi in enumerate(nodes):
+            if i != m:
+                num *= (x - xi)
+                den *= (xm - xi)
+        w.append(float(num / den))
+    return np.array(w, dtype=np.float64)
+
+
+def ref_forecast_combine(S_list, weights, V, R, X=None, store: str = "f64"):
+    """Cached step with a forecaster that is linear in stored coefficient states
+    (Sec. 5.3, Fig. 5(b): other predictors applied to the low-rank part):
+        C_hat = sum_m w_m S_m,   Fhat = C_hat V_k^T + R   [+ X]
+    With one state and weight 1 this is the paper's cached step.  X, if given,
+    is a tensor the forecast is added to (the hidden state of a residual
+    connection), so that Fhat itself need not be written."""
+    V = np.asarray(V, dtype=np.float64)
+    R = np.asarray(R, dtype=np.float64)
+    w = np.asarray(weights, dtype=np.float32).astype(np.float64)
+    if len(S_list) != len(w) or len(w) < 1:
+        raise ValueError("one weight per state")
+    C_hat = np.zeros_like(np.asarray(S_list[0], dtype=np.float64))
+    for w_m, S_m in zip(w, S_list):
+        C_hat = C_hat + w_m * np.asarray(S_m, dtype=np.float64)
+    out = C_hat @ V.T + R
+    if X is not None:
+        out = out + np.asarray(X, dtype=np.float64)
+    return round_store(out, store)
+
+
+def ref_full_step_residual_ema(F, V, S_prev, R_prev, alpha: float, alpha_r: float, init: bool, store: str = "f64"):
+    """Ablation "EMA on both parts" (Sec. 4.5, Fig. 5(c)): as ref_full_step, and the
+    residual state is smoothed too,
+        R_state = R_new                                   if init
+        R_state = (1 - alpha_r) R_prev + alpha_r R_new     otherwise,
+    with R_new = F - C V_k^T.  alpha_r = 1 is the paper's method (plain reuse of
+    the latest residual)."""
+    if not (0.0 < alpha_r <= 1.0):
+        raise ValueError("alpha_r must lie in (0, 1]")
+    R_new, S, C = ref_full_step(F, V, S_prev, alpha, init, store="f64")
+    if init:
+        R_state = R_new
+    else:
+        R_state = (1.0 - alpha_r) * np.asarray(R_prev, dtype=np.float64) + alpha_r * R_new
+    return round_store(R_state, store), _round_f32(S, store), _round_f32(C, store)
 
 
 # ----------------------------------------------------------------------------

@@ -269,3 +269,134 @@ def check_forecast(full, forecast):
     assert np.array_equal(forecast(S_, Z, R0, "f64"), F)
     # the forecast does not depend on anything but (S, V, R): no hidden state
     assert np.array_equal(forecast(S, V, R, "f64"), Fh)
+
+
+# ---------------------------------------------------------------------------
+# rank selection by retained energy (Eq. 6)
+# ---------------------------------------------------------------------------
+
+def check_select_rank(select, rank_all):
+    """select(sigma_lead, fro2, tau) -> (k_star, reached);  rank_all(sigma_all, tau) -> k_star."""
+    # equal singular values: k of n hold the fraction k/n, so k* = ceil(tau n)
+    n = 20
+    sig = np.full(n, 3.0, dtype=np.float32)
+    for tau, want in [(0.04, 1), (0.26, 6), (0.5, 10), (0.51, 11), (1.0, 20)]:   # no ties except exact binary fractions
+        assert select(sig, float(9.0 * n), tau) == (want, True)
+    # geometric energies sigma_i^2 = 2^-i (i >= 1, infinitely many: total energy 1):
+    # the k leading ones hold 1 - 2^-k, so k* = ceil(-log2(1 - tau))
+    sig = np.sqrt(2.0 ** -np.arange(1, 25)).astype(np.float32)
+    for tau, want in [(0.4, 1), (0.55, 2), (0.7, 2), (0.85, 3), (0.9, 4), (0.99, 7)]:
+        assert select(sig, 1.0, tau) == (want, True), tau
+    # only 3 values kept: they hold 87.5 % -- enough for 0.85, not for 0.9
+    assert select(sig[:3], 1.0, 0.85) == (3, True)
+    assert select(sig[:3], 1.0, 0.9) == (3, False)
+    assert select(sig[:2], 1.0, 0.85) == (2, False)
+    # with the whole spectrum known it is the textbook cumulative-energy rule
+    r = rng(41)
+    for trial in range(20):
+        s_all = np.sort(np.abs(r.standard_normal(30)) + 0.01)[::-1].astype(np.float32)
+        fro2 = float(np.sum(s_all.astype(np.float64) ** 2))
+        tau = float(r.uniform(0.05, 0.97))
+        frac = np.cumsum(s_all.astype(np.float64) ** 2) / fro2
+        if np.min(np.abs(frac - tau)) < 1e-6:      # a tie in the last bits: either answer is right
+            continue
+        assert select(s_all, fro2, tau) == (rank_all(s_all, tau), True)
+    # monotone in tau
+    ks = [select(s_all, fro2, t)[0] for t in np.linspace(0.01, 0.99, 50)]
+    assert all(a <= b for a, b in zip(ks, ks[1:]))
+
+
+def check_truncate_basis(truncate, full):
+    """A step with the truncated basis is the rank-k* step."""
+    r, F, V, S0 = _problem(33, n=30, d=18, k=6)
+    for ks in (1, 4, 6):
+        Vt, st = truncate(V, np.arange(6, 0, -1.0), ks)
+        assert np.array_equal(Vt[:, :ks], V[:, :ks]) and not Vt[:, ks:].any()
+        assert np.array_equal(st[:ks], np.arange(6, 6 - ks, -1.0)) and not st[ks:].any()
+        R, S, C = full(F, Vt, None, 0.5, True, "f64")
+        R_k, S_k, C_k = full(F, V[:, :ks], None, 0.5, True, "f64")
+        assert np.abs(R - R_k).max() <= 1e-13
+        assert np.abs(C[:, :ks] - C_k).max() <= 1e-13 and not C[:, ks:].any() and not S[:, ks:].any()
+    assert V[:, 5].any()          # the input was not modified
+
+
+# ---------------------------------------------------------------------------
+# forecasters that are linear in stored coefficient states (Sec. 5.3, Fig. 5(b))
+# ---------------------------------------------------------------------------
+
+def check_extrapolation_weights(weights):
+    # order 0: reuse; order 1: the straight line through the last two states
+    assert np.allclose(weights(0, 3, 6), [1.0], atol=0, rtol=0)
+    for j, d in [(1, 6), (5, 6), (2, 3)]:
+        assert np.allclose(weights(1, j, d), [1 + j / d, -j / d], rtol=1e-15)
+    # a polynomial of degree <= order is extrapolated exactly
+    r = rng(5)
+    for order in (1, 2, 3):
+        coef = r.standard_normal(order + 1)
+        poly = lambda t: sum(c * t ** i for i, c in enumerate(coef))
+        for j, d in [(1.0, 6.0), (4.0, 5.0), (7.0, 2.0)]:
+            w = weights(order, j, d)
+            t0 = 11.0
+            got = sum(w[m] * poly(t0 - m * d) for m in range(order + 1))
+            assert abs(got - poly(t0 + j)) <= 1e-9 * max(1.0, abs(poly(t0 + j))), (order, j, d)
+            assert abs(sum(w) - 1.0) <= 1e-12
+    # offset 0 returns the latest state itself
+    assert np.allclose(weights(3, 0, 6), [1, 0, 0, 0], atol=1e-15)
+    # offset -interval returns the state before it
+    assert np.allclose(weights(2, -6, 6), [0, 1, 0], atol=1e-15)
+
+
+def check_forecast_combine(combine, forecast, full, weights):
+    r, F, V, S0 = _problem(27)
+    R, S, C = full(F, V, None, 0.5, True, "f64")
+    # one state, weight 1: the paper's cached step
+    assert np.array_equal(combine([S], [1.0], V, R, None, "f64"), forecast(S, V, R, "f64"))
+    # linear in the states
+    S2 = r.standard_normal(S.shape)
+    w = [0.75, -1.5]
+    got = combine([S, S2], w, V, R, None, "f64")
+    want = R + w[0] * (S @ V.T) + w[1] * (S2 @ V.T)
+    assert np.abs(got - want).max() <= 1e-12
+    # order matters with unequal weights (a swapped pair is caught)
+    assert np.abs(got - combine([S2, S], w, V, R, None, "f64")).max() > 1e-3
+    # element-wise definition written out
+    n, d = F.shape
+    for (i, j) in [(0, 0), (7, 2), (n - 1, d - 1)]:
+        e = sum((w[0] * S[i, m] + w[1] * S2[i, m]) * V[j, m] for m in range(V.shape[1])) + R[i, j]
+        assert abs(got[i, j] - e) <= 1e-12
+    # added tensor
+    X = r.standard_normal(F.shape)
+    assert np.abs(combine([S, S2], w, V, R, X, "f64") - (want + X)).max() <= 1e-12
+    # a feature whose principal coefficients move on a straight line and whose residual is constant is
+    # forecast exactly by the order-1 weights on the last two observed coefficient sets
+    Cs = [C + t * S2 for t in (0.0, 6.0)]                  # observed at t = 0 and t = 6
+    j = 3.0          # weights 1.5 and -0.5 are exact in float32
+    F_future = (C + (6.0 + j) * S2) @ V.T + R
+    got = combine([Cs[1], Cs[0]], weights(1, j, 6.0), V, R, None, "f64")
+    assert np.abs(got - F_future).max() <= 1e-10
+    # storage rounding happens once, at the end
+    out = combine([S, S2], w, V, R, X, "bf16")
+    exact = want + X
+    assert np.all(np.abs(out - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-30)
+
+
+def check_residual_ema(full_ema, full):
+    r, F, V, S0 = _problem(29)
+    R_prev = r.standard_normal(F.shape)
+    # alpha_r = 1 and init: the paper's full step
+    for init in (True, False):
+        a = full_ema(F, V, S0, R_prev, 0.3, 1.0, init, "f64")
+        b = full(F, V, S0, 0.3, init, "f64")
+        assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    R_new, S, C = full(F, V, S0, 0.3, False, "f64")
+    Rs, S2, C2 = full_ema(F, V, S0, R_prev, 0.3, 0.25, False, "f64")
+    assert np.abs(Rs - (0.75 * R_prev + 0.25 * R_new)).max() <= 1e-13
+    assert np.array_equal(S2, S) and np.array_equal(C2, C)
+    # init ignores the previous residual
+    Ri, _, _ = full_ema(F, V, None, R_prev, 0.3, 0.25, True, "f64")
+    assert np.array_equal(Ri, full(F, V, None, 0.3, True, "f64")[0])
+    # a constant feature gives a constant residual state, whatever alpha_r
+    Rc = R_new
+    for _ in range(4):
+        Rc, _, _ = full_ema(F, V, S0, Rc, 0.3, 0.4, False, "f64")
+    assert np.abs(Rc - R_new).max() <= 1e-13

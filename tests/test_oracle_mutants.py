@@ -95,3 +95,85 @@ def test_fit_mutants_are_caught(mut):
         except AssertionError:
             caught += 1
     assert caught >= 1, mut
+
+
+@pytest.mark.parametrize("mut", ["sigma_not_squared", "strict_inequality_off_by_one", "index_not_count",
+                                 "normalised_by_kept_energy", "never_reports_unreached"])
+def test_select_rank_mutants_are_caught(mut):
+    from oracle import ref_rank_for_energy
+
+    def select(sigma_lead, fro2, tau):
+        sig = np.asarray(sigma_lead, np.float64)
+        e = sig if mut == "sigma_not_squared" else sig * sig
+        total = np.sum(e) if mut == "normalised_by_kept_energy" else float(fro2)
+        thr = float(np.float32(tau)) * total
+        acc = 0.0
+        for i, x in enumerate(e):
+            acc += x
+            if acc >= thr:
+                k = i + 1
+                if mut == "strict_inequality_off_by_one":
+                    k = min(len(e), k + 1)
+                if mut == "index_not_count":
+                    k = max(1, i)
+                return k, True
+        return len(e), (mut == "never_reports_unreached")
+    with pytest.raises(AssertionError):
+        pins.check_select_rank(select, ref_rank_for_energy)
+
+
+@pytest.mark.parametrize("mut", ["nodes_forward", "offset_sign", "not_normalised"])
+def test_extrapolation_weight_mutants_are_caught(mut):
+    def weights(order, offset, interval):
+        x = offset / interval
+        if mut == "offset_sign":
+            x = -x
+        nodes = [float(m) if mut == "nodes_forward" else -float(m) for m in range(order + 1)]
+        w = []
+        for m, xm in enumerate(nodes):
+            num = den = 1.0
+            for i, xi in enumerate(nodes):
+                if i != m:
+                    num *= (x - xi)
+                    den *= (xm - xi) if mut != "not_normalised" else 1.0
+            w.append(num / den)
+        return np.array(w)
+    with pytest.raises(AssertionError):
+        pins.check_extrapolation_weights(weights)
+
+
+@pytest.mark.parametrize("mut", ["weights_ignored", "weights_swapped", "residual_weighted", "added_tensor_dropped",
+                                 "first_state_only"])
+def test_forecast_combine_mutants_are_caught(mut):
+    from oracle import ref_extrapolation_weights
+
+    def combine(S_list, w, V, R, X, store="f64"):
+        from oracle import round_store
+        w = list(w)
+        if mut == "weights_ignored":
+            w = [1.0 / len(w)] * len(w)
+        if mut == "weights_swapped":
+            w = w[::-1]
+        if mut == "first_state_only":
+            S_list, w = S_list[:1], w[:1]
+        Ch = sum(wm * np.asarray(Sm, float) for wm, Sm in zip(w, S_list))
+        out = Ch @ V.T + (R * sum(w) if mut == "residual_weighted" else R)
+        if X is not None and mut != "added_tensor_dropped":
+            out = out + X
+        return round_store(out, store)
+    with pytest.raises(AssertionError):
+        pins.check_forecast_combine(combine, ref_forecast, ref_full_step, ref_extrapolation_weights)
+
+
+@pytest.mark.parametrize("mut", ["weights_swapped", "init_blends", "principal_state_smoothed_with_alpha_r"])
+def test_residual_ema_mutants_are_caught(mut):
+    def full_ema(F, V, S_prev, R_prev, alpha, alpha_r, init, store="f64"):
+        a = alpha_r if mut == "principal_state_smoothed_with_alpha_r" else alpha
+        R_new, S, C = ref_full_step(F, V, S_prev, a, init, "f64")
+        if init and mut != "init_blends":
+            return R_new, S, C
+        if mut == "weights_swapped":
+            return alpha_r * R_prev + (1 - alpha_r) * R_new, S, C
+        return (1 - alpha_r) * R_prev + alpha_r * R_new, S, C
+    with pytest.raises(AssertionError):
+        pins.check_residual_ema(full_ema, ref_full_step)

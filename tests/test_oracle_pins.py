@@ -56,3 +56,28 @@ def test_argument_errors():
         ref_full_step(F, np.zeros((3, 1)), None, 0.0, True)
     with pytest.raises(ValueError):
         ref_full_step(F, np.zeros((3, 1)), None, 1.5, True)
+
+
+def test_select_rank():
+    from oracle import ref_select_rank
+    pins.check_select_rank(ref_select_rank, ref_rank_for_energy)
+
+
+def test_truncate_basis():
+    from oracle import ref_truncate_basis
+    pins.check_truncate_basis(ref_truncate_basis, ref_full_step)
+
+
+def test_extrapolation_weights():
+    from oracle import ref_extrapolation_weights
+    pins.check_extrapolation_weights(ref_extrapolation_weights)
+
+
+def test_forecast_combine():
+    from oracle import ref_forecast_combine, ref_extrapolation_weights
+    pins.check_forecast_combine(ref_forecast_combine, ref_forecast, ref_full_step, ref_extrapolation_weights)
+
+
+def test_residual_ema():
+    from oracle import ref_full_step_residual_ema
+    pins.check_residual_ema(ref_full_step_residual_ema, ref_full_step)
