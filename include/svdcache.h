@@ -61,6 +61,9 @@ typedef enum {
   SVDC_E_HIP = -7        /* a HIP runtime call or kernel launch failed           */
 } svdc_status;
 
+/* Most coefficient states a linear forecaster may combine (svdcache_forecast_combine). */
+#define SVDC_MAX_STATES 4
+
 /* One batched problem: B independent blocks of identical shape.
  *   1 <= k <= min(N, D), k <= 1024;  ldf >= D;  block_stride >= (N-1)*ldf + D.
  *   Base pointers of F/R/Fhat must be 16-byte aligned; with dtype BF16, D, ldf
@@ -145,6 +148,53 @@ int32_t svdcache_full_step(const svdc_shape* shape, const void* F, const float* 
  *   if the caller no longer needs R. */
 int32_t svdcache_forecast(const svdc_shape* shape, const float* S, const float* V,
                           const void* packed, const void* R, void* Fhat, void* stream);
+
+/* Rank selection by retained energy (Sec. 3.2, Eq. 6; threshold tau about 0.85 in Sec. 4.5):
+ * per block the smallest k* <= k with  sum_{i <= k*} sigma_i^2  >=  tau * fro2,  where fro2 = ||F||_F^2 is the
+ * energy of ALL singular values (the fro2 output of svdcache_fit_basis).  Decided in float64, partial sums
+ * formed left to right.
+ *   sigma    in   [B,k] float32, descending (as returned by the fit)
+ *   fro2     in   [B]   float32
+ *   tau      in   (0, 1]
+ *   k_star   out  [B] int32, in 1..k
+ *   reached  out  [B] int32, nullable: 1 if the threshold was reached within the k fitted values, else 0
+ *                 (then k_star = k: the basis was fitted with too small a rank for this tau) */
+int32_t svdcache_select_rank(int32_t B, int32_t k, const float* sigma, const float* fro2, float tau,
+                             int32_t* k_star, int32_t* reached, void* stream);
+
+/* Per-block ranks inside one batched problem: zero the columns j >= k_star[b] of V[b] (and the entries of
+ * sigma[b], nullable).  A full / cached step with the truncated basis IS the rank-k_star[b] step of block b
+ * (the extra coefficients are identically zero), so blocks of different rank share one launch.  Pack the
+ * basis again afterwards.
+ *   V in/out [B,D,k] float32;  sigma in/out [B,k] float32 or NULL;  k_star in [B] int32, each in 0..k */
+int32_t svdcache_truncate_basis(const svdc_shape* shape, float* V, float* sigma, const int32_t* k_star,
+                                void* stream);
+
+/* Weights of polynomial extrapolation from equally spaced past states (HOST function, no GPU work):
+ * weights[m], m = 0..order, such that sum_m weights[m] * x(t - m*interval) is the value at t + offset of the
+ * polynomial of degree `order` through x(t), x(t - interval), ..., x(t - order*interval).  order 0 is plain
+ * reuse, order 1 the linear trend.  This is how a finite-difference forecaster applied to the principal
+ * coefficients (Sec. 5.3) enters svdcache_forecast_combine.
+ *   order in 0..SVDC_MAX_STATES-1;  interval != 0;  weights: host array of order+1 floats */
+int32_t svdcache_extrapolation_weights(int32_t order, double offset, double interval, float* weights);
+
+/* Cached step with a forecaster that is linear in stored coefficient states (Sec. 5.3: other predictors
+ * applied to the low-rank part; Sec. 3.5 for the reconstruction):
+ *   C_hat = sum_{m < num_states} weights[m] * S_list[m]
+ *   Out   = C_hat V^T + R [+ X]
+ * One state with weight 1 is svdcache_forecast.  One pass over R (and X), no intermediate buffers.
+ *   num_states  1..SVDC_MAX_STATES
+ *   S_list      HOST array of num_states device pointers, each [B,N,k] float32 (e.g. the C outputs of the
+ *               last full steps, or EMA states)
+ *   weights     HOST array of num_states floats
+ *   V, packed   as in svdcache_forecast
+ *   R           in  [B,N,D] dtype
+ *   X           in  [B,N,D] dtype or NULL: a tensor the forecast is added to (the hidden state of a residual
+ *               connection), so that the forecast itself never has to be written and read back
+ *   Out         out [B,N,D] dtype; may be the same buffer as R or as X */
+int32_t svdcache_forecast_combine(const svdc_shape* shape, int32_t num_states, const float* const* S_list,
+                                  const float* weights, const float* V, const void* packed, const void* R,
+                                  const void* X, void* Out, void* stream);
 
 #ifdef __cplusplus
 }

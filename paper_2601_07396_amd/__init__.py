@@ -10,6 +10,7 @@ from .binding import (
     SvdcError, Shape, SVDC_PRECISE, SVDC_FAST, lib_path, load_library, exported_symbols,
     svdcache_version, svdcache_strerror, svdcache_fit_workspace_bytes, svdcache_packed_basis_bytes,
     svdcache_has_mfma_path, svdcache_fit_basis, svdcache_pack_basis, svdcache_full_step, svdcache_forecast,
+    svdcache_select_rank, svdcache_truncate_basis, svdcache_extrapolation_weights, svdcache_forecast_combine,
     make_shape, fit_basis, pack_basis,
 )
 
@@ -17,5 +18,6 @@ __all__ = [
     "SvdcError", "Shape", "SVDC_PRECISE", "SVDC_FAST", "lib_path", "load_library", "exported_symbols",
     "svdcache_version", "svdcache_strerror", "svdcache_fit_workspace_bytes", "svdcache_packed_basis_bytes",
     "svdcache_has_mfma_path", "svdcache_fit_basis", "svdcache_pack_basis", "svdcache_full_step",
-    "svdcache_forecast", "make_shape", "fit_basis", "pack_basis",
+    "svdcache_forecast", "svdcache_select_rank", "svdcache_truncate_basis", "svdcache_extrapolation_weights",
+    "svdcache_forecast_combine", "make_shape", "fit_basis", "pack_basis",
 ]

@@ -44,6 +44,13 @@ EXPORTS = {
                                        C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_void_p]),
     "svdcache_forecast": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p]),
+    "svdcache_select_rank": (C.c_int32, [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p,
+                                         C.c_void_p, C.c_void_p]),
+    "svdcache_truncate_basis": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "svdcache_extrapolation_weights": (C.c_int32, [C.c_int32, C.c_double, C.c_double, C.POINTER(C.c_float)]),
+    "svdcache_forecast_combine": (C.c_int32, [C.POINTER(Shape), C.c_int32, C.POINTER(C.c_void_p),
+                                              C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p]),
 }
 
 _lib = None
@@ -155,6 +162,41 @@ def svdcache_forecast(shape: Shape, S, V, packed, R, Fhat):
     rc = load_library().svdcache_forecast(C.byref(shape), _ptr(S), _ptr(V), _ptr(packed), _ptr(R), _ptr(Fhat),
                                           _stream())
     _check(rc, "svdcache_forecast")
+
+
+def svdcache_select_rank(sigma, fro2, tau: float, k_star, reached=None):
+    """k_star [B] int32 (and reached [B] int32, optional) from sigma [B,k] float32 and fro2 [B] float32."""
+    _need_gpu(sigma, fro2, k_star, reached)
+    B, k = sigma.shape
+    rc = load_library().svdcache_select_rank(B, k, _ptr(sigma), _ptr(fro2), float(tau), _ptr(k_star), _ptr(reached),
+                                             _stream())
+    _check(rc, "svdcache_select_rank")
+
+
+def svdcache_truncate_basis(shape: Shape, V, sigma, k_star):
+    _need_gpu(V, sigma, k_star)
+    rc = load_library().svdcache_truncate_basis(C.byref(shape), _ptr(V), _ptr(sigma), _ptr(k_star), _stream())
+    _check(rc, "svdcache_truncate_basis")
+
+
+def svdcache_extrapolation_weights(order: int, offset: float, interval: float):
+    """Host-side: the order+1 weights as a list of Python floats (float32 values)."""
+    w = (C.c_float * (order + 1 if order >= 0 else 1))()
+    rc = load_library().svdcache_extrapolation_weights(int(order), float(offset), float(interval), w)
+    _check(rc, "svdcache_extrapolation_weights")
+    return [float(x) for x in w]
+
+
+def svdcache_forecast_combine(shape: Shape, S_list, weights, V, packed, R, X, Out):
+    _need_gpu(*S_list, V, packed, R, X, Out)
+    m = len(S_list)
+    if m != len(weights):
+        raise ValueError("one weight per state")
+    ptrs = (C.c_void_p * max(m, 1))(*[t.data_ptr() for t in S_list])
+    w = (C.c_float * max(m, 1))(*[float(x) for x in weights])
+    rc = load_library().svdcache_forecast_combine(C.byref(shape), m, ptrs, w, _ptr(V), _ptr(packed), _ptr(R),
+                                                  _ptr(X), _ptr(Out), _stream())
+    _check(rc, "svdcache_forecast_combine")
 
 
 # ---- conveniences that only allocate (torch owns the memory) ------------------------------------

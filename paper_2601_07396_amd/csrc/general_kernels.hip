@@ -97,12 +97,12 @@ __global__ __launch_bounds__(256) void full_step_general_kernel(const T* F, cons
   }
 }
 
-// Cached step (Sec. 3.5): Fhat = S V^T + R.  R and Fhat may alias.
+// Cached step (Sec. 3.5): Fhat = C_hat V^T + R [+ X] with the coefficient forecast C_hat = sum_m w_m S_m
+// (one state with weight one is the paper's EMA forecast).  X is nullable; Fhat may alias R or X.
 template <typename T>
-__global__ __launch_bounds__(256) void forecast_general_kernel(const float* __restrict__ S,
-                                                               const float* __restrict__ V, const T* R, T* Fh,
-                                                               int N, int D, int k, int64_t ldf,
-                                                               int64_t bstride) {
+__global__ __launch_bounds__(256) void forecast_general_kernel(const CoefStates cs, const float* __restrict__ V,
+                                                               const T* R, const T* X, T* Fh, int N, int D, int k,
+                                                               int64_t ldf, int64_t bstride) {
   __shared__ float ssh[kRowsPerGroup][kMaxRank];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int b = blockIdx.y;
@@ -110,11 +110,16 @@ __global__ __launch_bounds__(256) void forecast_general_kernel(const float* __re
   const bool valid = row < N;
   if (valid) {
     const int64_t srow = ((int64_t)b * N + row) * k;
-    for (int j = lane; j < k; j += kWave) ssh[wave][j] = S[srow + j];
+    for (int j = lane; j < k; j += kWave) {
+      float c = cs.w[0] * cs.s[0][srow + j];
+      for (int m = 1; m < cs.m; ++m) c = __builtin_fmaf(cs.w[m], cs.s[m][srow + j], c);
+      ssh[wave][j] = c;
+    }
   }
   __syncthreads();
   if (!valid) return;
   const T* r = R + (int64_t)b * bstride + row * ldf;
+  const T* x = X ? X + (int64_t)b * bstride + row * ldf : nullptr;
   T* o = Fh + (int64_t)b * bstride + row * ldf;
   const float* v = V + (int64_t)b * D * k;
   const float* sw = ssh[wave];
@@ -130,7 +135,9 @@ __global__ __launch_bounds__(256) void forecast_general_kernel(const float* __re
     } else {
       for (int j = 0; j < k; ++j) acc += sw[j] * vp[j];
     }
-    st_elem(o, d, ld_elem(r, d) + acc);
+    float base = ld_elem(r, d);
+    if (x) base += ld_elem(x, d);
+    st_elem(o, d, base + acc);
   }
 }
 
@@ -146,15 +153,64 @@ int32_t launch_full_step_general(const svdc_shape& s, const void* F, const float
   return launch_status();
 }
 
-int32_t launch_forecast_general(const svdc_shape& s, const float* S, const float* V, const void* R,
-                                void* Fhat, hipStream_t st) {
+int32_t launch_forecast_general(const svdc_shape& s, const CoefStates& cs, const float* V, const void* R,
+                                const void* X, void* Out, hipStream_t st) {
   dim3 grid((s.N + kRowsPerGroup - 1) / kRowsPerGroup, s.B), block(256);
   if (s.dtype == SVDC_BF16)
-    forecast_general_kernel<bf16_t><<<grid, block, 0, st>>>(S, V, (const bf16_t*)R, (bf16_t*)Fhat, s.N, s.D, s.k,
-                                                          s.ldf, s.block_stride);
+    forecast_general_kernel<bf16_t><<<grid, block, 0, st>>>(cs, V, (const bf16_t*)R, (const bf16_t*)X, (bf16_t*)Out,
+                                                          s.N, s.D, s.k, s.ldf, s.block_stride);
   else
-    forecast_general_kernel<float><<<grid, block, 0, st>>>(S, V, (const float*)R, (float*)Fhat, s.N, s.D, s.k,
-                                                         s.ldf, s.block_stride);
+    forecast_general_kernel<float><<<grid, block, 0, st>>>(cs, V, (const float*)R, (const float*)X, (float*)Out, s.N,
+                                                         s.D, s.k, s.ldf, s.block_stride);
+  return launch_status();
+}
+
+// ---------------------------------------------------------------------------
+// Rank selection by retained energy (Eq. 6) from the leading singular values and ||F||_F^2:
+// k* = smallest count whose squared singular values sum to at least tau * ||F||_F^2, in float64, summed left to
+// right.  One thread per block (k <= 1024 values).
+// ---------------------------------------------------------------------------
+__global__ void select_rank_kernel(const float* __restrict__ sigma, const float* __restrict__ fro2, float tau,
+                                   int32_t* k_star, int32_t* reached, int B, int k) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const double thr = (double)tau * (double)fro2[b];
+  double acc = 0.0;
+  int ks = k, ok = 0;
+  for (int i = 0; i < k; ++i) {
+    const double s = (double)sigma[(int64_t)b * k + i];
+    acc = acc + s * s;
+    if (acc >= thr) {
+      ks = i + 1;
+      ok = 1;
+      break;
+    }
+  }
+  k_star[b] = ks;
+  if (reached) reached[b] = ok;
+}
+
+// zero the columns j >= k_star[b] of V[b] (and of sigma[b])
+__global__ __launch_bounds__(256) void truncate_basis_kernel(float* V, float* sigma, const int32_t* __restrict__ k_star,
+                                                             int D, int k) {
+  const int b = blockIdx.y;
+  const int ks = k_star[b];
+  const int64_t n = (int64_t)D * k;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx < n && (int)(idx % k) >= ks) V[(int64_t)b * n + idx] = 0.f;
+  if (sigma && idx < k && idx >= ks) sigma[(int64_t)b * k + idx] = 0.f;
+}
+
+int32_t launch_select_rank(int B, int k, const float* sigma, const float* fro2, float tau, int32_t* k_star,
+                           int32_t* reached, hipStream_t st) {
+  select_rank_kernel<<<(B + 63) / 64, 64, 0, st>>>(sigma, fro2, tau, k_star, reached, B, k);
+  return launch_status();
+}
+
+int32_t launch_truncate_basis(const svdc_shape& s, float* V, float* sigma, const int32_t* k_star, hipStream_t st) {
+  const int64_t n = (int64_t)s.D * s.k;
+  dim3 grid((unsigned)((n + 255) / 256), s.B);
+  truncate_basis_kernel<<<grid, 256, 0, st>>>(V, sigma, k_star, s.D, s.k);
   return launch_status();
 }
 

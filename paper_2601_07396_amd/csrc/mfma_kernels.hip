@@ -158,12 +158,11 @@ struct RowPiece<float> {
 // MFMA computes Fhat^T = R^T + (-V)(-S)^T.  PD tiles are kept in flight.
 // ---------------------------------------------------------------------------
 
-template <typename T, int NCW, int KT2, bool SPLIT, int PD>
-__global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restrict__ S,
-                                                            const uint16_t* __restrict__ P, const T* R,
-                                                            T* Fh, int N, int D, int k, int64_t ldf,
-                                                            int64_t bstride, int NS, int groups_per_block,
-                                                            int tiles_per_group) {
+template <typename T, int NCW, int KT2, bool SPLIT, int PD, bool EXT>
+__global__ __launch_bounds__(256) void forecast_mfma_kernel(const CoefStates cs, const uint16_t* __restrict__ P,
+                                                            const T* R, const T* X, T* Fh, int N, int D, int k,
+                                                            int64_t ldf, int64_t bstride, int NS,
+                                                            int groups_per_block, int tiles_per_group) {
   const int slab = blockIdx.x % NS;
   const int rgb = blockIdx.x / NS;
   const int b = rgb / groups_per_block, rg = rgb % groups_per_block;
@@ -175,7 +174,12 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
   const int cg0 = (slab * kWavesPerGroup + wave) * NCW;
   const T* rbase = R + (int64_t)b * bstride + 32 * cg0 + 8 * g;
   T* obase = Fh + (int64_t)b * bstride + 32 * cg0 + 8 * g;
-  const float* sbase = S + (int64_t)b * N * k;
+  // EXT: the coefficient forecast is sum_m w_m S_m over up to kMaxStates stored states, and a tensor X
+  // (nullable) is added to the result; otherwise the single state cs.s[0] with weight one.
+  constexpr int MS = EXT ? kMaxStates : 1;
+  const bool has_x = EXT && X != nullptr;
+  const T* xbase = has_x ? X + (int64_t)b * bstride + 32 * cg0 + 8 * g : nullptr;
+  const int64_t soff = (int64_t)b * N * k;
   // Row tiles rg, rg + groups_per_block, ...: the workgroups of a block advance through its rows side by
   // side, which keeps the addresses in flight close together (measurably kinder to HBM than giving each
   // workgroup a contiguous range of tiles).
@@ -183,24 +187,35 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
   const int ntiles = min(tiles_per_group, (ntile_block - rg + groups_per_block - 1) / groups_per_block);
 
   RowPiece<T> rin[PD][NCW];
-  f32x4 sraw[PD][KT2][2];
+  RowPiece<T> xin[PD][EXT ? NCW : 1];
+  f32x4 sraw[PD][MS][KT2][2];
   // lane (r, g) needs S[row][j = 32 kt + 16 t + 4 g + i], i = 0..3 (zero beyond k)
-  auto load_tile = [&](int tile, RowPiece<T>(&ri)[NCW], f32x4(&sr)[KT2][2]) {
+  auto load_tile = [&](int tile, int u) {
     const int row = min(tile * 16 + r, N - 1);
 #pragma unroll
-    for (int kt = 0; kt < KT2; ++kt)
+    for (int ms = 0; ms < MS; ++ms) {
+      if (ms >= cs.m) break;
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const int j = 32 * kt + 16 * t + 4 * g;
-        sr[kt][t] = (j < k) ? *reinterpret_cast<const f32x4*>(sbase + (int64_t)row * k + j)
-                            : f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int kt = 0; kt < KT2; ++kt)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const int j = 32 * kt + 16 * t + 4 * g;
+          sraw[u][ms][kt][t] = (j < k) ? *reinterpret_cast<const f32x4*>(cs.s[ms] + soff + (int64_t)row * k + j)
+                                       : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < NCW; ++c) rin[u][c].load(rbase + (int64_t)row * ldf + 32 * c);
+    if constexpr (EXT) {
+      if (has_x) {
+#pragma unroll
+        for (int c = 0; c < NCW; ++c) xin[u][c].load(xbase + (int64_t)row * ldf + 32 * c);
       }
-#pragma unroll
-    for (int c = 0; c < NCW; ++c) ri[c].load(rbase + (int64_t)row * ldf + 32 * c);
+    }
   };
 #pragma unroll
   for (int u = 0; u < PD; ++u)
-    if (u < ntiles) load_tile(rg + u * groups_per_block, rin[u], sraw[u]);
+    if (u < ntiles) load_tile(rg + u * groups_per_block, u);
 
   u32x4 a_hi[NCW][2][KT2], a_lo[NCW][2][KT2];
 #pragma unroll
@@ -226,7 +241,17 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) c8[4 * t + i] = -sraw[u][kt][t][i];
+          for (int i = 0; i < 4; ++i) {
+            if constexpr (EXT) {
+              float v = cs.w[0] * sraw[u][0][kt][t][i];
+#pragma unroll
+              for (int ms = 1; ms < MS; ++ms)
+                if (ms < cs.m) v = __builtin_fmaf(cs.w[ms], sraw[u][ms][kt][t][i], v);
+              c8[4 * t + i] = -v;
+            } else {
+              c8[4 * t + i] = -sraw[u][0][kt][t][i];
+            }
+          }
         split_operand(c8, &shi[kt], &slo[kt]);
       }
       const int row = tile * 16 + r;
@@ -236,6 +261,12 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           f32x4 acc = rin[u][c].half(t);
+          if constexpr (EXT) {
+            if (has_x) {
+              const f32x4 xa = xin[u][c].half(t);
+              acc[0] += xa[0]; acc[1] += xa[1]; acc[2] += xa[2]; acc[3] += xa[3];
+            }
+          }
 #pragma unroll
           for (int kt = 0; kt < KT2; ++kt) {
             acc = mfma16(a_hi[c][t][kt], shi[kt], acc);
@@ -248,7 +279,7 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const float* __restr
         }
         if (row < N) RowPiece<T>::store(obase + (int64_t)row * ldf + 32 * c, res[0], res[1]);
       }
-      if (it + u + PD < ntiles) load_tile(tile + PD * groups_per_block, rin[u], sraw[u]);
+      if (it + u + PD < ntiles) load_tile(tile + PD * groups_per_block, u);
     }
   }
 }
@@ -490,9 +521,9 @@ int32_t launch_pack_basis(const svdc_shape& s, const float* V, void* packed, hip
 
 namespace {
 
-template <typename T, int NCW, int KT2, bool SPLIT, int PD>
-int32_t forecast_launch(const svdc_shape& s, const float* S, const void* packed, const void* R, void* Fhat,
-                        hipStream_t st) {
+template <typename T, int NCW, int KT2, bool SPLIT, int PD, bool EXT>
+int32_t forecast_launch(const svdc_shape& s, const CoefStates& cs, const void* packed, const void* R, const void* X,
+                        void* Fhat, hipStream_t st) {
   const int NS = s.D / (128 * NCW);
   const int ntile = (s.N + 15) / 16;
   // Row tiles per workgroup: 6..16, chosen so that the workgroups fill whole rounds of the machine
@@ -509,33 +540,38 @@ int32_t forecast_launch(const svdc_shape& s, const float* S, const void* packed,
   const int gpb = (ntile + tpg - 1) / tpg;
   const int64_t grid = (int64_t)NS * gpb * s.B;
   if (grid > 0x7fffffff) return SVDC_E_SHAPE;
-  forecast_mfma_kernel<T, NCW, KT2, SPLIT, PD><<<(unsigned)grid, 256, 0, st>>>(
-      S, (const uint16_t*)packed, (const T*)R, (T*)Fhat, s.N, s.D, s.k, s.ldf, s.block_stride, NS, gpb, tpg);
+  forecast_mfma_kernel<T, NCW, KT2, SPLIT, PD, EXT><<<(unsigned)grid, 256, 0, st>>>(
+      cs, (const uint16_t*)packed, (const T*)R, (const T*)X, (T*)Fhat, s.N, s.D, s.k, s.ldf, s.block_stride, NS, gpb,
+      tpg);
   return launch_status();
 }
 
 // widest slab per wave (NCW chunks) that divides D / 128 and keeps the basis operands in registers
-template <typename T, int KT2, bool SPLIT, int PD>
-int32_t forecast_by_width(const svdc_shape& s, const float* S, const void* packed, const void* R, void* Fhat,
-                          hipStream_t st) {
+template <typename T, int KT2, bool SPLIT, int PD, bool EXT>
+int32_t forecast_by_width(const svdc_shape& s, const CoefStates& cs, const void* packed, const void* R, const void* X,
+                          void* Fhat, hipStream_t st) {
   // registers: basis operands 8 (16 with the low parts) per chunk and 32 coefficients, row pieces 4 (8 for f32)
-  constexpr int kBudget = (SPLIT ? 12 : 24) / KT2 / (sizeof(T) == 4 ? 2 : 1);
-  constexpr int kMax = kBudget >= 12 ? 12 : (kBudget >= 6 ? 6 : (kBudget >= 4 ? 4 : (kBudget >= 3 ? 3 : 2)));
+  // (the extended kernel also holds up to 4 coefficient states and the added tensor per tile in flight)
+  constexpr int kBudget = (SPLIT ? 12 : 24) / KT2 / (sizeof(T) == 4 ? 2 : 1) / (EXT && KT2 >= 2 ? 2 : 1);
+  constexpr int kMax =
+      kBudget >= 12 ? 12 : (kBudget >= 6 ? 6 : (kBudget >= 4 ? 4 : (kBudget >= 3 ? 3 : (kBudget >= 2 ? 2 : 1))));
   const int m = s.D / 128;
   if constexpr (kMax >= 12) {
-    if (m % 12 == 0) return forecast_launch<T, 12, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+    if (m % 12 == 0) return forecast_launch<T, 12, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
   }
   if constexpr (kMax >= 6) {
-    if (m % 6 == 0) return forecast_launch<T, 6, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+    if (m % 6 == 0) return forecast_launch<T, 6, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
   }
   if constexpr (kMax >= 4) {
-    if (m % 4 == 0) return forecast_launch<T, 4, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+    if (m % 4 == 0) return forecast_launch<T, 4, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
   }
   if constexpr (kMax >= 3) {
-    if (m % 3 == 0) return forecast_launch<T, 3, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+    if (m % 3 == 0) return forecast_launch<T, 3, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
   }
-  if (m % 2 == 0) return forecast_launch<T, 2, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
-  return forecast_launch<T, 1, KT2, SPLIT, PD>(s, S, packed, R, Fhat, st);
+  if constexpr (kMax >= 2) {
+    if (m % 2 == 0) return forecast_launch<T, 2, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
+  }
+  return forecast_launch<T, 1, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
 }
 
 template <typename T, int CH, int RT, int KT2, bool SPLIT, int RD>
@@ -610,23 +646,42 @@ int32_t launch_full_step_mfma(const svdc_shape& s, const void* F, const void* pa
                                      : full_step_by_width<bf16_t, false>(s, F, packed, R, S, C, alpha, init, st);
 }
 
-int32_t launch_forecast_mfma(const svdc_shape& s, const float* S, const void* packed, const void* R,
-                             void* Fhat, hipStream_t st) {
+namespace {
+
+template <bool EXT>
+int32_t forecast_dispatch(const svdc_shape& s, const CoefStates& cs, const void* packed, const void* R,
+                          const void* X, void* Fhat, hipStream_t st) {
   const int kp = padded_rank(s.k);
   if (s.dtype == SVDC_F32) {
-    if (kp == 32) return forecast_by_width<float, 1, true, 1>(s, S, packed, R, Fhat, st);
-    if (kp == 64) return forecast_by_width<float, 2, true, 2>(s, S, packed, R, Fhat, st);
-    return forecast_by_width<float, 4, true, 2>(s, S, packed, R, Fhat, st);
+    if (kp == 32) return forecast_by_width<float, 1, true, 1, EXT>(s, cs, packed, R, X, Fhat, st);
+    if (kp == 64) return forecast_by_width<float, 2, true, 2, EXT>(s, cs, packed, R, X, Fhat, st);
+    return forecast_by_width<float, 4, true, 2, EXT>(s, cs, packed, R, X, Fhat, st);
   }
   if (s.precision == SVDC_PRECISE) {
-    if (kp == 32) return forecast_by_width<bf16_t, 1, true, 1>(s, S, packed, R, Fhat, st);
-    if (kp == 64) return forecast_by_width<bf16_t, 2, true, 2>(s, S, packed, R, Fhat, st);
-    return forecast_by_width<bf16_t, 4, true, 2>(s, S, packed, R, Fhat, st);
+    if (kp == 32) return forecast_by_width<bf16_t, 1, true, 1, EXT>(s, cs, packed, R, X, Fhat, st);
+    if (kp == 64) return forecast_by_width<bf16_t, 2, true, 2, EXT>(s, cs, packed, R, X, Fhat, st);
+    return forecast_by_width<bf16_t, 4, true, 2, EXT>(s, cs, packed, R, X, Fhat, st);
   }
   // at rank <= 32 the split-operand kernel is the faster one (its matrix-core work is hidden anyway)
-  if (kp == 32) return forecast_by_width<bf16_t, 1, true, 1>(s, S, packed, R, Fhat, st);
-  if (kp == 64) return forecast_by_width<bf16_t, 2, false, 2>(s, S, packed, R, Fhat, st);
-  return forecast_by_width<bf16_t, 4, false, 2>(s, S, packed, R, Fhat, st);
+  if (kp == 32) return forecast_by_width<bf16_t, 1, true, 1, EXT>(s, cs, packed, R, X, Fhat, st);
+  if (kp == 64) return forecast_by_width<bf16_t, 2, false, 2, EXT>(s, cs, packed, R, X, Fhat, st);
+  return forecast_by_width<bf16_t, 4, false, 2, EXT>(s, cs, packed, R, X, Fhat, st);
+}
+
+}  // namespace
+
+int32_t launch_forecast_mfma(const svdc_shape& s, const float* S, const void* packed, const void* R,
+                             void* Fhat, hipStream_t st) {
+  CoefStates cs{};
+  cs.s[0] = S;
+  cs.w[0] = 1.f;
+  cs.m = 1;
+  return forecast_dispatch<false>(s, cs, packed, R, nullptr, Fhat, st);
+}
+
+int32_t launch_forecast_combine_mfma(const svdc_shape& s, const CoefStates& cs, const void* packed, const void* R,
+                                     const void* X, void* Out, hipStream_t st) {
+  return forecast_dispatch<true>(s, cs, packed, R, X, Out, st);
 }
 
 }  // namespace svdc

@@ -10,11 +10,25 @@ namespace svdc {
 
 inline int32_t launch_status() { return hipGetLastError() == hipSuccess ? SVDC_OK : SVDC_E_HIP; }
 
+// Coefficient states of a forecaster that is linear in them: C_hat = sum_{i < m} w[i] * s[i] (device pointers,
+// each [B, N, k] float32).  Passed to kernels by value.
+constexpr int kMaxStates = SVDC_MAX_STATES;
+struct CoefStates {
+  const float* s[kMaxStates];
+  float w[kMaxStates];
+  int m;
+};
+
 // ---- general (any-shape) kernels: general_kernels.hip -----------------------
 int32_t launch_full_step_general(const svdc_shape& s, const void* F, const float* V, void* R, float* S,
                                  float* C, float alpha, int init, hipStream_t st);
-int32_t launch_forecast_general(const svdc_shape& s, const float* S, const float* V, const void* R,
-                                void* Fhat, hipStream_t st);
+// Out = (sum_m w_m S_m) V^T + R [+ X]   (X nullable)
+int32_t launch_forecast_general(const svdc_shape& s, const CoefStates& cs, const float* V, const void* R,
+                                const void* X, void* Out, hipStream_t st);
+// rank selection by retained energy and truncation of a fitted basis to per-block ranks
+int32_t launch_select_rank(int B, int k, const float* sigma, const float* fro2, float tau, int32_t* k_star,
+                           int32_t* reached, hipStream_t st);
+int32_t launch_truncate_basis(const svdc_shape& s, float* V, float* sigma, const int32_t* k_star, hipStream_t st);
 
 // ---- matrix-core kernels: mfma_kernels.hip -----------------------------------
 bool mfma_shape_supported(const svdc_shape& s);
@@ -24,6 +38,8 @@ int32_t launch_full_step_mfma(const svdc_shape& s, const void* F, const void* pa
                               float* C, float alpha, int init, hipStream_t st);
 int32_t launch_forecast_mfma(const svdc_shape& s, const float* S, const void* packed, const void* R,
                              void* Fhat, hipStream_t st);
+int32_t launch_forecast_combine_mfma(const svdc_shape& s, const CoefStates& cs, const void* packed, const void* R,
+                                     const void* X, void* Out, hipStream_t st);
 
 // ---- basis fit: fit_kernels.hip ------------------------------------------------
 struct FitPlan {

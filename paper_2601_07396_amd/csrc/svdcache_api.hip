@@ -106,7 +106,66 @@ int32_t svdcache_forecast(const svdc_shape* shape, const float* S, const float* 
     if (!aligned(packed, 256)) return SVDC_E_ALIGN;
     return launch_forecast_mfma(*shape, S, packed, R, Fhat, (hipStream_t)stream);
   }
-  return launch_forecast_general(*shape, S, V, R, Fhat, (hipStream_t)stream);
+  CoefStates cs{};
+  cs.s[0] = S;
+  cs.w[0] = 1.f;
+  cs.m = 1;
+  return launch_forecast_general(*shape, cs, V, R, nullptr, Fhat, (hipStream_t)stream);
+}
+
+int32_t svdcache_select_rank(int32_t B, int32_t k, const float* sigma, const float* fro2, float tau,
+                             int32_t* k_star, int32_t* reached, void* stream) {
+  if (!sigma || !fro2 || !k_star) return SVDC_E_NULL;
+  if (B < 1 || k < 1 || k > 1024) return SVDC_E_SHAPE;
+  if (!(tau > 0.f && tau <= 1.f)) return SVDC_E_PARAM;
+  return launch_select_rank(B, k, sigma, fro2, tau, k_star, reached, (hipStream_t)stream);
+}
+
+int32_t svdcache_truncate_basis(const svdc_shape* shape, float* V, float* sigma, const int32_t* k_star,
+                                void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!V || !k_star) return SVDC_E_NULL;
+  return launch_truncate_basis(*shape, V, sigma, k_star, (hipStream_t)stream);
+}
+
+int32_t svdcache_extrapolation_weights(int32_t order, double offset, double interval, float* weights) {
+  if (!weights) return SVDC_E_NULL;
+  if (order < 0 || order >= SVDC_MAX_STATES || interval == 0.0 || !(interval == interval) || !(offset == offset))
+    return SVDC_E_PARAM;
+  // Lagrange weights at x = offset / interval for the nodes 0, -1, ..., -order
+  const double x = offset / interval;
+  for (int m = 0; m <= order; ++m) {
+    double w = 1.0;
+    for (int i = 0; i <= order; ++i)
+      if (i != m) w *= (x + i) / (double)(i - m);
+    weights[m] = (float)w;
+  }
+  return SVDC_OK;
+}
+
+int32_t svdcache_forecast_combine(const svdc_shape* shape, int32_t num_states, const float* const* S_list,
+                                  const float* weights, const float* V, const void* packed, const void* R,
+                                  const void* X, void* Out, void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!S_list || !weights || !V || !R || !Out) return SVDC_E_NULL;
+  if (num_states < 1 || num_states > SVDC_MAX_STATES) return SVDC_E_PARAM;
+  CoefStates cs{};
+  cs.m = num_states;
+  for (int m = 0; m < num_states; ++m) {
+    if (!S_list[m]) return SVDC_E_NULL;
+    if (!aligned(S_list[m], 16)) return SVDC_E_ALIGN;
+    if (!(weights[m] == weights[m])) return SVDC_E_PARAM;   // NaN
+    cs.s[m] = S_list[m];
+    cs.w[m] = weights[m];
+  }
+  if (!aligned(R, 16) || !aligned(Out, 16) || !aligned(V, 16) || (X && !aligned(X, 16))) return SVDC_E_ALIGN;
+  if (packed && mfma_shape_supported(*shape)) {
+    if (!aligned(packed, 256)) return SVDC_E_ALIGN;
+    return launch_forecast_combine_mfma(*shape, cs, packed, R, X, Out, (hipStream_t)stream);
+  }
+  return launch_forecast_general(*shape, cs, V, R, X, Out, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -90,3 +90,34 @@ def test_calls_refuse_cpu_tensors():
     s = pkg.make_shape(F, 8)
     with pytest.raises(RuntimeError, match="GPU"):
         pkg.svdcache_forecast(s, torch.zeros(1, 64, 8), torch.zeros(1, 64, 8), None, F, F)
+
+
+def test_extrapolation_weights_is_a_host_function(lib):
+    """No GPU work behind it: callable anywhere; checked against the oracle's rational-arithmetic version."""
+    import numpy as np
+    from oracle import ref_extrapolation_weights
+    for order in range(4):
+        for off, itv in [(1, 6), (5, 6), (2.5, 3), (0, 4), (-4, 4), (7, 2)]:
+            got = pkg.svdcache_extrapolation_weights(order, off, itv)
+            want = ref_extrapolation_weights(order, off, itv).astype(np.float32)
+            assert np.allclose(got, want, rtol=2e-7, atol=1e-7), (order, off, itv)
+    w = (C.c_float * 4)()
+    assert lib.svdcache_extrapolation_weights(1, 1.0, 6.0, None) == -1
+    assert lib.svdcache_extrapolation_weights(4, 1.0, 6.0, w) == -5      # more states than SVDC_MAX_STATES
+    assert lib.svdcache_extrapolation_weights(-1, 1.0, 6.0, w) == -5
+    assert lib.svdcache_extrapolation_weights(1, 1.0, 0.0, w) == -5
+
+
+def test_widened_entry_points_validate_on_the_host(lib):
+    s = Shape(1, 16, 64, 4, 64, 16 * 64, 0, 0)
+    fake = C.c_void_p(256)
+    assert lib.svdcache_select_rank(1, 4, None, fake, 0.85, fake, None, None) == -1
+    assert lib.svdcache_select_rank(0, 4, fake, fake, 0.85, fake, None, None) == -2
+    assert lib.svdcache_select_rank(1, 4, fake, fake, 0.0, fake, None, None) == -5
+    assert lib.svdcache_truncate_basis(C.byref(s), None, None, fake, None) == -1
+    ptrs = (C.c_void_p * 1)(256)
+    w = (C.c_float * 1)(1.0)
+    assert lib.svdcache_forecast_combine(C.byref(s), 0, ptrs, w, fake, None, fake, None, fake, None) == -5
+    assert lib.svdcache_forecast_combine(C.byref(s), 1, None, w, fake, None, fake, None, fake, None) == -1
+    bad = (C.c_void_p * 1)(260)                                           # not 16-byte aligned
+    assert lib.svdcache_forecast_combine(C.byref(s), 1, bad, w, fake, None, fake, None, fake, None) == -4

@@ -1,0 +1,235 @@
+"""GPU parity of the entry points beyond the three basic ones: rank selection by retained energy,
+per-block rank truncation, and cached steps with forecasters that are linear in stored states."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2601_07396_amd as pkg
+from oracle import (ref_full_step, ref_select_rank, ref_truncate_basis, ref_forecast_combine,
+                    ref_extrapolation_weights, ref_fit_basis)
+from synth import WORKLOADS, FeatureStream
+from util import TOL, to_np, assert_close
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _problem(B, N, D, k, dtype, seed, nstates=1):
+    g = torch.Generator().manual_seed(seed)
+    R = torch.randn(B, N, D, generator=g).to(dtype)
+    X = torch.randn(B, N, D, generator=g).to(dtype)
+    V = torch.linalg.qr(torch.randn(B, D, k, generator=g, dtype=torch.float64))[0].float().contiguous()
+    S = [3.0 * torch.randn(B, N, k, generator=g) for _ in range(nstates)]
+    return R, X, V, S
+
+
+# ------------------------------------------------------------------ rank selection (Eq. 6)
+
+def test_select_rank_matches_oracle_exactly():
+    g = torch.Generator().manual_seed(3)
+    B, k = 57, 32
+    sig = torch.sort(torch.rand(B, k, generator=g) * 4 + 0.01, dim=1, descending=True)[0]
+    energy = (sig.double() ** 2).sum(1)
+    fro2 = (energy * (1.0 + 0.4 * torch.rand(B, generator=g).double())).float()     # part of the energy is outside
+    fro2[::7] = energy[::7].float()                                                  # ... or none of it
+    ks = torch.empty(B, dtype=torch.int32, device=DEV)
+    ok = torch.empty(B, dtype=torch.int32, device=DEV)
+    for tau in (0.05, 0.5, 0.85, 0.95, 1.0):
+        pkg.svdcache_select_rank(sig.to(DEV), fro2.to(DEV), tau, ks, ok)
+        torch.cuda.synchronize()
+        for b in range(B):
+            want = ref_select_rank(sig[b].numpy(), float(fro2[b]), tau)
+            assert (int(ks[b]), bool(ok[b])) == want, (tau, b)
+    # the flag is optional
+    pkg.svdcache_select_rank(sig.to(DEV), fro2.to(DEV), 0.85, ks, None)
+    torch.cuda.synchronize()
+    assert all(int(ks[b]) == ref_select_rank(sig[b].numpy(), float(fro2[b]), 0.85)[0] for b in range(B))
+
+
+def test_select_rank_on_a_fitted_basis():
+    """tau-rule on the GPU fit of the tiny configuration against the rule applied to the exact spectrum."""
+    wl = WORKLOADS["tiny"]
+    F = torch.stack([FeatureStream(wl, b).at(0) for b in range(wl.B)])
+    k = 32
+    V, sigma, fro2 = pkg.fit_basis(F.to(DEV), k, q=8)
+    ks = torch.empty(wl.B, dtype=torch.int32, device=DEV)
+    ok = torch.empty(wl.B, dtype=torch.int32, device=DEV)
+    for tau in (0.5, 0.85, 0.99):
+        pkg.svdcache_select_rank(sigma, fro2, tau, ks, ok)
+        torch.cuda.synchronize()
+        for b in range(wl.B):
+            _, s_exact, fr = ref_fit_basis(to_np(F[b]), k)
+            want = ref_select_rank(s_exact.astype(np.float32), fr, tau)
+            frac = np.cumsum(s_exact ** 2) / fr
+            if np.min(np.abs(frac - tau)) > 1e-4:        # away from a tie the decision is unique
+                assert (int(ks[b]), bool(ok[b])) == want, (tau, b)
+
+
+def test_select_rank_and_truncate_reject_bad_arguments():
+    sig = torch.ones(2, 4, device=DEV)
+    fro = torch.ones(2, device=DEV)
+    ks = torch.empty(2, dtype=torch.int32, device=DEV)
+    for tau in (0.0, -1.0, 1.5, float("nan")):
+        with pytest.raises(pkg.SvdcError) as e:
+            pkg.svdcache_select_rank(sig, fro, tau, ks, None)
+        assert e.value.code == -5
+    with pytest.raises(pkg.SvdcError) as e:
+        pkg.svdcache_select_rank(sig, fro, 0.5, None, None)
+    assert e.value.code == -1
+
+
+# ------------------------------------------------------------------ per-block ranks in one launch
+
+@pytest.mark.parametrize("dtype,D", [(torch.float32, 64), (torch.bfloat16, 72), (torch.bfloat16, 256),
+                                     (torch.float32, 256)], ids=["f32-general", "bf16-general", "bf16-mfma", "f32-mfma"])
+def test_truncated_basis_gives_per_block_rank(dtype, D):
+    store = "f32" if dtype == torch.float32 else "bf16"
+    B, N, k = 3, 100, 16
+    g = torch.Generator().manual_seed(D)
+    F = torch.randn(B, N, D, generator=g).to(dtype)
+    V = torch.linalg.qr(torch.randn(B, D, k, generator=g, dtype=torch.float64))[0].float().contiguous()
+    sigma = torch.arange(k, 0, -1).float().repeat(B, 1)
+    k_star = torch.tensor([16, 5, 1], dtype=torch.int32)
+    Vd, sd = V.to(DEV), sigma.to(DEV)
+    shape = pkg.make_shape(F, k)
+    pkg.svdcache_truncate_basis(shape, Vd, sd, k_star.to(DEV))
+    torch.cuda.synchronize()
+    for b in range(B):
+        Vt, st = ref_truncate_basis(to_np(V[b]), to_np(sigma[b]), int(k_star[b]))
+        assert np.array_equal(to_np(Vd[b]), Vt) and np.array_equal(to_np(sd[b]), st)
+    pk = pkg.pack_basis(shape, Vd)
+    assert (pk is not None) == (D == 256)
+    Fd = F.to(DEV)
+    R = torch.empty_like(Fd)
+    S = torch.empty(B, N, k, device=DEV)
+    Cc = torch.empty_like(S)
+    pkg.svdcache_full_step(shape, Fd, Vd, pk, R, S, Cc, 0.5, True)
+    torch.cuda.synchronize()
+    for b in range(B):
+        ks = int(k_star[b])
+        Rr, Sr, Cr = ref_full_step(to_np(F[b]), to_np(V[b][:, :ks]), None, 0.5, True, store)   # the rank-k* step
+        assert_close(to_np(R[b]), Rr, store, f"R[{b}]", floor_of=to_np(F[b]))
+        assert_close(to_np(Cc[b][:, :ks]), Cr, "f32", f"C[{b}]")
+        assert not to_np(Cc[b][:, ks:]).any() and not to_np(S[b][:, ks:]).any()
+    # sigma is optional
+    pkg.svdcache_truncate_basis(shape, Vd, None, torch.zeros(B, dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    assert not Vd.any()
+
+
+# ------------------------------------------------------------------ forecasters linear in stored states
+
+def test_extrapolation_weights_host_function():
+    for order in range(4):
+        for off, itv in [(1, 6), (5, 6), (2.5, 3), (0, 4), (-4, 4)]:
+            got = pkg.svdcache_extrapolation_weights(order, off, itv)
+            want = ref_extrapolation_weights(order, off, itv)
+            assert np.allclose(got, want.astype(np.float32), rtol=2e-7, atol=1e-7), (order, off, itv)
+    for bad in [(-1, 1, 6), (4, 1, 6), (1, 1, 0)]:
+        with pytest.raises(pkg.SvdcError) as e:
+            pkg.svdcache_extrapolation_weights(*bad)
+        assert e.value.code == -5
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("B,N,D,k", [(2, 67, 72, 5), (1, 130, 200, 17),                       # general kernels
+                                     (2, 150, 256, 32), (1, 77, 512, 8), (1, 140, 512, 128),   # matrix-core kernels
+                                     (1, 150, 3072, 32), (1, 70, 3072, 64), (1, 33, 1024, 20)])
+def test_forecast_combine(dtype, B, N, D, k):
+    store = "f32" if dtype == torch.float32 else "bf16"
+    R, X, V, S = _problem(B, N, D, k, dtype, seed=N + D + k, nstates=4)
+    shape = pkg.make_shape(R, k)
+    Rd, Xd, Vd, Sd = R.to(DEV), X.to(DEV), V.to(DEV), [s.to(DEV) for s in S]
+    pk = pkg.pack_basis(shape, Vd)
+    cases = [(1, [1.0], False), (2, [1.5, -0.5], False), (3, [1.875, -1.25, 0.375], True),
+             (4, [0.25, -2.0, 3.0, 0.125], True), (1, [0.75], True)]
+    for m, w, use_x in cases:
+        out = torch.full_like(Rd, 7.0)
+        pkg.svdcache_forecast_combine(shape, Sd[:m], w, Vd, pk, Rd, Xd if use_x else None, out)
+        torch.cuda.synchronize()
+        for b in range(B):
+            want = ref_forecast_combine([to_np(s[b]) for s in S[:m]], w, to_np(V[b]), to_np(R[b]),
+                                        to_np(X[b]) if use_x else None, store)
+            assert_close(to_np(out[b]), want, store, f"combine m={m} x={use_x} block {b}")
+    # one state with weight one is the basic cached step, bit for bit
+    a, b_ = torch.empty_like(Rd), torch.empty_like(Rd)
+    pkg.svdcache_forecast(shape, Sd[0], Vd, pk, Rd, a)
+    pkg.svdcache_forecast_combine(shape, Sd[:1], [1.0], Vd, pk, Rd, None, b_)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b_)
+    # in place: the output may be the residual buffer or the added tensor
+    want = torch.empty_like(Rd)
+    pkg.svdcache_forecast_combine(shape, Sd[:2], [1.5, -0.5], Vd, pk, Rd, Xd, want)
+    r2, x2 = Rd.clone(), Xd.clone()
+    pkg.svdcache_forecast_combine(shape, Sd[:2], [1.5, -0.5], Vd, pk, r2, Xd, r2)
+    pkg.svdcache_forecast_combine(shape, Sd[:2], [1.5, -0.5], Vd, pk, Rd, x2, x2)
+    torch.cuda.synchronize()
+    assert torch.equal(r2, want) and torch.equal(x2, want)
+
+
+def test_forecast_combine_rejects_bad_arguments():
+    R, X, V, S = _problem(1, 16, 64, 4, torch.float32, seed=1, nstates=5)
+    shape = pkg.make_shape(R, 4)
+    Rd, Vd, Sd = R.to(DEV), V.to(DEV), [s.to(DEV) for s in S]
+    out = torch.empty_like(Rd)
+    for m in (0, 5):
+        with pytest.raises(pkg.SvdcError) as e:
+            pkg.svdcache_forecast_combine(shape, Sd[:m], [1.0] * m, Vd, None, Rd, None, out)
+        assert e.value.code == -5
+    with pytest.raises(pkg.SvdcError) as e:
+        pkg.svdcache_forecast_combine(shape, Sd[:2], [1.0, float("nan")], Vd, None, Rd, None, out)
+    assert e.value.code == -5
+
+
+def test_linear_trend_forecast_tracks_a_drifting_feature():
+    """A feature whose principal coefficients drift linearly in time, observed at two full steps: the order-1
+    weights on the two stored coefficient sets forecast the later feature; plain reuse of the last one does not."""
+    B, N, D, k = 1, 200, 256, 32
+    g = torch.Generator().manual_seed(11)
+    V = torch.linalg.qr(torch.randn(B, D, k, generator=g, dtype=torch.float64))[0].float().contiguous()
+    C0, dC = 4 * torch.randn(B, N, k, generator=g), 0.3 * torch.randn(B, N, k, generator=g)
+    E = 0.05 * torch.randn(B, N, D, generator=g)
+    E = E - (E @ V) @ V.transpose(1, 2)                       # residual part, orthogonal to the basis
+    feat = lambda t: ((C0 + t * dC) @ V.transpose(1, 2) + E).to(torch.bfloat16)
+    shape = pkg.make_shape(feat(0), k)
+    Vd = V.to(DEV)
+    pk = pkg.pack_basis(shape, Vd)
+    R = torch.empty(B, N, D, device=DEV, dtype=torch.bfloat16)
+    S = torch.empty(B, N, k, device=DEV)
+    Cs = [torch.empty_like(S), torch.empty_like(S)]
+    pkg.svdcache_full_step(shape, feat(0).to(DEV), Vd, pk, R, S, Cs[0], 1.0, True)
+    pkg.svdcache_full_step(shape, feat(6).to(DEV), Vd, pk, R, S, Cs[1], 1.0, False)
+    w = pkg.svdcache_extrapolation_weights(1, 3, 6)
+    trend, reuse = torch.empty_like(R), torch.empty_like(R)
+    pkg.svdcache_forecast_combine(shape, [Cs[1], Cs[0]], w, Vd, pk, R, None, trend)
+    pkg.svdcache_forecast(shape, Cs[1], Vd, pk, R, reuse)
+    torch.cuda.synchronize()
+    target = feat(9).float()
+    err = lambda x: float((x.float().cpu() - target).norm() / target.norm())
+    assert err(trend) <= 1e-2 and err(reuse) >= 5 * err(trend)
+
+
+def test_flux57_full_size_combine_sampled_rows():
+    """The extended cached step in the launch configuration of the benchmark (57 x 4608 x 3072 bf16, k = 32):
+    two states, an added tensor, sampled rows against the oracle."""
+    wl = WORKLOADS["flux57"]
+    B = wl.B
+    R = torch.empty(B, wl.N, wl.D, device=DEV, dtype=torch.bfloat16)
+    for b in range(B):
+        R[b] = FeatureStream(wl, b, device=DEV).at(0)
+    X = R.roll(1, dims=0).contiguous()
+    g = torch.Generator(device=DEV).manual_seed(5)
+    S = [torch.randn(B, wl.N, wl.k, device=DEV, generator=g) for _ in range(2)]
+    V = torch.linalg.qr(torch.randn(B, wl.D, wl.k, device=DEV, generator=g))[0].contiguous()
+    shape = pkg.make_shape(R, wl.k)
+    pk = pkg.pack_basis(shape, V)
+    out = torch.empty_like(R)
+    w = [1.5, -0.5]
+    pkg.svdcache_forecast_combine(shape, S, w, V, pk, R, X, out)
+    torch.cuda.synchronize()
+    gc = torch.Generator().manual_seed(6)
+    for b in (0, 31, 56):
+        rows = torch.cat([torch.tensor([0, 15, 16, wl.N - 1]), torch.randint(0, wl.N, (64,), generator=gc)]).unique()
+        want = ref_forecast_combine([to_np(s[b][rows]) for s in S], w, to_np(V[b]), to_np(R[b][rows]),
+                                    to_np(X[b][rows]), "bf16")
+        assert_close(to_np(out[b][rows]), want, "bf16", f"combine block {b}")
