@@ -104,6 +104,8 @@ def main():
                     help="number of distinct full-step feature tensors kept in HBM (0 = one per full step, "
                          "capped so that everything fits); the full steps cycle through them")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-widened", action="store_true",
+                    help="skip the short timing of the entry points beyond fit / full step / cached step")
     ap.add_argument("--fast", action="store_true", help="SVDC_FAST arithmetic (single bf16 operands)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling profiler byte counters)")
@@ -246,6 +248,44 @@ def main():
                 "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((wl.name, k, bool(args.fast), dom_kernel)) if B == WORKLOADS[wl.name].B else None,
                 "avg_launch_ms": kernels[dom]["avg_ms"], "algorithmic_bytes_per_launch": kernels[dom]["bytes"]}
 
+    # ---- entry points beyond the three basic ones (outside the timed step; reported separately) -------
+    widened = None
+    if not args.no_widened:
+        def timed(fn, reps=10):
+            fn()
+            torch.cuda.synchronize()
+            a, bb = ev(), ev()
+            a.record()
+            for _ in range(reps):
+                fn()
+            bb.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(bb) / reps
+        eb = wl.elem_bytes
+        S2 = torch.randn_like(S)
+        X = feats[1 % n_inputs]
+        w2 = pkg.svdcache_extrapolation_weights(1, 3, wl.interval)
+        k_star = torch.empty(B, dtype=torch.int32, device=dev)
+        reached = torch.empty(B, dtype=torch.int32, device=dev)
+        V2 = V.clone()
+        t_comb = timed(lambda: pkg.svdcache_forecast_combine(shape, [S, S2], w2, V, packed, R, None, Fh))
+        t_add = timed(lambda: pkg.svdcache_forecast_combine(shape, [S, S2], w2, V, packed, R, X, Fh))
+        t_sel = timed(lambda: pkg.svdcache_select_rank(sigma, fro2, 0.85, k_star, reached))
+        t_trunc = timed(lambda: pkg.svdcache_truncate_basis(shape, V2, None, k_star))
+        by_comb = B * (2 * N * D * eb + 2 * N * k * 4 + D * k * 4)
+        by_add = by_comb + B * N * D * eb
+        widened = {
+            "svdcache_forecast_combine(2 states)": {"avg_ms": t_comb, "bytes": by_comb, "GBps": by_comb / t_comb / 1e6,
+                                                    "frac_of_hbm_peak": by_comb / t_comb / 1e6 / HBM_PEAK_GBS},
+            "svdcache_forecast_combine(2 states, added tensor)": {
+                "avg_ms": t_add, "bytes": by_add, "GBps": by_add / t_add / 1e6,
+                "frac_of_hbm_peak": by_add / t_add / 1e6 / HBM_PEAK_GBS},
+            "svdcache_select_rank": {"avg_ms": t_sel, "k_star_min_max": [int(k_star.min()), int(k_star.max())],
+                                     "reached_all": bool(reached.all())},
+            "svdcache_truncate_basis": {"avg_ms": t_trunc},
+        }
+        del S2, V2
+
     # ---- CPU oracle on a bounded sample ----------------------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -282,7 +322,7 @@ def main():
                                f"every {wl.interval} (per step: 1 fit + {n_full} full steps + {n_cached} cached steps)",
                    "alpha": wl.alpha, "blocks": B, "N": N, "D": D, "k": k},
         "frac_of_hbm_peak": value / HBM_PEAK_GBS,
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "widened": widened,
         "input_generation_s": gen_s, "distinct_full_step_inputs": n_inputs,
     }
     print(json.dumps(out))
