@@ -259,6 +259,48 @@ def ref_full_step_residual_ema(F, V, S_prev, R_prev, alpha: float, alpha_r: floa
 
 
 # ----------------------------------------------------------------------------
+# basis reuse across prompts and re-basing (Sec. 3.3, Fig. 1(b))
+# ----------------------------------------------------------------------------
+
+
+def ref_basis_overlap(V_old, V_new):
+    """M = V_old^T V_new  (k_old x k_new): entry (i, j) is the cosine between the
+    i-th old and the j-th new basis direction (both sets orthonormal)."""
+    return np.asarray(V_old, dtype=np.float64).T @ np.asarray(V_new, dtype=np.float64)
+
+
+def ref_rebase_state(S, M, store: str = "f64"):
+    """Coefficient state carried over to a refitted basis.  The principal part the
+    state stands for is S V_old^T; its coefficients in the new basis are
+    (S V_old^T) V_new = S (V_old^T V_new) = S M.  If both bases span the same
+    subspace nothing is lost: S_new V_new^T = S V_old^T."""
+    out = np.asarray(S, dtype=np.float64) @ np.asarray(M, dtype=np.float64)
+    return _round_f32(out, store)
+
+
+def ref_basis_similarity(V_a, sigma_a, V_b, sigma_b):
+    """Similarity of two fitted bases as in Fig. 1(b): cosine similarity times
+    magnitude similarity, for each pair of right singular vectors and for the two
+    singular-value vectors.  Reading taken here (the caption gives no formula):
+    cosine = |<a, b>| / (|a| |b|) (singular vectors are defined up to sign, so the
+    absolute value), magnitude similarity = min(|a|, |b|) / max(|a|, |b|).
+    Returns (sim_dir [k], sim_sigma)."""
+    Va, Vb = np.asarray(V_a, dtype=np.float64), np.asarray(V_b, dtype=np.float64)
+    sa, sb = np.asarray(sigma_a, dtype=np.float64), np.asarray(sigma_b, dtype=np.float64)
+
+    def sim(a, b, signed):
+        na, nb = np.sqrt(np.sum(a * a)), np.sqrt(np.sum(b * b))
+        if na == 0.0 or nb == 0.0:
+            return 0.0
+        dot = np.sum(a * b)
+        cos = (dot if signed else abs(dot)) / (na * nb)
+        return cos * min(na, nb) / max(na, nb)
+
+    sim_dir = np.array([sim(Va[:, j], Vb[:, j], False) for j in range(Va.shape[1])])
+    return sim_dir, sim(sa, sb, True)
+
+
+# ----------------------------------------------------------------------------
 # a whole sampling trajectory for one block
 # ----------------------------------------------------------------------------
 

@@ -400,3 +400,74 @@ def check_residual_ema(full_ema, full):
     for _ in range(4):
         Rc, _, _ = full_ema(F, V, S0, Rc, 0.3, 0.4, False, "f64")
     assert np.abs(Rc - R_new).max() <= 1e-13
+
+
+# ---------------------------------------------------------------------------
+# basis reuse and re-basing (Sec. 3.3, Fig. 1(b))
+# ---------------------------------------------------------------------------
+
+def check_rebase(overlap, rebase, forecast):
+    r = rng(61)
+    n, d, k = 40, 24, 6
+    V = random_orthonormal(r, d, k)
+    S = r.standard_normal((n, k))
+    R = r.standard_normal((n, d))
+    # same basis: M = I, state unchanged
+    M = overlap(V, V)
+    assert np.abs(M - np.eye(k)).max() <= 1e-14
+    assert np.abs(rebase(S, M) - S).max() <= 1e-13
+    # a rotation inside the same subspace changes the coefficients but not the feature they stand for
+    Q = random_orthonormal(r, k, k)
+    V2 = V @ Q
+    M = overlap(V, V2)
+    assert np.abs(M - Q).max() <= 1e-13
+    S2 = rebase(S, M)
+    assert np.abs(S2 - S).max() > 0.1
+    assert np.abs(forecast(S2, V2, R, "f64") - forecast(S, V, R, "f64")).max() <= 1e-12
+    # entry (i, j) is the inner product of old direction i with new direction j (not the transpose)
+    W = random_orthonormal(r, d, k)
+    M = overlap(V, W)
+    assert abs(M[1, 4] - float(V[:, 1] @ W[:, 4])) <= 1e-14 and abs(M[1, 4] - M[4, 1]) > 1e-3
+    # general new basis: the new coefficients are those of the orthogonal projection of S V^T onto span(W)
+    P_old = S @ V.T
+    best = np.linalg.lstsq(W, P_old.T, rcond=None)[0].T          # argmin_X |X W^T - P_old|
+    assert np.abs(rebase(S, M) - best).max() <= 1e-12
+    # a basis orthogonal to the old one carries nothing over
+    full = random_orthonormal(r, d, 2 * k)
+    assert np.abs(rebase(S, overlap(full[:, :k], full[:, k:]))).max() <= 1e-13
+
+
+def check_basis_similarity(similarity):
+    r = rng(62)
+    d, k = 30, 5
+    V = random_orthonormal(r, d, k)
+    s = np.array([9.0, 5.0, 3.0, 2.0, 1.0])
+    sd, ss = similarity(V, s, V, s)
+    assert np.abs(sd - 1).max() <= 1e-14 and abs(ss - 1) <= 1e-14
+    # a sign flip of a singular vector changes nothing; scaling the spectrum by c costs min(c, 1/c)
+    V2 = V.copy()
+    V2[:, 2] *= -1
+    sd, ss = similarity(V, s, V2, 0.5 * s)
+    assert np.abs(sd - 1).max() <= 1e-14 and abs(ss - 0.5) <= 1e-14
+    sd, ss = similarity(V, s, V2, 4.0 * s)
+    assert abs(ss - 0.25) <= 1e-14
+    # a direction rotated by the angle phi inside a plane has similarity cos(phi)
+    phi = 0.3
+    V3 = V.copy()
+    V3[:, 0] = np.cos(phi) * V[:, 0] + np.sin(phi) * V[:, 1]
+    sd, _ = similarity(V, s, V3, s)
+    assert abs(sd[0] - np.cos(phi)) <= 1e-14 and np.abs(sd[1:] - 1).max() <= 1e-14
+    # orthogonal directions: zero; a non-unit vector pays its norm ratio
+    full = random_orthonormal(r, d, 2 * k)
+    sd, _ = similarity(full[:, :k], s, full[:, k:], s)
+    assert np.abs(sd).max() <= 1e-14
+    V4 = V.copy()
+    V4[:, 1] *= 0.8
+    sd, _ = similarity(V, s, V4, s)
+    assert abs(sd[1] - 0.8) <= 1e-14
+    # different spectra: the textbook cosine times the norm ratio
+    t = np.array([8.0, 6.0, 1.0, 1.0, 0.5])
+    _, ss = similarity(V, s, V, t)
+    cos = float(s @ t) / (np.linalg.norm(s) * np.linalg.norm(t))
+    assert abs(ss - cos * min(np.linalg.norm(s), np.linalg.norm(t)) / max(np.linalg.norm(s), np.linalg.norm(t))) <= 1e-14
+    assert ss < 1

@@ -177,3 +177,40 @@ def test_residual_ema_mutants_are_caught(mut):
         return (1 - alpha_r) * R_prev + alpha_r * R_new, S, C
     with pytest.raises(AssertionError):
         pins.check_residual_ema(full_ema, ref_full_step)
+
+
+@pytest.mark.parametrize("mut", ["overlap_transposed", "rebase_transposed", "rebase_left_multiply_pinv"])
+def test_rebase_mutants_are_caught(mut):
+    def overlap(Va, Vb):
+        return (Vb.T @ Va) if mut == "overlap_transposed" else (Va.T @ Vb)
+
+    def rebase(S, M, store="f64"):
+        if mut == "rebase_transposed":
+            return S @ M.T
+        if mut == "rebase_left_multiply_pinv":
+            return S @ np.linalg.pinv(M)
+        return S @ M
+    with pytest.raises(AssertionError):
+        pins.check_rebase(overlap, rebase, ref_forecast)
+
+
+@pytest.mark.parametrize("mut", ["signed_cosine", "no_magnitude_term", "magnitude_ratio_inverted", "rows_not_columns"])
+def test_basis_similarity_mutants_are_caught(mut):
+    def similarity(Va, sa, Vb, sb):
+        def sim(a, b, signed):
+            na, nb = np.linalg.norm(a), np.linalg.norm(b)
+            if na == 0 or nb == 0:
+                return 0.0
+            dot = float(a @ b)
+            cos = (dot if (signed or mut == "signed_cosine") else abs(dot)) / (na * nb)
+            mag = min(na, nb) / max(na, nb)
+            if mut == "no_magnitude_term":
+                mag = 1.0
+            if mut == "magnitude_ratio_inverted":
+                mag = max(na, nb) / min(na, nb)
+            return cos * mag
+        if mut == "rows_not_columns":
+            return np.array([sim(Va[j], Vb[j], False) for j in range(Va.shape[1])]), sim(sa, sb, True)
+        return np.array([sim(Va[:, j], Vb[:, j], False) for j in range(Va.shape[1])]), sim(sa, sb, True)
+    with pytest.raises(AssertionError):
+        pins.check_basis_similarity(similarity)

@@ -81,3 +81,13 @@ def test_forecast_combine():
 def test_residual_ema():
     from oracle import ref_full_step_residual_ema
     pins.check_residual_ema(ref_full_step_residual_ema, ref_full_step)
+
+
+def test_rebase_state():
+    from oracle import ref_basis_overlap, ref_rebase_state
+    pins.check_rebase(ref_basis_overlap, ref_rebase_state, ref_forecast)
+
+
+def test_basis_similarity():
+    from oracle import ref_basis_similarity
+    pins.check_basis_similarity(ref_basis_similarity)
