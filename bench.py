@@ -272,6 +272,14 @@ def main():
         t_add = timed(lambda: pkg.svdcache_forecast_combine(shape, [S, S2], w2, V, packed, R, X, Fh))
         t_sel = timed(lambda: pkg.svdcache_select_rank(sigma, fro2, 0.85, k_star, reached))
         t_trunc = timed(lambda: pkg.svdcache_truncate_basis(shape, V2, None, k_star))
+        Mo = torch.empty(B, k, k, device=dev)
+        S3 = torch.empty_like(S)
+        sim_dir = torch.empty(B, k, device=dev)
+        sim_sig = torch.empty(B, device=dev)
+        rebase_ok = k <= 128
+        t_ov = timed(lambda: pkg.svdcache_basis_overlap(shape, V, V2, Mo)) if rebase_ok else None
+        t_rb = timed(lambda: pkg.svdcache_rebase_state(shape, Mo, S, S3)) if rebase_ok else None
+        t_sim = timed(lambda: pkg.svdcache_basis_similarity(shape, V, sigma, V2, sigma, sim_dir, sim_sig))
         by_comb = B * (2 * N * D * eb + 2 * N * k * 4 + D * k * 4)
         by_add = by_comb + B * N * D * eb
         widened = {
@@ -283,8 +291,12 @@ def main():
             "svdcache_select_rank": {"avg_ms": t_sel, "k_star_min_max": [int(k_star.min()), int(k_star.max())],
                                      "reached_all": bool(reached.all())},
             "svdcache_truncate_basis": {"avg_ms": t_trunc},
+            "svdcache_basis_overlap": {"avg_ms": t_ov},
+            "svdcache_rebase_state": {"avg_ms": t_rb, "bytes": B * (2 * N * k + k * k) * 4,
+                                      "GBps": B * (2 * N * k + k * k) * 4 / t_rb / 1e6 if t_rb else None},
+            "svdcache_basis_similarity": {"avg_ms": t_sim},
         }
-        del S2, V2
+        del S2, V2, S3
 
     # ---- CPU oracle on a bounded sample ----------------------------------------------------------
     cpu = None

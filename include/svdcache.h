@@ -196,6 +196,27 @@ int32_t svdcache_forecast_combine(const svdc_shape* shape, int32_t num_states, c
                                   const float* weights, const float* V, const void* packed, const void* R,
                                   const void* X, void* Out, void* stream);
 
+/* Basis reuse and re-basing (Sec. 3.3: one basis, fitted once, serves other prompts; Fig. 1(b): it stays
+ * similar across prompts).  When a basis IS refitted, the coefficient state fitted to the old basis is carried
+ * over instead of being dropped:
+ *
+ * svdcache_basis_overlap   M[b] = V_old[b]^T V_new[b]           ([B,k,k] float32, row i = old direction i)
+ * svdcache_rebase_state    S_out[b] = S_in[b] M[b]              the coefficients of S_in V_old^T in the new basis
+ *                                                               (exact when both bases span the same subspace)
+ * svdcache_basis_similarity  cosine similarity times magnitude similarity, as plotted in Fig. 1(b):
+ *                          sim_dir[b][j] = |<a,b>| / (|a||b|) * min(|a|,|b|) / max(|a|,|b|) for a, b = column j of
+ *                          V_a[b], V_b[b]; sim_sigma[b] the same (signed cosine) for the singular-value vectors.
+ *                          Values above about 0.8 mean the cached basis can be reused.
+ * The shape argument supplies B, D, k (overlap, similarity) or B, N, k (rebase); k <= 128 for overlap and rebase.
+ * S_out may be S_in.  sim_sigma (and then sigma_a, sigma_b) may be NULL. */
+int32_t svdcache_basis_overlap(const svdc_shape* shape, const float* V_old, const float* V_new, float* M,
+                               void* stream);
+int32_t svdcache_rebase_state(const svdc_shape* shape, const float* M, const float* S_in, float* S_out,
+                              void* stream);
+int32_t svdcache_basis_similarity(const svdc_shape* shape, const float* V_a, const float* sigma_a,
+                                  const float* V_b, const float* sigma_b, float* sim_dir, float* sim_sigma,
+                                  void* stream);
+
 #ifdef __cplusplus
 }
 #endif

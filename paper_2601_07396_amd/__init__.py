@@ -11,7 +11,8 @@ from .binding import (
     svdcache_version, svdcache_strerror, svdcache_fit_workspace_bytes, svdcache_packed_basis_bytes,
     svdcache_has_mfma_path, svdcache_fit_basis, svdcache_pack_basis, svdcache_full_step, svdcache_forecast,
     svdcache_select_rank, svdcache_truncate_basis, svdcache_extrapolation_weights, svdcache_forecast_combine,
-    make_shape, fit_basis, pack_basis,
+    svdcache_basis_overlap, svdcache_rebase_state, svdcache_basis_similarity,
+    make_shape, fit_basis, pack_basis, save_basis, load_basis,
 )
 
 __all__ = [
@@ -19,5 +20,6 @@ __all__ = [
     "svdcache_version", "svdcache_strerror", "svdcache_fit_workspace_bytes", "svdcache_packed_basis_bytes",
     "svdcache_has_mfma_path", "svdcache_fit_basis", "svdcache_pack_basis", "svdcache_full_step",
     "svdcache_forecast", "svdcache_select_rank", "svdcache_truncate_basis", "svdcache_extrapolation_weights",
-    "svdcache_forecast_combine", "make_shape", "fit_basis", "pack_basis",
+    "svdcache_forecast_combine", "svdcache_basis_overlap", "svdcache_rebase_state", "svdcache_basis_similarity",
+    "make_shape", "fit_basis", "pack_basis", "save_basis", "load_basis",
 ]

@@ -48,6 +48,10 @@ EXPORTS = {
                                          C.c_void_p, C.c_void_p]),
     "svdcache_truncate_basis": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "svdcache_extrapolation_weights": (C.c_int32, [C.c_int32, C.c_double, C.c_double, C.POINTER(C.c_float)]),
+    "svdcache_basis_overlap": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "svdcache_rebase_state": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "svdcache_basis_similarity": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_void_p]),
     "svdcache_forecast_combine": (C.c_int32, [C.POINTER(Shape), C.c_int32, C.POINTER(C.c_void_p),
                                               C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                               C.c_void_p, C.c_void_p]),
@@ -199,6 +203,25 @@ def svdcache_forecast_combine(shape: Shape, S_list, weights, V, packed, R, X, Ou
     _check(rc, "svdcache_forecast_combine")
 
 
+def svdcache_basis_overlap(shape: Shape, V_old, V_new, M):
+    _need_gpu(V_old, V_new, M)
+    rc = load_library().svdcache_basis_overlap(C.byref(shape), _ptr(V_old), _ptr(V_new), _ptr(M), _stream())
+    _check(rc, "svdcache_basis_overlap")
+
+
+def svdcache_rebase_state(shape: Shape, M, S_in, S_out):
+    _need_gpu(M, S_in, S_out)
+    rc = load_library().svdcache_rebase_state(C.byref(shape), _ptr(M), _ptr(S_in), _ptr(S_out), _stream())
+    _check(rc, "svdcache_rebase_state")
+
+
+def svdcache_basis_similarity(shape: Shape, V_a, sigma_a, V_b, sigma_b, sim_dir, sim_sigma):
+    _need_gpu(V_a, sigma_a, V_b, sigma_b, sim_dir, sim_sigma)
+    rc = load_library().svdcache_basis_similarity(C.byref(shape), _ptr(V_a), _ptr(sigma_a), _ptr(V_b), _ptr(sigma_b),
+                                                  _ptr(sim_dir), _ptr(sim_sigma), _stream())
+    _check(rc, "svdcache_basis_similarity")
+
+
 # ---- conveniences that only allocate (torch owns the memory) ------------------------------------
 
 def fit_basis(F: torch.Tensor, k: int, p: int = 0, q: int = 0, seed: int = 0):
@@ -213,6 +236,30 @@ def fit_basis(F: torch.Tensor, k: int, p: int = 0, q: int = 0, seed: int = 0):
         raise SvdcError(-2, "svdcache_fit_workspace_bytes")
     ws = torch.empty(nbytes, device=dev, dtype=torch.uint8)
     svdcache_fit_basis(shape, F, V, sigma, fro2, ws, p, q, seed)
+    return V, sigma, fro2
+
+
+def save_basis(path: str, V: torch.Tensor, sigma: torch.Tensor, fro2: Optional[torch.Tensor] = None):
+    """Write a fitted basis to a file (numpy .npz, plain arrays only): the one-time SVD of a model is done
+    offline on a reference prompt and its V and sigma are reused for every later prompt (Sec. 3.3)."""
+    import numpy as np
+    arrays = {"V": V.detach().float().cpu().numpy(), "sigma": sigma.detach().float().cpu().numpy()}
+    if fro2 is not None:
+        arrays["fro2"] = fro2.detach().float().cpu().numpy()
+    with open(path, "wb") as f:
+        np.savez(f, **arrays)
+
+
+def load_basis(path: str, device="cuda:0"):
+    """(V [B,D,k], sigma [B,k], fro2 [B] or None) from a file written by save_basis, as float32 tensors on
+    `device`.  Nothing in the file is executed (no pickled objects are accepted)."""
+    import numpy as np
+    with np.load(path, allow_pickle=False) as z:
+        V = torch.from_numpy(z["V"]).to(device).contiguous()
+        sigma = torch.from_numpy(z["sigma"]).to(device).contiguous()
+        fro2 = torch.from_numpy(z["fro2"]).to(device).contiguous() if "fro2" in z.files else None
+    if V.dim() != 3 or sigma.shape != (V.shape[0], V.shape[2]):
+        raise ValueError("not a basis file: V must be [B, D, k] and sigma [B, k]")
     return V, sigma, fro2
 
 

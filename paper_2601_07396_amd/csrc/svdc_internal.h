@@ -30,6 +30,13 @@ int32_t launch_select_rank(int B, int k, const float* sigma, const float* fro2, 
                            int32_t* reached, hipStream_t st);
 int32_t launch_truncate_basis(const svdc_shape& s, float* V, float* sigma, const int32_t* k_star, hipStream_t st);
 
+// ---- basis reuse and re-basing: basis_kernels.hip ------------------------------------------
+bool rebase_rank_supported(int k);
+int32_t launch_basis_overlap(const svdc_shape& s, const float* V_old, const float* V_new, float* M, hipStream_t st);
+int32_t launch_rebase_state(const svdc_shape& s, const float* M, const float* S_in, float* S_out, hipStream_t st);
+int32_t launch_basis_similarity(const svdc_shape& s, const float* V_a, const float* sigma_a, const float* V_b,
+                                const float* sigma_b, float* sim_dir, float* sim_sigma, hipStream_t st);
+
 // ---- matrix-core kernels: mfma_kernels.hip -----------------------------------
 bool mfma_shape_supported(const svdc_shape& s);
 size_t mfma_packed_bytes(const svdc_shape& s);

@@ -168,4 +168,32 @@ int32_t svdcache_forecast_combine(const svdc_shape* shape, int32_t num_states, c
   return launch_forecast_general(*shape, cs, V, R, X, Out, (hipStream_t)stream);
 }
 
+int32_t svdcache_basis_overlap(const svdc_shape* shape, const float* V_old, const float* V_new, float* M,
+                               void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!V_old || !V_new || !M) return SVDC_E_NULL;
+  if (!rebase_rank_supported(shape->k)) return SVDC_E_SHAPE;
+  return launch_basis_overlap(*shape, V_old, V_new, M, (hipStream_t)stream);
+}
+
+int32_t svdcache_rebase_state(const svdc_shape* shape, const float* M, const float* S_in, float* S_out,
+                              void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!M || !S_in || !S_out) return SVDC_E_NULL;
+  if (!rebase_rank_supported(shape->k)) return SVDC_E_SHAPE;
+  return launch_rebase_state(*shape, M, S_in, S_out, (hipStream_t)stream);
+}
+
+int32_t svdcache_basis_similarity(const svdc_shape* shape, const float* V_a, const float* sigma_a,
+                                  const float* V_b, const float* sigma_b, float* sim_dir, float* sim_sigma,
+                                  void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!V_a || !V_b || !sim_dir) return SVDC_E_NULL;
+  if (sim_sigma && (!sigma_a || !sigma_b)) return SVDC_E_NULL;
+  return launch_basis_similarity(*shape, V_a, sigma_a, V_b, sigma_b, sim_dir, sim_sigma, (hipStream_t)stream);
+}
+
 }  // extern "C"

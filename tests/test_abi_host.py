@@ -121,3 +121,20 @@ def test_widened_entry_points_validate_on_the_host(lib):
     assert lib.svdcache_forecast_combine(C.byref(s), 1, None, w, fake, None, fake, None, fake, None) == -1
     bad = (C.c_void_p * 1)(260)                                           # not 16-byte aligned
     assert lib.svdcache_forecast_combine(C.byref(s), 1, bad, w, fake, None, fake, None, fake, None) == -4
+
+
+def test_basis_file_round_trip(tmp_path):
+    """The offline basis file holds plain arrays and comes back bit for bit (file IO only, no GPU)."""
+    import torch
+    g = torch.Generator().manual_seed(1)
+    V, sigma, fro2 = torch.randn(3, 40, 6, generator=g), torch.rand(3, 6, generator=g), torch.rand(3, generator=g)
+    path = str(tmp_path / "basis.npz")
+    pkg.save_basis(path, V, sigma, fro2)
+    V2, s2, f2 = pkg.load_basis(path, device="cpu")
+    assert torch.equal(V, V2) and torch.equal(sigma, s2) and torch.equal(fro2, f2)
+    pkg.save_basis(path, V, sigma)
+    assert pkg.load_basis(path, device="cpu")[2] is None
+    import numpy as np
+    np.savez(path, V=np.zeros((2, 3)), sigma=np.zeros(3))
+    with pytest.raises(ValueError):
+        pkg.load_basis(path, device="cpu")

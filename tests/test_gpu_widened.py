@@ -233,3 +233,110 @@ def test_flux57_full_size_combine_sampled_rows():
         want = ref_forecast_combine([to_np(s[b][rows]) for s in S], w, to_np(V[b]), to_np(R[b][rows]),
                                     to_np(X[b][rows]), "bf16")
         assert_close(to_np(out[b][rows]), want, "bf16", f"combine block {b}")
+
+
+# ------------------------------------------------------------------ basis reuse and re-basing (Sec. 3.3)
+
+@pytest.mark.parametrize("B,N,D,k", [(2, 70, 200, 17), (1, 130, 3072, 32), (2, 130, 256, 128), (1, 9, 8, 1),
+                                     (3, 257, 512, 64)])
+def test_basis_overlap_and_rebase(B, N, D, k):
+    from oracle import ref_basis_overlap, ref_rebase_state, ref_forecast
+    g = torch.Generator().manual_seed(D + k)
+    Vo = torch.linalg.qr(torch.randn(B, D, k, generator=g, dtype=torch.float64))[0].float().contiguous()
+    # new basis: mostly a rotation of the old one, tilted a little out of its subspace
+    Q = torch.linalg.qr(torch.randn(B, k, k, generator=g, dtype=torch.float64))[0]
+    Vn = torch.linalg.qr(Vo.double() @ Q + 0.05 * torch.randn(B, D, k, generator=g, dtype=torch.float64))[0]
+    Vn = Vn.float().contiguous()
+    S = 3 * torch.randn(B, N, k, generator=g)
+    R = torch.randn(B, N, D, generator=g)
+    shape = pkg.make_shape(R, k)
+    M = torch.empty(B, k, k, device=DEV)
+    Sn = torch.empty(B, N, k, device=DEV)
+    pkg.svdcache_basis_overlap(shape, Vo.to(DEV), Vn.to(DEV), M)
+    pkg.svdcache_rebase_state(shape, M, S.to(DEV), Sn)
+    Sip = S.clone().to(DEV)
+    pkg.svdcache_rebase_state(shape, M, Sip, Sip)                      # in place
+    torch.cuda.synchronize()
+    assert torch.equal(Sip, Sn)
+    for b in range(B):
+        Mr = ref_basis_overlap(to_np(Vo[b]), to_np(Vn[b]))
+        assert np.abs(to_np(M[b]) - Mr).max() <= 2e-6
+        assert_close(to_np(Sn[b]), ref_rebase_state(to_np(S[b]), to_np(M[b]), "f32"), "f32", f"rebase block {b}")
+    # exact carry-over inside the same subspace: the cached step gives the same feature before and after
+    Vrot = (Vo.double() @ Q).float().contiguous()
+    pkg.svdcache_basis_overlap(shape, Vo.to(DEV), Vrot.to(DEV), M)
+    pkg.svdcache_rebase_state(shape, M, S.to(DEV), Sn)
+    a, c = torch.empty(B, N, D, device=DEV), torch.empty(B, N, D, device=DEV)
+    pkg.svdcache_forecast(shape, S.to(DEV), Vo.to(DEV), None, R.to(DEV), a)
+    pkg.svdcache_forecast(shape, Sn, Vrot.to(DEV), None, R.to(DEV), c)
+    torch.cuda.synchronize()
+    assert float((a - c).norm() / a.norm()) <= 2e-6
+
+
+def test_refit_on_a_drifted_feature_keeps_the_state_useful():
+    """Fit on F_0, run full steps, refit on a later feature whose subspace has drifted, carry the EMA state
+    over, and compare the cached step in the new basis with the oracle fed the same inputs."""
+    from oracle import ref_basis_overlap, ref_rebase_state, ref_forecast
+    wl = WORKLOADS["flux1"].with_(N=512)
+    fs = FeatureStream(wl, 0, device=DEV)
+    F0, F1 = fs.at(0).unsqueeze(0).contiguous(), fs.at(wl.interval).unsqueeze(0).contiguous()
+    k = wl.k
+    shape = pkg.make_shape(F0, k)
+    V0, s0, _ = pkg.fit_basis(F0, k)
+    V1, s1, _ = pkg.fit_basis(F1, k)
+    pk0, pk1 = pkg.pack_basis(shape, V0), pkg.pack_basis(shape, V1)
+    R = torch.empty_like(F0)
+    S = torch.empty(1, wl.N, k, device=DEV)
+    pkg.svdcache_full_step(shape, F0, V0, pk0, R, S, None, 0.5, True)
+    M = torch.empty(1, k, k, device=DEV)
+    pkg.svdcache_basis_overlap(shape, V0, V1, M)
+    S1 = torch.empty_like(S)
+    pkg.svdcache_rebase_state(shape, M, S, S1)
+    Cn = torch.empty_like(S)
+    pkg.svdcache_full_step(shape, F1, V1, pk1, R, S1, Cn, 0.5, False)     # EMA continues in the new basis
+    Fh = torch.empty_like(F0)
+    pkg.svdcache_forecast(shape, S1, V1, pk1, R, Fh)
+    sim_dir = torch.empty(1, k, device=DEV)
+    sim_sig = torch.empty(1, device=DEV)
+    pkg.svdcache_basis_similarity(shape, V0, s0, V1, s1, sim_dir, sim_sig)
+    torch.cuda.synchronize()
+    Mr = ref_basis_overlap(to_np(V0[0]), to_np(V1[0]))
+    assert np.abs(to_np(M[0]) - Mr).max() <= 2e-6
+    S_carry = ref_rebase_state(to_np(S[0]), Mr, "f32")
+    Rr, Sr, Cr = ref_full_step(to_np(F1[0]), to_np(V1[0]), S_carry, 0.5, False, "bf16")
+    assert_close(to_np(S1[0]), Sr, "f32", "EMA state after re-basing")
+    assert_close(to_np(Fh[0]), ref_forecast(to_np(S1[0]), to_np(V1[0]), to_np(R[0]), "bf16"), "bf16", "Fhat")
+    # the synthetic stream keeps its subspace: the leading directions and the spectrum stay similar (Fig. 1(b))
+    assert float(sim_sig) > 0.8 and float(sim_dir[0, 0]) > 0.8
+
+
+@pytest.mark.parametrize("B,D,k", [(2, 200, 17), (1, 3072, 32), (3, 64, 8)])
+def test_basis_similarity(B, D, k):
+    from oracle import ref_basis_similarity
+    g = torch.Generator().manual_seed(D * 7 + k)
+    Va = torch.linalg.qr(torch.randn(B, D, k, generator=g, dtype=torch.float64))[0].float().contiguous()
+    Vb = (Va + 0.3 * torch.randn(B, D, k, generator=g) / D ** 0.5).contiguous()
+    Vb[:, :, 0] *= -1.0                      # sign flip: no effect
+    Vb[:, :, k - 1] = 0.0                    # a zero direction scores zero
+    sa = torch.sort(torch.rand(B, k, generator=g) * 5 + 0.1, descending=True)[0]
+    sb = (sa * (1 + 0.2 * torch.randn(B, k, generator=g))).abs() * 0.7
+    shape = pkg.make_shape(torch.empty(B, max(k, 4), D), k)
+    sd = torch.empty(B, k, device=DEV)
+    ss = torch.empty(B, device=DEV)
+    pkg.svdcache_basis_similarity(shape, Va.to(DEV), sa.to(DEV), Vb.to(DEV), sb.to(DEV), sd, ss)
+    torch.cuda.synchronize()
+    for b in range(B):
+        wd, ws = ref_basis_similarity(to_np(Va[b]), to_np(sa[b]), to_np(Vb[b]), to_np(sb[b]))
+        assert np.abs(to_np(sd[b]) - wd).max() <= 1e-6 and abs(float(ss[b]) - ws) <= 1e-6
+    sd2 = torch.empty(B, k, device=DEV)
+    pkg.svdcache_basis_similarity(shape, Va.to(DEV), None, Vb.to(DEV), None, sd2, None)   # spectrum part optional
+    torch.cuda.synchronize()
+    assert torch.equal(sd, sd2)
+
+
+def test_rebase_rejects_ranks_beyond_its_limit():
+    shape = pkg.make_shape(torch.empty(1, 200, 256), 160)
+    t = torch.empty(1, 256, 160, device=DEV)
+    with pytest.raises(pkg.SvdcError) as e:
+        pkg.svdcache_basis_overlap(shape, t, t, torch.empty(1, 160, 160, device=DEV))
+    assert e.value.code == -2
