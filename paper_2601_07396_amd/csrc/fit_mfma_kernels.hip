@@ -307,7 +307,9 @@ __global__ void clear_f32_kernel(float* p, int64_t n) {
 template <int NCW>
 void backproject_groups(const svdc_shape& s, int* gpb, int* rows) {
   int dev = 0, cus = 256;
-  if (hipGetDevice(&dev) == hipSuccess) hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    cus = 256;
   const int64_t slabs = (int64_t)(s.D / (128 * NCW)) * s.B;
   int g = (int)((cus + slabs / 2) / slabs);
   if (g < 1) g = 1;

@@ -554,7 +554,7 @@ int32_t forecast_by_width(const svdc_shape& s, const CoefStates& cs, const void*
   // (the extended kernel also holds up to 4 coefficient states and the added tensor per tile in flight)
   constexpr int kBudget = (SPLIT ? 12 : 24) / KT2 / (sizeof(T) == 4 ? 2 : 1) / (EXT && KT2 >= 2 ? 2 : 1);
   constexpr int kMax =
-      kBudget >= 12 ? 12 : (kBudget >= 6 ? 6 : (kBudget >= 4 ? 4 : (kBudget >= 3 ? 3 : (kBudget >= 2 ? 2 : 1))));
+      kBudget >= 12 ? 12 : (kBudget >= 6 ? 6 : (kBudget >= 4 ? 4 : (kBudget >= 3 ? 3 : ((kBudget >= 2 || !EXT) ? 2 : 1))));
   const int m = s.D / 128;
   if constexpr (kMax >= 12) {
     if (m % 12 == 0) return forecast_launch<T, 12, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
@@ -609,16 +609,28 @@ constexpr int ring_depth(int CH, int W, int KT2) {
   return rd;
 }
 
+// A launch with fewer tiles than compute units leaves units idle: such small problems take tiles one step
+// smaller (their packed-basis traffic does not matter at that size).
+template <typename T, int CH, int KT2, bool SPLIT>
+int32_t full_step_by_size(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
+                          float alpha, int init, hipStream_t st) {
+  constexpr int W = sizeof(T) == 4 ? 2 : 1;
+  constexpr int RT = tile_rows(CH, W, KT2), RD = ring_depth(CH, W, KT2);
+  if constexpr (RT > 1) {
+    const int64_t tiles = (int64_t)((s.N + 16 * RT - 1) / (16 * RT)) * s.B;
+    if (tiles < num_compute_units())
+      return full_step_launch<T, CH, RT - 1, KT2, SPLIT, RD>(s, F, packed, R, S, C, alpha, init, st);
+  }
+  return full_step_launch<T, CH, RT, KT2, SPLIT, RD>(s, F, packed, R, S, C, alpha, init, st);
+}
+
 template <typename T, int CH, bool SPLIT>
 int32_t full_step_by_rank(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
                           float alpha, int init, hipStream_t st) {
-  constexpr int W = sizeof(T) == 4 ? 2 : 1;
   const int kp = padded_rank(s.k);
-  if (kp == 32)
-    return full_step_launch<T, CH, tile_rows(CH, W, 1), 1, SPLIT, ring_depth(CH, W, 1)>(s, F, packed, R, S, C, alpha, init, st);
-  if (kp == 64)
-    return full_step_launch<T, CH, tile_rows(CH, W, 2), 2, SPLIT, ring_depth(CH, W, 2)>(s, F, packed, R, S, C, alpha, init, st);
-  return full_step_launch<T, CH, tile_rows(CH, W, 4), 4, SPLIT, ring_depth(CH, W, 4)>(s, F, packed, R, S, C, alpha, init, st);
+  if (kp == 32) return full_step_by_size<T, CH, 1, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
+  if (kp == 64) return full_step_by_size<T, CH, 2, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
+  return full_step_by_size<T, CH, 4, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
 }
 
 template <typename T, bool SPLIT>
