@@ -280,6 +280,9 @@ def main():
         t_ov = timed(lambda: pkg.svdcache_basis_overlap(shape, V, V2, Mo)) if rebase_ok else None
         t_rb = timed(lambda: pkg.svdcache_rebase_state(shape, Mo, S, S3)) if rebase_ok else None
         t_sim = timed(lambda: pkg.svdcache_basis_similarity(shape, V, sigma, V2, sigma, sim_dir, sim_sig))
+        t_rema = timed(lambda: pkg.svdcache_full_step_residual_ema(shape, feats[0], V, packed, Fh, Fh, S3, None,
+                                                                   wl.alpha, 0.5, False))
+        by_rema = by_full + B * N * D * eb
         by_comb = B * (2 * N * D * eb + 2 * N * k * 4 + D * k * 4)
         by_add = by_comb + B * N * D * eb
         widened = {
@@ -288,6 +291,8 @@ def main():
             "svdcache_forecast_combine(2 states, added tensor)": {
                 "avg_ms": t_add, "bytes": by_add, "GBps": by_add / t_add / 1e6,
                 "frac_of_hbm_peak": by_add / t_add / 1e6 / HBM_PEAK_GBS},
+            "svdcache_full_step_residual_ema": {"avg_ms": t_rema, "bytes": by_rema, "GBps": by_rema / t_rema / 1e6,
+                                                "frac_of_hbm_peak": by_rema / t_rema / 1e6 / HBM_PEAK_GBS},
             "svdcache_select_rank": {"avg_ms": t_sel, "k_star_min_max": [int(k_star.min()), int(k_star.max())],
                                      "reached_all": bool(reached.all())},
             "svdcache_truncate_basis": {"avg_ms": t_trunc},

@@ -196,6 +196,19 @@ int32_t svdcache_forecast_combine(const svdc_shape* shape, int32_t num_states, c
                                   const float* weights, const float* V, const void* packed, const void* R,
                                   const void* X, void* Out, void* stream);
 
+/* Full-compute step that smooths the residual state as well (the "EMA on both parts" variant of the ablation
+ * in Sec. 4.5 / Fig. 5(c); the paper's method reuses the latest residual, which is alpha_r = 1):
+ *   C, S as in svdcache_full_step;
+ *   R = F - C V^T                                        if init != 0 or alpha_r == 1
+ *   R = (1 - alpha_r) R_prev + alpha_r (F - C V^T)       otherwise
+ *   R_prev  in   [B,N,D] dtype; may be NULL when it is not read; may be the buffer R (state updated in place),
+ *                but must not be the buffer F
+ *   alpha_r in (0, 1]; all other arguments as in svdcache_full_step (R may be the buffer F when R_prev is
+ *   a third buffer or is not read) */
+int32_t svdcache_full_step_residual_ema(const svdc_shape* shape, const void* F, const float* V,
+                                        const void* packed, const void* R_prev, void* R, float* S, float* C,
+                                        float alpha, float alpha_r, int32_t init, void* stream);
+
 /* Basis reuse and re-basing (Sec. 3.3: one basis, fitted once, serves other prompts; Fig. 1(b): it stays
  * similar across prompts).  When a basis IS refitted, the coefficient state fitted to the old basis is carried
  * over instead of being dropped:

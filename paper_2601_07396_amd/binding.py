@@ -42,6 +42,9 @@ EXPORTS = {
     "svdcache_pack_basis": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "svdcache_full_step": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_void_p]),
+    "svdcache_full_step_residual_ema": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float,
+                                                    C.c_int32, C.c_void_p]),
     "svdcache_forecast": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p]),
     "svdcache_select_rank": (C.c_int32, [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p,
@@ -159,6 +162,15 @@ def svdcache_full_step(shape: Shape, F, V, packed, R, S, Cout, alpha: float, ini
     rc = load_library().svdcache_full_step(C.byref(shape), _ptr(F), _ptr(V), _ptr(packed), _ptr(R), _ptr(S),
                                            _ptr(Cout), float(alpha), int(bool(init)), _stream())
     _check(rc, "svdcache_full_step")
+
+
+def svdcache_full_step_residual_ema(shape: Shape, F, V, packed, R_prev, R, S, Cout, alpha: float, alpha_r: float,
+                                    init: bool):
+    _need_gpu(F, V, packed, R_prev, R, S, Cout)
+    rc = load_library().svdcache_full_step_residual_ema(C.byref(shape), _ptr(F), _ptr(V), _ptr(packed), _ptr(R_prev),
+                                                        _ptr(R), _ptr(S), _ptr(Cout), float(alpha), float(alpha_r),
+                                                        int(bool(init)), _stream())
+    _check(rc, "svdcache_full_step_residual_ema")
 
 
 def svdcache_forecast(shape: Shape, S, V, packed, R, Fhat):

@@ -15,9 +15,9 @@ constexpr int kChunk = 32;         // columns of V handled per projection pass
 // F and R may alias (in place): each element of a row is read before it is written.
 template <typename T>
 __global__ __launch_bounds__(256) void full_step_general_kernel(const T* F, const float* __restrict__ V, T* R,
-                                                                float* S, float* C, int N, int D, int k,
-                                                                int64_t ldf, int64_t bstride, float alpha,
-                                                                int init) {
+                                                                const T* Rp, float alpha_r, float* S, float* C,
+                                                                int N, int D, int k, int64_t ldf, int64_t bstride,
+                                                                float alpha, int init) {
   __shared__ float csh[kRowsPerGroup][kMaxRank];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int b = blockIdx.y;
@@ -93,7 +93,10 @@ __global__ __launch_bounds__(256) void full_step_general_kernel(const T* F, cons
     } else {
       for (int j = 0; j < k; ++j) acc += cw[j] * vp[j];
     }
-    st_elem(r, d, ld_elem(f, d) - acc);
+    float rnew = ld_elem(f, d) - acc;
+    // optional smoothing of the residual state (Rp: previous residual, may be the buffer R itself)
+    if (Rp) rnew = (1.f - alpha_r) * ld_elem(Rp + (int64_t)b * bstride + row * ldf, d) + alpha_r * rnew;
+    st_elem(r, d, rnew);
   }
 }
 
@@ -142,14 +145,16 @@ __global__ __launch_bounds__(256) void forecast_general_kernel(const CoefStates 
 }
 
 int32_t launch_full_step_general(const svdc_shape& s, const void* F, const float* V, void* R, float* S,
-                                 float* C, float alpha, int init, hipStream_t st) {
+                                 float* C, float alpha, int init, ResidualEma re, hipStream_t st) {
   dim3 grid((s.N + kRowsPerGroup - 1) / kRowsPerGroup, s.B), block(256);
   if (s.dtype == SVDC_BF16)
-    full_step_general_kernel<bf16_t><<<grid, block, 0, st>>>((const bf16_t*)F, V, (bf16_t*)R, S, C, s.N, s.D, s.k,
-                                                           s.ldf, s.block_stride, alpha, init);
+    full_step_general_kernel<bf16_t><<<grid, block, 0, st>>>((const bf16_t*)F, V, (bf16_t*)R, (const bf16_t*)re.prev,
+                                                           re.alpha_r, S, C, s.N, s.D, s.k, s.ldf, s.block_stride,
+                                                           alpha, init);
   else
-    full_step_general_kernel<float><<<grid, block, 0, st>>>((const float*)F, V, (float*)R, S, C, s.N, s.D, s.k,
-                                                          s.ldf, s.block_stride, alpha, init);
+    full_step_general_kernel<float><<<grid, block, 0, st>>>((const float*)F, V, (float*)R, (const float*)re.prev,
+                                                          re.alpha_r, S, C, s.N, s.D, s.k, s.ldf, s.block_stride,
+                                                          alpha, init);
   return launch_status();
 }
 

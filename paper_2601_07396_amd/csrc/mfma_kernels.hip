@@ -302,11 +302,12 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const CoefStates cs,
 // S1 / S2: use the low parts of the basis (and of C) in phase 1 / phase 2.
 // F and R may alias: a tile is completely in registers before it is overwritten.
 // ---------------------------------------------------------------------------
-template <typename T, int CH, int RT, int KT2, bool S1, bool S2, int RD>
+template <typename T, int CH, int RT, int KT2, bool S1, bool S2, int RD, bool REMA>
 __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const uint16_t* __restrict__ P,
-                                                             T* R, float* S, float* C, int N, int k,
-                                                             int64_t ldf, int64_t bstride, float alpha, int init,
-                                                             int tiles_per_block, int total) {
+                                                             T* R, const T* Rp, float alpha_r, float* S, float* C,
+                                                             int N, int k, int64_t ldf, int64_t bstride,
+                                                             float alpha, int init, int tiles_per_block,
+                                                             int total) {
   constexpr int KP = KT2 * 32, KT = KT2 * 2, D = CH * 128;
   constexpr int M = CH * KT;   // basis operand items per wave and phase (a high + a low 16-byte word per lane each)
   __shared__ f32x4 part[kWavesPerGroup][KT][RT][64];
@@ -384,6 +385,26 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
         if (S1) rl[slot] = p1l[(m + RD) * 64];
       }
       __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // REMA: the residual state is smoothed too, R = (1 - alpha_r) R_prev + alpha_r (F - C V^T); PR chunks of the
+    // previous residual are kept in flight
+    constexpr int PR = 4;
+    RowPiece<T> rp[REMA ? PR : 1][REMA ? RT : 1];
+    const T* pbase = REMA ? Rp + (int64_t)b * bstride + 8 * g : nullptr;
+    auto load_prev = [&](int c) {
+      if constexpr (REMA) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          const int row = min(row0 + 16 * rt + r, N - 1);
+          rp[c % PR][rt].load(pbase + (int64_t)row * ldf + 32 * (cg0 + c));
+        }
+      }
+    };
+    if constexpr (REMA) {
+#pragma unroll
+      for (int c = 0; c < PR; ++c)
+        if (c < CH) load_prev(c);
     }
 
     // the first reconstruction operands are requested before the reduction so they arrive during it;
@@ -483,8 +504,19 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
       }
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
+        if constexpr (REMA) {
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const f32x4 old = rp[c % PR][rt].half(t);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[rt][t][i] = (1.f - alpha_r) * old[i] + alpha_r * x[rt][t][i];
+          }
+        }
         const int row = row0 + 16 * rt + r;
         if (row < N) RowPiece<T>::store(obase + (int64_t)row * ldf + 32 * (cg0 + c), x[rt][0], x[rt][1]);
+      }
+      if constexpr (REMA) {
+        if (c + PR < CH) load_prev(c + PR);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -574,16 +606,16 @@ int32_t forecast_by_width(const svdc_shape& s, const CoefStates& cs, const void*
   return forecast_launch<T, 1, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
 }
 
-template <typename T, int CH, int RT, int KT2, bool SPLIT, int RD>
+template <typename T, int CH, int RT, int KT2, bool SPLIT, int RD, bool REMA>
 int32_t full_step_launch(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
-                         float alpha, int init, hipStream_t st) {
+                         float alpha, int init, ResidualEma re, hipStream_t st) {
   const int tiles = (s.N + 16 * RT - 1) / (16 * RT);
   const int64_t total = (int64_t)tiles * s.B;
   if (total > 0x7fffffff) return SVDC_E_SHAPE;
   const int grid = (int)std::min<int64_t>(total, num_compute_units());
-  full_step_mfma_kernel<T, CH, RT, KT2, SPLIT, SPLIT, RD><<<grid, 256, 0, st>>>(
-      (const T*)F, (const uint16_t*)packed, (T*)R, S, C, s.N, s.k, s.ldf, s.block_stride, alpha, init, tiles,
-      (int)total);
+  full_step_mfma_kernel<T, CH, RT, KT2, SPLIT, SPLIT, RD, REMA><<<grid, 256, 0, st>>>(
+      (const T*)F, (const uint16_t*)packed, (T*)R, (const T*)re.prev, re.alpha_r, S, C, s.N, s.k, s.ldf,
+      s.block_stride, alpha, init, tiles, (int)total);
   return launch_status();
 }
 
@@ -613,37 +645,40 @@ constexpr int ring_depth(int CH, int W, int KT2) {
 // smaller (their packed-basis traffic does not matter at that size).
 template <typename T, int CH, int KT2, bool SPLIT>
 int32_t full_step_by_size(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
-                          float alpha, int init, hipStream_t st) {
+                          float alpha, int init, ResidualEma re, hipStream_t st) {
   constexpr int W = sizeof(T) == 4 ? 2 : 1;
   constexpr int RT = tile_rows(CH, W, KT2), RD = ring_depth(CH, W, KT2);
+  // the variant that also smooths the residual keeps a few chunks of the previous residual in flight: one row
+  // tile less
+  if (re.prev) return full_step_launch<T, CH, (RT > 1 ? RT - 1 : 1), KT2, SPLIT, RD, true>(s, F, packed, R, S, C, alpha, init, re, st);
   if constexpr (RT > 1) {
     const int64_t tiles = (int64_t)((s.N + 16 * RT - 1) / (16 * RT)) * s.B;
     if (tiles < num_compute_units())
-      return full_step_launch<T, CH, RT - 1, KT2, SPLIT, RD>(s, F, packed, R, S, C, alpha, init, st);
+      return full_step_launch<T, CH, RT - 1, KT2, SPLIT, RD, false>(s, F, packed, R, S, C, alpha, init, re, st);
   }
-  return full_step_launch<T, CH, RT, KT2, SPLIT, RD>(s, F, packed, R, S, C, alpha, init, st);
+  return full_step_launch<T, CH, RT, KT2, SPLIT, RD, false>(s, F, packed, R, S, C, alpha, init, re, st);
 }
 
 template <typename T, int CH, bool SPLIT>
 int32_t full_step_by_rank(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
-                          float alpha, int init, hipStream_t st) {
+                          float alpha, int init, ResidualEma re, hipStream_t st) {
   const int kp = padded_rank(s.k);
-  if (kp == 32) return full_step_by_size<T, CH, 1, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
-  if (kp == 64) return full_step_by_size<T, CH, 2, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
-  return full_step_by_size<T, CH, 4, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
+  if (kp == 32) return full_step_by_size<T, CH, 1, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
+  if (kp == 64) return full_step_by_size<T, CH, 2, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
+  return full_step_by_size<T, CH, 4, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
 }
 
 template <typename T, bool SPLIT>
 int32_t full_step_by_width(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
-                           float alpha, int init, hipStream_t st) {
+                           float alpha, int init, ResidualEma re, hipStream_t st) {
   switch (s.D / 128) {
-    case 2: return full_step_by_rank<T, 2, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
-    case 4: return full_step_by_rank<T, 4, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
-    case 8: return full_step_by_rank<T, 8, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
-    case 12: return full_step_by_rank<T, 12, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
-    case 16: return full_step_by_rank<T, 16, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
-    case 24: return full_step_by_rank<T, 24, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
-    case 32: return full_step_by_rank<T, 32, SPLIT>(s, F, packed, R, S, C, alpha, init, st);
+    case 2: return full_step_by_rank<T, 2, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
+    case 4: return full_step_by_rank<T, 4, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
+    case 8: return full_step_by_rank<T, 8, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
+    case 12: return full_step_by_rank<T, 12, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
+    case 16: return full_step_by_rank<T, 16, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
+    case 24: return full_step_by_rank<T, 24, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
+    case 32: return full_step_by_rank<T, 32, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
     default: return SVDC_E_SHAPE;
   }
 }
@@ -651,11 +686,12 @@ int32_t full_step_by_width(const svdc_shape& s, const void* F, const void* packe
 }  // namespace
 
 int32_t launch_full_step_mfma(const svdc_shape& s, const void* F, const void* packed, void* R, float* S,
-                              float* C, float alpha, int init, hipStream_t st) {
+                              float* C, float alpha, int init, ResidualEma re, hipStream_t st) {
   // float32 features always use the full operand split (a single bf16 operand would cost 8 of their 24 bits)
-  if (s.dtype == SVDC_F32) return full_step_by_width<float, true>(s, F, packed, R, S, C, alpha, init, st);
-  return s.precision == SVDC_PRECISE ? full_step_by_width<bf16_t, true>(s, F, packed, R, S, C, alpha, init, st)
-                                     : full_step_by_width<bf16_t, false>(s, F, packed, R, S, C, alpha, init, st);
+  if (s.dtype == SVDC_F32) return full_step_by_width<float, true>(s, F, packed, R, S, C, alpha, init, re, st);
+  return s.precision == SVDC_PRECISE
+             ? full_step_by_width<bf16_t, true>(s, F, packed, R, S, C, alpha, init, re, st)
+             : full_step_by_width<bf16_t, false>(s, F, packed, R, S, C, alpha, init, re, st);
 }
 
 namespace {

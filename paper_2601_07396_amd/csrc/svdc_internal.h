@@ -20,8 +20,13 @@ struct CoefStates {
 };
 
 // ---- general (any-shape) kernels: general_kernels.hip -----------------------
+// Optional smoothing of the residual state: R = (1 - alpha_r) prev + alpha_r (F - C V^T); prev == nullptr: plain.
+struct ResidualEma {
+  const void* prev = nullptr;
+  float alpha_r = 1.f;
+};
 int32_t launch_full_step_general(const svdc_shape& s, const void* F, const float* V, void* R, float* S,
-                                 float* C, float alpha, int init, hipStream_t st);
+                                 float* C, float alpha, int init, ResidualEma re, hipStream_t st);
 // Out = (sum_m w_m S_m) V^T + R [+ X]   (X nullable)
 int32_t launch_forecast_general(const svdc_shape& s, const CoefStates& cs, const float* V, const void* R,
                                 const void* X, void* Out, hipStream_t st);
@@ -42,7 +47,7 @@ bool mfma_shape_supported(const svdc_shape& s);
 size_t mfma_packed_bytes(const svdc_shape& s);
 int32_t launch_pack_basis(const svdc_shape& s, const float* V, void* packed, hipStream_t st);
 int32_t launch_full_step_mfma(const svdc_shape& s, const void* F, const void* packed, void* R, float* S,
-                              float* C, float alpha, int init, hipStream_t st);
+                              float* C, float alpha, int init, ResidualEma re, hipStream_t st);
 int32_t launch_forecast_mfma(const svdc_shape& s, const float* S, const void* packed, const void* R,
                              void* Fhat, hipStream_t st);
 int32_t launch_forecast_combine_mfma(const svdc_shape& s, const CoefStates& cs, const void* packed, const void* R,

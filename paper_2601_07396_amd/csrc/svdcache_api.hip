@@ -91,9 +91,35 @@ int32_t svdcache_full_step(const svdc_shape* shape, const void* F, const float* 
     return SVDC_E_ALIGN;
   if (packed && mfma_shape_supported(*shape)) {
     if (!aligned(packed, 256)) return SVDC_E_ALIGN;
-    return launch_full_step_mfma(*shape, F, packed, R, S, C, alpha, init != 0, (hipStream_t)stream);
+    return launch_full_step_mfma(*shape, F, packed, R, S, C, alpha, init != 0, ResidualEma{}, (hipStream_t)stream);
   }
-  return launch_full_step_general(*shape, F, V, R, S, C, alpha, init != 0, (hipStream_t)stream);
+  return launch_full_step_general(*shape, F, V, R, S, C, alpha, init != 0, ResidualEma{}, (hipStream_t)stream);
+}
+
+int32_t svdcache_full_step_residual_ema(const svdc_shape* shape, const void* F, const float* V, const void* packed,
+                                        const void* R_prev, void* R, float* S, float* C, float alpha,
+                                        float alpha_r, int32_t init, void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!F || !V || !R || !S) return SVDC_E_NULL;
+  if (!(alpha > 0.f && alpha <= 1.f) || !(alpha_r > 0.f && alpha_r <= 1.f)) return SVDC_E_PARAM;
+  ResidualEma re;
+  if (init == 0 && alpha_r < 1.f) {
+    if (!R_prev) return SVDC_E_NULL;
+    // the previous residual is read while the new one is written: it may be the output buffer (updated in
+    // place) but then the output cannot also be the feature buffer
+    if (R_prev == F) return SVDC_E_PARAM;
+    if (!aligned(R_prev, 16)) return SVDC_E_ALIGN;
+    re.prev = R_prev;
+    re.alpha_r = alpha_r;
+  }
+  if (!aligned(F, 16) || !aligned(R, 16) || !aligned(V, 16) || !aligned(S, 16) || (C && !aligned(C, 16)))
+    return SVDC_E_ALIGN;
+  if (packed && mfma_shape_supported(*shape)) {
+    if (!aligned(packed, 256)) return SVDC_E_ALIGN;
+    return launch_full_step_mfma(*shape, F, packed, R, S, C, alpha, init != 0, re, (hipStream_t)stream);
+  }
+  return launch_full_step_general(*shape, F, V, R, S, C, alpha, init != 0, re, (hipStream_t)stream);
 }
 
 int32_t svdcache_forecast(const svdc_shape* shape, const float* S, const float* V, const void* packed,

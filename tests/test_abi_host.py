@@ -138,3 +138,13 @@ def test_basis_file_round_trip(tmp_path):
     np.savez(path, V=np.zeros((2, 3)), sigma=np.zeros(3))
     with pytest.raises(ValueError):
         pkg.load_basis(path, device="cpu")
+
+
+def test_residual_ema_validates_on_the_host(lib):
+    s = Shape(1, 16, 64, 4, 64, 16 * 64, 0, 0)
+    f, r, v, st = C.c_void_p(256), C.c_void_p(512), C.c_void_p(1024), C.c_void_p(2048)
+    call = lib.svdcache_full_step_residual_ema
+    assert call(C.byref(s), f, v, None, None, r, st, None, 0.5, 0.5, 0, None) == -1     # R_prev needed
+    assert call(C.byref(s), f, v, None, f, r, st, None, 0.5, 0.5, 0, None) == -5        # R_prev is F
+    assert call(C.byref(s), f, v, None, r, r, st, None, 0.5, 0.0, 0, None) == -5        # alpha_r out of range
+    assert call(C.byref(s), None, v, None, r, r, st, None, 0.5, 0.5, 0, None) == -1

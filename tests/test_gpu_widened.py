@@ -340,3 +340,88 @@ def test_rebase_rejects_ranks_beyond_its_limit():
     with pytest.raises(pkg.SvdcError) as e:
         pkg.svdcache_basis_overlap(shape, t, t, torch.empty(1, 160, 160, device=DEV))
     assert e.value.code == -2
+
+
+# ------------------------------------------------------------------ residual smoothed too (Sec. 4.5 ablation)
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("B,N,D,k", [(2, 67, 72, 5), (1, 130, 200, 17), (2, 150, 256, 32), (1, 140, 512, 128),
+                                     (1, 150, 3072, 32), (1, 100, 3072, 64), (1, 50, 1024, 20)])
+def test_full_step_residual_ema(dtype, B, N, D, k):
+    from oracle import ref_full_step_residual_ema
+    store = "f32" if dtype == torch.float32 else "bf16"
+    g = torch.Generator().manual_seed(N * 5 + D + k)
+    F = torch.randn(B, N, D, generator=g).to(dtype)
+    Rp = torch.randn(B, N, D, generator=g).to(dtype)
+    V = torch.linalg.qr(torch.randn(B, D, k, generator=g, dtype=torch.float64))[0].float().contiguous()
+    S0 = torch.randn(B, N, k, generator=g)
+    shape = pkg.make_shape(F, k)
+    Fd, Vd = F.to(DEV), V.to(DEV)
+    pk = pkg.pack_basis(shape, Vd)
+    for init, a_r in [(False, 0.25), (True, 0.25), (False, 1.0)]:
+        R = Rp.clone().to(DEV)                       # in place: the state buffer is both R_prev and R
+        S = S0.clone().to(DEV)
+        Cc = torch.empty_like(S)
+        pkg.svdcache_full_step_residual_ema(shape, Fd, Vd, pk, R, R, S, Cc, 0.3, a_r, init)
+        R2 = torch.full_like(R, 7.0)                 # out of place gives the same bits
+        S2 = S0.clone().to(DEV)
+        pkg.svdcache_full_step_residual_ema(shape, Fd, Vd, pk, Rp.to(DEV), R2, S2, None, 0.3, a_r, init)
+        torch.cuda.synchronize()
+        assert torch.equal(R, R2) and torch.equal(S, S2)
+        for b in range(B):
+            Rr, Sr, Cr = ref_full_step_residual_ema(to_np(F[b]), to_np(V[b]), to_np(S0[b]), to_np(Rp[b]), 0.3, a_r,
+                                                    init, store)
+            assert_close(to_np(R[b]), Rr, store, f"R[{b}] init={init} a_r={a_r}", floor_of=to_np(F[b]))
+            assert_close(to_np(S[b]), Sr, "f32", f"S[{b}]")
+            assert_close(to_np(Cc[b]), Cr, "f32", f"C[{b}]")
+    # alpha_r = 1 is the paper's full step, bit for bit, and then R_prev is not needed
+    Ra, Rb = torch.empty_like(Fd), torch.empty_like(Fd)
+    Sa, Sb = S0.clone().to(DEV), S0.clone().to(DEV)
+    pkg.svdcache_full_step(shape, Fd, Vd, pk, Ra, Sa, None, 0.3, False)
+    pkg.svdcache_full_step_residual_ema(shape, Fd, Vd, pk, None, Rb, Sb, None, 0.3, 1.0, False)
+    torch.cuda.synchronize()
+    assert torch.equal(Ra, Rb) and torch.equal(Sa, Sb)
+
+
+def test_full_step_residual_ema_rejects_bad_arguments():
+    F = torch.randn(1, 16, 64, device=DEV)
+    V = torch.linalg.qr(torch.randn(1, 64, 4, device=DEV))[0].contiguous()
+    S = torch.zeros(1, 16, 4, device=DEV)
+    R = torch.empty_like(F)
+    shape = pkg.make_shape(F, 4)
+    for a_r in (0.0, 1.5, float("nan")):
+        with pytest.raises(pkg.SvdcError) as e:
+            pkg.svdcache_full_step_residual_ema(shape, F, V, None, R, R, S, None, 0.5, a_r, False)
+        assert e.value.code == -5
+    with pytest.raises(pkg.SvdcError) as e:          # previous residual needed but missing
+        pkg.svdcache_full_step_residual_ema(shape, F, V, None, None, R, S, None, 0.5, 0.5, False)
+    assert e.value.code == -1
+    with pytest.raises(pkg.SvdcError) as e:          # the previous residual cannot be the feature buffer
+        pkg.svdcache_full_step_residual_ema(shape, F, V, None, F, R, S, None, 0.5, 0.5, False)
+    assert e.value.code == -5
+
+
+def test_flux57_full_size_residual_ema_sampled_rows():
+    from oracle import ref_full_step_residual_ema
+    wl = WORKLOADS["flux57"]
+    B = wl.B
+    F = torch.empty(B, wl.N, wl.D, device=DEV, dtype=torch.bfloat16)
+    for b in range(B):
+        F[b] = FeatureStream(wl, b, device=DEV).at(wl.interval)
+    R = F.roll(3, dims=0).contiguous()
+    Rp = R.clone()
+    g = torch.Generator(device=DEV).manual_seed(9)
+    S0 = torch.randn(B, wl.N, wl.k, device=DEV, generator=g)
+    S = S0.clone()
+    V = torch.linalg.qr(torch.randn(B, wl.D, wl.k, device=DEV, generator=g))[0].contiguous()
+    shape = pkg.make_shape(F, wl.k)
+    pk = pkg.pack_basis(shape, V)
+    pkg.svdcache_full_step_residual_ema(shape, F, V, pk, R, R, S, None, wl.alpha, 0.5, False)
+    torch.cuda.synchronize()
+    gc = torch.Generator().manual_seed(10)
+    for b in (0, 30, 56):
+        rows = torch.cat([torch.tensor([0, 31, 32, 47, 48, wl.N - 1]), torch.randint(0, wl.N, (64,), generator=gc)]).unique()
+        Rr, Sr, _ = ref_full_step_residual_ema(to_np(F[b][rows]), to_np(V[b]), to_np(S0[b][rows]), to_np(Rp[b][rows]),
+                                               wl.alpha, 0.5, False, "bf16")
+        assert_close(to_np(R[b][rows]), Rr, "bf16", f"R block {b}", floor_of=to_np(F[b][rows]))
+        assert_close(to_np(S[b][rows]), Sr, "f32", f"S block {b}")
