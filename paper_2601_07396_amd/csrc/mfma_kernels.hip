@@ -88,18 +88,6 @@ __global__ __launch_bounds__(256) void pack_basis_kernel(const float* __restrict
   }
 }
 
-// Workgroup id -> (block, row tile) such that the workgroups that land on one
-// XCD (ids congruent modulo 8) walk through the blocks one after the other:
-// each XCD's L2 then holds the packed basis of one or two blocks at a time.
-__device__ __forceinline__ bool xcd_tile(int tiles_per_block, int total, int* b, int* tile) {
-  const int per_xcd = (total + 7) / 8;
-  const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (v >= total) return false;
-  *b = v / tiles_per_block;
-  *tile = v % tiles_per_block;
-  return true;
-}
-
 // split 8 fp32 coefficients into bf16 high and low operand words
 __device__ __forceinline__ void split_operand(const float (&c)[8], u32x4* hi, u32x4* lo) {
   float rem[8];
