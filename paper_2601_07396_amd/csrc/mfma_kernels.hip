@@ -144,6 +144,8 @@ struct RowPiece<float> {
 // rows.  Per tile and chunk: two MFMAs per 32 coefficients whose accumulator
 // starts at R; the coefficient operand is -S (bf16 high + low parts), so the
 // MFMA computes Fhat^T = R^T + (-V)(-S)^T.  PD tiles are kept in flight.
+// EXT: the coefficient operand is sum_m w_m S_m over up to kMaxStates stored states (forecasters that are linear
+// in them, Sec. 5.3) and a tensor X may be added to the result (Out = C_hat V^T + R + X).
 // ---------------------------------------------------------------------------
 
 template <typename T, int NCW, int KT2, bool SPLIT, int PD, bool EXT>
@@ -288,6 +290,8 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const CoefStates cs,
 //   then     the next tile's rows are requested in one burst, so the loads are
 //            in flight while nothing else of this wave waits behind them
 // S1 / S2: use the low parts of the basis (and of C) in phase 1 / phase 2.
+// REMA: the residual state is smoothed as well (ablation of Sec. 4.5): R = (1 - alpha_r) Rp + alpha_r (F - C V^T),
+// with the previous residual Rp read chunk by chunk a few chunks ahead; Rp may be the buffer R.
 // F and R may alias: a tile is completely in registers before it is overwritten.
 // ---------------------------------------------------------------------------
 template <typename T, int CH, int RT, int KT2, bool S1, bool S2, int RD, bool REMA>
