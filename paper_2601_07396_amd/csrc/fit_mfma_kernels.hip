@@ -264,7 +264,10 @@ constexpr int width_for() { return KT <= 2 ? 12 : (KT == 4 ? 6 : 3); }
 template <int NCW, int KT>
 void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, double* fro_acc,
                     bool split, hipStream_t st) {
-  constexpr int TG = KT <= 4 ? 8 : 4;
+  // 4 row tiles per workgroup from sketch width 64 on: with a 4-chunk slab that is about 250 registers, so two
+  // workgroups share a compute unit and one streams F while the other loads its Q operands (measured 8 % / 13 %
+  // faster than 8 tiles x 6 chunks at 3072 channels, plain / split operands)
+  constexpr int TG = KT <= 2 ? 8 : 4;
   // the split operand doubles the Q registers: halve the slab width when it is wide
   constexpr int NCWS = (NCW * KT > 12 && NCW % 2 == 0) ? NCW / 2 : NCW;
   const int ntile = (s.N + 15) / 16;
@@ -320,9 +323,8 @@ void backproject_groups(const svdc_shape& s, int* gpb, int* rows) {
 }
 
 // largest instantiated slab width (chunks per wave) that divides D / 128 and is at most `cap`
-template <int KT, typename Fn12, typename Fn6, typename Fn4, typename Fn3, typename Fn2, typename Fn1>
+template <int KT, int cap, typename Fn12, typename Fn6, typename Fn4, typename Fn3, typename Fn2, typename Fn1>
 void by_width(int m, Fn12 f12, Fn6 f6, Fn4 f4, Fn3 f3, Fn2 f2, Fn1 f1) {
-  constexpr int cap = width_for<KT>();
   if constexpr (cap >= 12) { if (m % 12 == 0) return f12(); }
   if constexpr (cap >= 6) { if (m % 6 == 0) return f6(); }
   if constexpr (cap >= 4) { if (m % 4 == 0) return f4(); }
@@ -334,8 +336,8 @@ void by_width(int m, Fn12 f12, Fn6 f6, Fn4 f4, Fn3 f3, Fn2 f2, Fn1 f1) {
 template <int KT>
 void project_kt(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, double* fro, bool split,
                 hipStream_t st) {
-  constexpr int cap = width_for<KT>();
-  by_width<KT>(
+  constexpr int cap = KT == 4 ? 4 : width_for<KT>();
+  by_width<KT, cap>(
       s.D / 128, [&] { project_launch<(cap >= 12 ? 12 : 1), KT>(s, l, F, Qp, Y, fro, split, st); },
       [&] { project_launch<(cap >= 6 ? 6 : 1), KT>(s, l, F, Qp, Y, fro, split, st); },
       [&] { project_launch<(cap >= 4 ? 4 : 1), KT>(s, l, F, Qp, Y, fro, split, st); },
@@ -358,7 +360,7 @@ void backproject_one(const svdc_shape& s, int l, const void* F, const float* Y, 
 template <int KT>
 void backproject_kt(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, hipStream_t st) {
   constexpr int cap = width_for<KT>();
-  by_width<KT>(
+  by_width<KT, cap>(
       s.D / 128, [&] { backproject_one<(cap >= 12 ? 12 : 1), KT>(s, l, F, Y, Z, st); },
       [&] { backproject_one<(cap >= 6 ? 6 : 1), KT>(s, l, F, Y, Z, st); },
       [&] { backproject_one<(cap >= 4 ? 4 : 1), KT>(s, l, F, Y, Z, st); },
