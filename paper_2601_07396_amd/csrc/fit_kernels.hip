@@ -546,9 +546,9 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
           be += __shfl_xor(be, o, kWave);
           ga += __shfl_xor(ga, o, kWave);
         }
-        // rotate when the columns are not yet orthogonal to 1e-10 (compared in squares, no sqrt): the outputs are
+        // rotate when the columns are not yet orthogonal to 1e-7 (compared in squares, no sqrt): the outputs are
         // float32, and a sweep that finds nothing above the threshold ends the iteration
-        if (ga * ga > 1e-20 * al * be) {
+        if (ga * ga > 1e-14 * al * be) {
           // The rotation ANGLE only steers convergence, so tan(theta) is computed in float32; cos and sin
           // are then formed in float64 so that the rotation is orthogonal to double round-off.
           const double zd = (be - al) * 0.5 * __builtin_amdgcn_rcp(ga);     // approximate reciprocal is enough
