@@ -248,6 +248,19 @@ def main():
                 "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((wl.name, k, bool(args.fast), dom_kernel)) if B == WORKLOADS[wl.name].B else None,
                 "avg_launch_ms": kernels[dom]["avg_ms"], "algorithmic_bytes_per_launch": kernels[dom]["bytes"]}
 
+    # ---- empirical ceiling: a plain device-to-device copy of one feature tensor (read + write bytes / time) ----
+    Fh.copy_(R)
+    torch.cuda.synchronize()
+    ca, cb = ev(), ev()
+    ca.record()
+    for _ in range(10):
+        Fh.copy_(R)
+    cb.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2.0 * per_tensor * 10 / ca.elapsed_time(cb) / 1e6
+    roofline["empirical_copy_GBps"] = copy_gbps
+    roofline["frac_of_empirical_copy"] = ach / copy_gbps
+
     # ---- entry points beyond the three basic ones (outside the timed step; reported separately) -------
     widened = None
     if not args.no_widened:
