@@ -139,8 +139,9 @@ __global__ __launch_bounds__(256) void fit_gemm_kernel(const T* __restrict__ F, 
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void gram_f64_kernel(const float* __restrict__ A, double* G, int rows, int l,
                                                        int rows_per_slice, int ntile) {
-  __shared__ float Ai[16][64];
-  __shared__ float Aj[16][64];
+  // staged as float64 so that each value is converted once, not once per use
+  __shared__ double Ai[16][64];
+  __shared__ double Aj[16][64];
   const int b = blockIdx.z;
   const int ti = blockIdx.y / ntile, tj = blockIdx.y % ntile;
   const float* a = A + (int64_t)b * rows * l;
@@ -152,23 +153,37 @@ __global__ __launch_bounds__(256) void gram_f64_kernel(const float* __restrict__
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+  const bool vec = (l & 3) == 0;
   for (int r0 = rbeg; r0 < rend; r0 += 16) {
     const int rr = t >> 4, c = (t & 15) * 4;
     const int64_t r = r0 + rr;
+    const int ci = ti * 64 + c, cj = tj * 64 + c;
+    float vi[4] = {0.f, 0.f, 0.f, 0.f}, vj[4] = {0.f, 0.f, 0.f, 0.f};
+    if (r < rend) {
+      if (vec) {
+        if (ci < l) *reinterpret_cast<float4*>(vi) = *reinterpret_cast<const float4*>(a + r * l + ci);
+        if (cj < l) *reinterpret_cast<float4*>(vj) = *reinterpret_cast<const float4*>(a + r * l + cj);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (ci + e < l) vi[e] = a[r * l + ci + e];
+          if (cj + e < l) vj[e] = a[r * l + cj + e];
+        }
+      }
+    }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int ci = ti * 64 + c + e, cj = tj * 64 + c + e;
-      Ai[rr][c + e] = (r < rend && ci < l) ? a[r * l + ci] : 0.f;
-      Aj[rr][c + e] = (r < rend && cj < l) ? a[r * l + cj] : 0.f;
+      Ai[rr][c + e] = (double)vi[e];
+      Aj[rr][c + e] = (double)vj[e];
     }
     __syncthreads();
 #pragma unroll
     for (int rr2 = 0; rr2 < 16; ++rr2) {
       double x[4], y[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) x[i] = (double)Ai[rr2][ty * 4 + i];
+      for (int i = 0; i < 4; ++i) x[i] = Ai[rr2][ty * 4 + i];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) y[j] = (double)Aj[rr2][tx * 4 + j];
+      for (int j = 0; j < 4; ++j) y[j] = Aj[rr2][tx * 4 + j];
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
