@@ -26,7 +26,7 @@ int32_t check_shape(const svdc_shape* s) {
 
 extern "C" {
 
-int32_t svdcache_version(void) { return 100; }
+int32_t svdcache_version(void) { return 200; }   // 0.2.0: entry points beyond fit / full step / cached step
 
 const char* svdcache_strerror(int32_t status) {
   switch (status) {
