@@ -13,7 +13,7 @@ from .binding import (
     svdcache_full_step_residual_ema,
     svdcache_select_rank, svdcache_truncate_basis, svdcache_extrapolation_weights, svdcache_forecast_combine,
     svdcache_basis_overlap, svdcache_rebase_state, svdcache_basis_similarity,
-    make_shape, fit_basis, pack_basis, save_basis, load_basis,
+    make_shape, fit_basis, fit_basis_for_energy, pack_basis, save_basis, load_basis,
 )
 
 __all__ = [
@@ -22,5 +22,5 @@ __all__ = [
     "svdcache_has_mfma_path", "svdcache_fit_basis", "svdcache_pack_basis", "svdcache_full_step",
     "svdcache_forecast", "svdcache_full_step_residual_ema", "svdcache_select_rank", "svdcache_truncate_basis", "svdcache_extrapolation_weights",
     "svdcache_forecast_combine", "svdcache_basis_overlap", "svdcache_rebase_state", "svdcache_basis_similarity",
-    "make_shape", "fit_basis", "pack_basis", "save_basis", "load_basis",
+    "make_shape", "fit_basis", "fit_basis_for_energy", "pack_basis", "save_basis", "load_basis",
 ]

@@ -251,6 +251,31 @@ def fit_basis(F: torch.Tensor, k: int, p: int = 0, q: int = 0, seed: int = 0):
     return V, sigma, fro2
 
 
+def fit_basis_for_energy(F: torch.Tensor, tau: float = 0.85, k_init: int = 32, k_max: int = 128, p: int = 0,
+                         q: int = 0, seed: int = 0):
+    """Rank chosen by the energy rule (Eq. 6): fit with k_init, let the device pick k*_b per block, and fit
+    again with twice the rank (up to k_max) while some block has not reached tau within the fitted values
+    (the sketch must be at least as wide as the rank it is asked about).  The loop and its one device-to-host
+    read per pass are host policy; every arithmetic step is a library call.
+    Returns (V [B,D,k] with the columns >= k*_b zeroed, sigma [B,k] likewise, fro2 [B], k_star [B] int32,
+    reached [B] int32) where k is the rank of the last fit."""
+    if F.dim() == 2:
+        F = F.unsqueeze(0)
+    B, N, D = F.shape
+    k = max(1, min(k_init, N, D))
+    while True:
+        V, sigma, fro2 = fit_basis(F, k, p, q, seed)
+        k_star = torch.empty(B, dtype=torch.int32, device=F.device)
+        reached = torch.empty(B, dtype=torch.int32, device=F.device)
+        svdcache_select_rank(sigma, fro2, tau, k_star, reached)
+        k_next = min(2 * k, k_max, N, D)
+        if bool(reached.all()) or k_next <= k:
+            break
+        k = k_next
+    svdcache_truncate_basis(make_shape(F, k), V, sigma, k_star)
+    return V, sigma, fro2, k_star, reached
+
+
 def save_basis(path: str, V: torch.Tensor, sigma: torch.Tensor, fro2: Optional[torch.Tensor] = None):
     """Write a fitted basis to a file (numpy .npz, plain arrays only): the one-time SVD of a model is done
     offline on a reference prompt and its V and sigma are reused for every later prompt (Sec. 3.3)."""

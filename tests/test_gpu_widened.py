@@ -425,3 +425,41 @@ def test_flux57_full_size_residual_ema_sampled_rows():
                                                wl.alpha, 0.5, False, "bf16")
         assert_close(to_np(R[b][rows]), Rr, "bf16", f"R block {b}", floor_of=to_np(F[b][rows]))
         assert_close(to_np(S[b][rows]), Sr, "f32", f"S block {b}")
+
+
+def test_fit_basis_for_energy_grows_the_rank_until_tau_is_reached():
+    """Constructed spectra: block 0 needs 5 directions for 85 % of its energy, block 1 needs 22, so a first fit
+    with rank 8 is too small for block 1 and the rank is doubled (8 -> 16 -> 32)."""
+    B, N, D, m = 2, 600, 256, 40
+    g = torch.Generator().manual_seed(77)
+    U = torch.linalg.qr(torch.randn(B, N, m, generator=g, dtype=torch.float64))[0]
+    W = torch.linalg.qr(torch.randn(B, D, m, generator=g, dtype=torch.float64))[0]
+    s = torch.zeros(B, m, dtype=torch.float64)
+    s[0] = torch.tensor([10.0, 8.0, 6.0] + [1.0] * (m - 3))
+    s[1] = torch.tensor([3.0] * 24 + [1.0] * (m - 24))
+    F = (U * s.unsqueeze(1)) @ W.transpose(1, 2)
+    Fd = F.float().to(DEV)
+    V, sigma, fro2, k_star, reached = pkg.fit_basis_for_energy(Fd, tau=0.85, k_init=8, k_max=64, q=6)
+    torch.cuda.synchronize()
+    assert V.shape[2] == 32 and bool(reached.all())
+    want = []
+    for b in range(B):
+        e = np.cumsum(to_np(s[b]) ** 2) / float((s[b] ** 2).sum())
+        want.append(int(np.searchsorted(e, 0.85) + 1))
+    assert [int(x) for x in k_star] == want == [5, 22]
+    for b in range(B):
+        ks = int(k_star[b])
+        assert not to_np(V[b][:, ks:]).any() and not to_np(sigma[b][ks:]).any()
+        assert np.abs(to_np(sigma[b][:ks]) / to_np(s[b][:ks]) - 1).max() <= 1e-4
+        # the kept directions span the leading right singular vectors
+        P = to_np(V[b][:, :ks])
+        assert np.abs(P.T @ P - np.eye(ks)).max() <= 1e-5
+        # the directions above the flat tail lie in the span of the true leading singular vectors (inside a
+        # cluster of equal sigma any rotation is a correct answer)
+        lead, cols = (3, 3) if b == 0 else (24, ks)
+        Wl = to_np(W[b][:, :lead])
+        assert np.linalg.norm(P[:, :cols] - Wl @ (Wl.T @ P[:, :cols])) <= 1e-3 * np.sqrt(cols)
+    # the rank cannot grow beyond k_max: the answer saturates and says so
+    V2, s2, f2, ks2, r2 = pkg.fit_basis_for_energy(Fd, tau=0.85, k_init=8, k_max=16, q=6)
+    torch.cuda.synchronize()
+    assert V2.shape[2] == 16 and [int(x) for x in r2] == [1, 0] and int(ks2[1]) == 16
