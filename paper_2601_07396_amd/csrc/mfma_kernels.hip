@@ -699,7 +699,8 @@ int32_t forecast_dispatch(const svdc_shape& s, const CoefStates& cs, const void*
   }
   if (s.precision == SVDC_PRECISE) {
     if (kp == 32) return forecast_by_width<bf16_t, 1, true, 1, EXT>(s, cs, packed, R, X, Fhat, st);
-    if (kp == 64) return forecast_by_width<bf16_t, 2, true, 2, EXT>(s, cs, packed, R, X, Fhat, st);
+    // at rank 64 the matrix-core time per tile is no longer small next to its memory time: more tiles in flight
+    if (kp == 64) return forecast_by_width<bf16_t, 2, true, (EXT ? 2 : 4), EXT>(s, cs, packed, R, X, Fhat, st);
     return forecast_by_width<bf16_t, 4, true, 2, EXT>(s, cs, packed, R, X, Fhat, st);
   }
   // at rank <= 32 the split-operand kernel is the faster one (its matrix-core work is hidden anyway)
