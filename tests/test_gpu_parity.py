@@ -445,3 +445,19 @@ def test_mfma_float32_features(B, N, D, k):
             assert_close(to_np(Cc[b]), Cr, "f32", f"C[{b}]")
             Fr = ref_forecast(to_np(S[b]), to_np(V[b]), to_np(R[b]), "f32")
             assert_close(to_np(Fh[b]), Fr, "f32", f"Fhat[{b}]")
+
+
+def test_step_kernels_are_bitwise_deterministic():
+    """No atomics on the output path of the step kernels: two runs on the same inputs give the same bits
+    (matrix-core path at FLUX width and the general path)."""
+    for (B, N, D, k) in [(3, 300, 3072, 32), (2, 130, 200, 17)]:
+        Fbuf, V, S0 = _rand_problem(B, N, D, k, torch.bfloat16, seed=N)
+        runs = []
+        for _ in range(2):
+            R, S, Cc, shape, pk = _run_full(Fbuf, D, V, S0, 0.4, False)
+            Fh = torch.empty_like(R)
+            pkg.svdcache_forecast(shape, S, V.to(DEV), pk, R, Fh)
+            torch.cuda.synchronize()
+            runs.append((R.clone(), S.clone(), Cc.clone(), Fh.clone()))
+        for a, b in zip(*runs):
+            assert torch.equal(a, b)
