@@ -463,3 +463,40 @@ def test_fit_basis_for_energy_grows_the_rank_until_tau_is_reached():
     V2, s2, f2, ks2, r2 = pkg.fit_basis_for_energy(Fd, tau=0.85, k_init=8, k_max=16, q=6)
     torch.cuda.synchronize()
     assert V2.shape[2] == 16 and [int(x) for x in r2] == [1, 0] and int(ks2[1]) == 16
+
+
+def test_extended_kernels_with_strided_rows():
+    """Row stride larger than D on the matrix-core path: the combined cached step (3 states + added tensor) and
+    the residual-smoothing full step touch nothing beyond column D."""
+    from oracle import ref_full_step_residual_ema
+    B, N, D, k, ldf = 2, 150, 3072, 32, 3072 + 64
+    g = torch.Generator().manual_seed(3)
+
+    def strided(x):
+        buf = torch.zeros(B, N, ldf, dtype=torch.bfloat16)
+        buf[:, :, :D] = x
+        return buf.to(DEV)
+    F, Rp, X = [torch.randn(B, N, D, generator=g).to(torch.bfloat16) for _ in range(3)]
+    V = torch.linalg.qr(torch.randn(B, D, k, generator=g, dtype=torch.float64))[0].float().contiguous()
+    S = [torch.randn(B, N, k, generator=g) for _ in range(3)]
+    Fb, Rb, Xb, Ob = strided(F), strided(Rp), strided(X), strided(torch.zeros(B, N, D))
+    shape = pkg.make_shape(Fb[:, :, :D], k)
+    assert shape.ldf == ldf
+    Vd = V.to(DEV)
+    pk = pkg.pack_basis(shape, Vd)
+    assert pk is not None
+    w = [0.5, 1.25, -0.75]
+    pkg.svdcache_forecast_combine(shape, [s.to(DEV) for s in S], w, Vd, pk, Rb[:, :, :D], Xb[:, :, :D], Ob[:, :, :D])
+    S1 = S[0].clone().to(DEV)
+    Rs = Rb.clone()
+    pkg.svdcache_full_step_residual_ema(shape, Fb[:, :, :D], Vd, pk, Rs[:, :, :D], Rs[:, :, :D], S1, None, 0.3, 0.4,
+                                        False)
+    torch.cuda.synchronize()
+    for b in range(B):
+        want = ref_forecast_combine([to_np(s[b]) for s in S], w, to_np(V[b]), to_np(Rp[b]), to_np(X[b]), "bf16")
+        assert_close(to_np(Ob[b, :, :D]), want, "bf16", "combine, strided rows")
+        Rr, Sr, _ = ref_full_step_residual_ema(to_np(F[b]), to_np(V[b]), to_np(S[0][b]), to_np(Rp[b]), 0.3, 0.4,
+                                               False, "bf16")
+        assert_close(to_np(Rs[b, :, :D]), Rr, "bf16", "residual smoothing, strided rows", floor_of=to_np(F[b]))
+        assert_close(to_np(S1[b]), Sr, "f32", "S")
+    assert not Ob[:, :, D:].any() and not Rs[:, :, D:].any()
