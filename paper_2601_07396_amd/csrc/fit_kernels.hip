@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void gram_f64_kernel(const float* __restrict__
   const int b = blockIdx.z;
   const int ti = blockIdx.y / ntile, tj = blockIdx.y % ntile;
   const float* a = A + (int64_t)b * rows * l;
-  double* g = G + (int64_t)b * l * l;
+  double* g = G + ((int64_t)b * gridDim.x + blockIdx.x) * l * l;   // partial Gram matrix of this row slice
   const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
   const int rbeg = blockIdx.x * rows_per_slice, rend = min(rows, rbeg + rows_per_slice);
   double acc[4][4];
@@ -198,9 +198,21 @@ __global__ __launch_bounds__(256) void gram_f64_kernel(const float* __restrict__
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int gj = tj * 64 + tx * 4 + j;
-      if (gj < l) atomicAdd(&g[(int64_t)gi * l + gj], acc[i][j]);
+      if (gj < l) g[(int64_t)gi * l + gj] = acc[i][j];
     }
   }
+}
+
+// G[b] = sum over the row slices of the partial Gram matrices, in slice order (no atomics: the same bits every run)
+__global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restrict__ part, double* G, int nslice,
+                                                          int64_t ll) {
+  const int b = blockIdx.y;
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= ll) return;
+  const double* p = part + (int64_t)b * nslice * ll + e;
+  double s = 0.0;
+  for (int i = 0; i < nslice; ++i) s += p[(int64_t)i * ll];
+  G[(int64_t)b * ll + e] = s;
 }
 
 // ---------------------------------------------------------------------------
@@ -642,6 +654,8 @@ __global__ __launch_bounds__(256) void sumsq_kernel(const T* __restrict__ F, dou
 // ---------------------------------------------------------------------------
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+constexpr int kGramSlices = 16;   // row slices whose partial Gram matrices are summed in a fixed order
+
 bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan) {
   int pp = p ? p->oversample_p : 0;
   int q = p ? p->power_iters_q : 0;
@@ -663,6 +677,7 @@ bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan)
   plan->off_Z = off; off = align_up(off + B * s.D * l * sizeof(float), 256);
   plan->off_Y = off; off = align_up(off + B * (size_t)s.N * l * sizeof(float), 256);
   plan->off_G = off; off = align_up(off + B * l * l * sizeof(double), 256);
+  plan->off_Gp = off; off = align_up(off + B * kGramSlices * (size_t)l * l * sizeof(double), 256);
   plan->off_M = off; off = align_up(off + B * l * l * sizeof(double), 256);
   plan->off_W = off; off = align_up(off + 2 * B * l * (l + 1) * sizeof(double), 256);
   plan->off_misc = off; off = align_up(off + B * sizeof(double), 256);
@@ -704,12 +719,15 @@ void gemm_fty(const svdc_shape& s, int l, const T* F, const float* Y, float* Z, 
   fit_gemm_kernel<T, true><<<grid, 256, 0, st>>>(F, Y, Z, s.N, s.D, l, s.ldf, s.block_stride, split_len, nsplit);
 }
 
-void gram(const float* A, double* G, int B, int rows, int l, hipStream_t st) {
-  zero_f64(G, (int64_t)B * l * l, st);
+void gram(const float* A, double* G, double* Gpart, int B, int rows, int l, hipStream_t st) {
   const int ntile = (l + 63) / 64;
-  const int rows_per_slice = 256;
-  dim3 grid((rows + rows_per_slice - 1) / rows_per_slice, ntile * ntile, B);
-  gram_f64_kernel<<<grid, 256, 0, st>>>(A, G, rows, l, rows_per_slice, ntile);
+  int rows_per_slice = ((rows + kGramSlices - 1) / kGramSlices + 15) / 16 * 16;
+  if (rows_per_slice < 64) rows_per_slice = 64;
+  const int nslice = (rows + rows_per_slice - 1) / rows_per_slice;
+  dim3 grid(nslice, ntile * ntile, B);
+  gram_f64_kernel<<<grid, 256, 0, st>>>(A, Gpart, rows, l, rows_per_slice, ntile);
+  const int64_t ll = (int64_t)l * l;
+  gram_reduce_kernel<<<dim3((unsigned)((ll + 255) / 256), B), 256, 0, st>>>(Gpart, G, nslice, ll);
 }
 
 int32_t chol_inv(double* G, double* Minv, int B, int l, hipStream_t st, double* rdiag = nullptr) {
@@ -760,12 +778,12 @@ int32_t cholqr_apply(const float* In, float* Out, double* G, double* M, int B, i
   return rows_times_small(In, M, Out, B, rows, l, l, l, st);
 }
 
-int32_t orth(float* Zin, float* Qout, double* G, double* M, int B, int rows, int l, bool two_pass,
+int32_t orth(float* Zin, float* Qout, double* G, double* Gpart, double* M, int B, int rows, int l, bool two_pass,
              hipStream_t st) {
-  gram(Zin, G, B, rows, l, st);
+  gram(Zin, G, Gpart, B, rows, l, st);
   if (cholqr_apply(Zin, Qout, G, M, B, rows, l, st) != SVDC_OK) return SVDC_E_HIP;
   if (!two_pass) return SVDC_OK;
-  gram(Qout, G, B, rows, l, st);
+  gram(Qout, G, Gpart, B, rows, l, st);
   return cholqr_apply(Qout, Zin, G, M, B, rows, l, st);
 }
 
@@ -777,6 +795,7 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   float* Z = (float*)(ws + pl.off_Z);
   float* Y = (float*)(ws + pl.off_Y);
   double* G = (double*)(ws + pl.off_G);
+  double* Gp = (double*)(ws + pl.off_Gp);
   double* M = (double*)(ws + pl.off_M);
   double* Wg = (double*)(ws + pl.off_W);
   double* misc = (double*)(ws + pl.off_misc);
@@ -787,7 +806,7 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   // Rayleigh-Ritz step and must be orthonormal to round-off: Q <- orth(Omega), two passes.
   if (pl.q == 0) {
     init_omega_kernel<<<(unsigned)((nq + 255) / 256), 256, 0, st>>>(Z, (int64_t)s.D * l, nq, pl.seed);
-    if (orth(Z, Q, G, M, B, s.D, l, true, st) != SVDC_OK) return SVDC_E_HIP;
+    if (orth(Z, Q, G, Gp, M, B, s.D, l, true, st) != SVDC_OK) return SVDC_E_HIP;
     std::swap(Q, Z);
   } else {
     init_omega_kernel<<<(unsigned)((nq + 255) / 256), 256, 0, st>>>(Q, (int64_t)s.D * l, nq, pl.seed);
@@ -815,13 +834,13 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
       gemm_fty<T>(s, l, F, Y, Z, st);
     }
     const bool last_it = it + 1 == pl.q;
-    if (orth(Z, Q, G, M, B, s.D, l, last_it, st) != SVDC_OK) return SVDC_E_HIP;
+    if (orth(Z, Q, G, Gp, M, B, s.D, l, last_it, st) != SVDC_OK) return SVDC_E_HIP;
     if (last_it) std::swap(Q, Z);
   }
 
   // Rayleigh-Ritz on span(Q)
   project(true);
-  gram(Y, G, B, s.N, l, st);
+  gram(Y, G, Gp, B, s.N, l, st);
   if (chol_inv(G, nullptr, B, l, st) != SVDC_OK) return SVDC_E_HIP;
   if (want_fro && !fro_done) {
     const int rpg = 64;

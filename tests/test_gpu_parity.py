@@ -461,3 +461,17 @@ def test_step_kernels_are_bitwise_deterministic():
             runs.append((R.clone(), S.clone(), Cc.clone(), Fh.clone()))
         for a, b in zip(*runs):
             assert torch.equal(a, b)
+
+
+def test_flux57_fit_is_bitwise_reproducible():
+    """At the batch size of the benchmark no step of the fit sums in an order that depends on scheduling
+    (back-projection with one row group per block, Gram matrices from ordered partial sums): two fits of the
+    same features give the same basis, bit for bit."""
+    wl = WORKLOADS["flux57"]
+    F = torch.empty(wl.B, wl.N, wl.D, device=DEV, dtype=torch.bfloat16)
+    for b in range(wl.B):
+        F[b] = FeatureStream(wl, b, device=DEV).at(0)
+    V1, s1, _ = pkg.fit_basis(F, wl.k)
+    V2, s2, _ = pkg.fit_basis(F, wl.k)
+    torch.cuda.synchronize()
+    assert torch.equal(V1, V2) and torch.equal(s1, s2)
