@@ -472,9 +472,13 @@ __global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* __rest
                                                              const double* __restrict__ rdiag, float* Out,
                                                              int rows, int l) {
   const int b = blockIdx.y, t = threadIdx.x;
-  // every thread reads the same element of L at the same time: wave-uniform addresses, scalar loads
-  const double* Lf = Lfac + (int64_t)b * l * l;
-  const double* rd = rdiag + (int64_t)b * l;
+  // every thread reads the same element of L at the same time: the factor is staged in LDS and read as
+  // broadcasts (as scalar loads its 32 KB at l = 64 overflow the scalar cache)
+  __shared__ double Lf[LMAX * LMAX];
+  __shared__ double rd[LMAX];
+  for (int e = t; e < l * l; e += 256) Lf[e] = Lfac[(int64_t)b * l * l + e];
+  if (t < l) rd[t] = rdiag[(int64_t)b * l + t];
+  __syncthreads();
   const int64_t row = (int64_t)blockIdx.x * 256 + t;
   if (row >= rows) return;
   const float* in = In + ((int64_t)b * rows + row) * l;
