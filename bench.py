@@ -30,8 +30,8 @@ MFMA_BF16_PEAK_TF = 2500.0     # dense bf16, published
 # k = 32, SVDC_PRECISE), each scaled by what the same counter reads for a plain 1 GiB device copy
 # (profiles/flux57_k32_hbm_traffic.md).  Only valid for that configuration.
 MEASURED_TRAFFIC = {
-    ("flux57", 32, False, "forecast_mfma_kernel"): 3404111774,
-    ("flux57", 32, False, "full_step_mfma_kernel"): 3927709181,
+    ("flux57", 32, False, "forecast_mfma_kernel"): 3403536265,
+    ("flux57", 32, False, "full_step_mfma_kernel"): 3930973209,
 }
 
 
