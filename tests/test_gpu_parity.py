@@ -136,10 +136,15 @@ def test_fit_basis_power_law_inputs(dtype, N, D, k):
     _fit_checks(F[0], V[0], sigma[0], fro2[0], k, store)
 
 
-def test_tiny_trajectory_matches_oracle_step_by_step():
-    """Config 1: 2 blocks, 256 x 64, k = 8, fp32, 10 steps, every 3rd a full step, alpha = 0.5.
-    The GPU-fitted basis is handed to the oracle so both sides use the same V."""
+@pytest.mark.parametrize("alpha,interval", [(None, None), (0.3, 5), (0.7, 8), (0.1, 3), (1.0, 2)],
+                         ids=["config", "a0.3-N5", "a0.7-N8", "a0.1-N3", "reuse-N2"])
+def test_tiny_trajectory_matches_oracle_step_by_step(alpha, interval):
+    """Config 1: 2 blocks, 256 x 64, k = 8, fp32, 10 steps, every 3rd a full step, alpha = 0.5; then the EMA
+    weights and caching intervals of the sweep configuration (alpha = 0.1 is the paper's beta = 0.9, alpha = 1
+    plain reuse).  The GPU-fitted basis is handed to the oracle so both sides use the same V."""
     wl = WORKLOADS["tiny"]
+    if alpha is not None:
+        wl = wl.with_(alpha=alpha, interval=interval, T=17)
     streams = [FeatureStream(wl, b) for b in range(wl.B)]
     feats = [torch.stack([s.at(t) for s in streams]) for t in range(wl.T)]
     F0 = feats[0].to(DEV)
