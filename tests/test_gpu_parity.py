@@ -480,3 +480,35 @@ def test_flux57_fit_is_bitwise_reproducible():
     V2, s2, _ = pkg.fit_basis(F, wl.k)
     torch.cuda.synchronize()
     assert torch.equal(V1, V2) and torch.equal(s1, s2)
+
+
+def test_flux_block_trajectory_against_a_free_running_oracle():
+    """Config 2 (one FLUX-sized block, bf16, k = 32, full step every 5) over 16 timesteps on the matrix-core
+    path.  The oracle keeps its OWN state on 80 sampled token rows (rows are independent given V), so errors of
+    the GPU path would have to stay small over four EMA updates, not just within one call."""
+    wl = WORKLOADS["flux1"].with_(T=16)
+    fs = FeatureStream(wl, 0, device=DEV)
+    F0 = fs.at(0).unsqueeze(0).contiguous()
+    shape = pkg.make_shape(F0, wl.k)
+    V, _, _ = pkg.fit_basis(F0, wl.k)
+    pk = pkg.pack_basis(shape, V)
+    assert pk is not None
+    Vn = to_np(V[0])
+    rows = torch.cat([torch.tensor([0, 15, 16, 47, 48, wl.N - 1]),
+                      torch.randint(0, wl.N, (74,), generator=torch.Generator().manual_seed(4))]).unique()
+    R = torch.empty_like(F0)
+    S = torch.empty(1, wl.N, wl.k, device=DEV)
+    Fh = torch.empty_like(F0)
+    Rr = Sr = None
+    for t in range(wl.T):
+        if is_full_step(t, wl.interval):
+            Ft = fs.at(t).unsqueeze(0).contiguous()
+            pkg.svdcache_full_step(shape, Ft, V, pk, R, S, None, wl.alpha, t == 0)
+            torch.cuda.synchronize()
+            Rr, Sr, _ = ref_full_step(to_np(Ft[0][rows]), Vn, Sr, wl.alpha, t == 0, "bf16")
+            assert_close(to_np(R[0][rows]), Rr, "bf16", f"t={t} R", floor_of=to_np(Ft[0][rows]))
+            assert_close(to_np(S[0][rows]), Sr, "f32", f"t={t} S")
+        else:
+            pkg.svdcache_forecast(shape, S, V, pk, R, Fh)
+            torch.cuda.synchronize()
+            assert_close(to_np(Fh[0][rows]), ref_forecast(Sr, Vn, Rr, "bf16"), "bf16", f"t={t} Fhat")
