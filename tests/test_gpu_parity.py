@@ -52,8 +52,8 @@ def test_full_step_and_forecast_general_shapes(dtype, B, N, D, k):
             assert_close(to_np(R[b]), Rr, store, f"R[{b}]", floor_of=to_np(Fbuf[b]))
             assert_close(to_np(S[b]), Sr, "f32", f"S[{b}]")
             assert_close(to_np(Cc[b]), Cr, "f32", f"C[{b}]")
-            # forecast checked with the GPU's own (S, R) as inputs to the oracle
-            Fr = ref_forecast(to_np(S[b]), to_np(V[b]), to_np(R[b]), store)
+            # the oracle forecasts from its OWN state: nothing computed on the GPU is fed to it
+            Fr = ref_forecast(Sr, to_np(V[b]), Rr, store)
             assert_close(to_np(Fh[b]), Fr, store, f"Fhat[{b}]")
 
 
@@ -64,18 +64,19 @@ def test_strided_rows_inplace_and_null_C(dtype):
     Fbuf, V, S0 = _rand_problem(B, N, D, k, dtype, seed=5, ldf=ldf)
     R, S, Cc, shape, pk = _run_full(Fbuf, D, V, S0, 0.5, False, want_C=False, inplace=True)
     assert Cc is None and shape.ldf == ldf
+    state = []
     for b in range(B):
         Rr, Sr, _ = ref_full_step(to_np(Fbuf[b, :, :D]), to_np(V[b]), to_np(S0[b]), 0.5, False, store)
         assert_close(to_np(R[b, :, :D]), Rr, store, "R in place")
         assert_close(to_np(S[b]), Sr, "f32", "S")
+        state.append((Rr, Sr))
     # the padding columns beyond D are not touched
     assert torch.equal(R[:, :, D:].cpu(), Fbuf[:, :, D:])
-    # forecast in place (Fhat aliases R)
-    Rc = R.clone()
+    # forecast in place (Fhat aliases R); the oracle continues from its own state
     pkg.svdcache_forecast(shape, S, V.to(DEV), pk, R[:, :, :D], R[:, :, :D])
     torch.cuda.synchronize()
     for b in range(B):
-        Fr = ref_forecast(to_np(S[b]), to_np(V[b]), to_np(Rc[b, :, :D]), store)
+        Fr = ref_forecast(state[b][1], to_np(V[b]), state[b][0], store)
         assert_close(to_np(R[b, :, :D]), Fr, store, "Fhat in place")
 
 
@@ -141,7 +142,7 @@ def test_fit_basis_power_law_inputs(dtype, N, D, k):
 def test_tiny_trajectory_matches_oracle_step_by_step(alpha, interval):
     """Config 1: 2 blocks, 256 x 64, k = 8, fp32, 10 steps, every 3rd a full step, alpha = 0.5; then the EMA
     weights and caching intervals of the sweep configuration (alpha = 0.1 is the paper's beta = 0.9, alpha = 1
-    plain reuse).  The GPU-fitted basis is handed to the oracle so both sides use the same V."""
+    plain reuse).  Both sides use the same basis: the generator's leading directions."""
     wl = WORKLOADS["tiny"]
     if alpha is not None:
         wl = wl.with_(alpha=alpha, interval=interval, T=17)
@@ -149,7 +150,9 @@ def test_tiny_trajectory_matches_oracle_step_by_step(alpha, interval):
     feats = [torch.stack([s.at(t) for s in streams]) for t in range(wl.T)]
     F0 = feats[0].to(DEV)
     shape = pkg.make_shape(F0, wl.k)
-    V, sigma, _ = pkg.fit_basis(F0, wl.k)
+    # the basis both sides use is the generator's own set of leading directions (nothing fitted on the GPU is
+    # handed to the oracle; the fit has its own tests)
+    V = torch.stack([s.V[:, :wl.k].float() for s in streams]).contiguous().to(DEV)
     pk = pkg.pack_basis(shape, V)
     R = torch.empty_like(F0)
     S = torch.empty(wl.B, wl.N, wl.k, device=DEV)
@@ -252,7 +255,7 @@ def test_mfma_full_step_and_forecast(B, N, D, k):
             assert_close(to_np(R[b]), Rr, "bf16", f"R[{b}]", floor_of=to_np(F[b]))
             assert_close(to_np(S[b]), Sr, "f32", f"S[{b}]")
             assert_close(to_np(Cc[b]), Cr, "f32", f"C[{b}]")
-            Fr = ref_forecast(to_np(S[b]), to_np(V[b]), to_np(R[b]), "bf16")
+            Fr = ref_forecast(Sr, to_np(V[b]), Rr, "bf16")      # the oracle's own state
             assert_close(to_np(Fh[b]), Fr, "bf16", f"Fhat[{b}]")
             # the split-operand arithmetic is far inside the bf16 budget: the error is the output rounding
             assert rel_err(to_np(R[b]), Rr) <= 3e-3 and rel_err(to_np(Fh[b]), Fr) <= 3e-3
@@ -284,16 +287,17 @@ def test_mfma_inplace_and_strided(k):
     for init in (True, False):
         R, S, _, shape, pk = _run_full(buf, D, V, S0, 0.5, init, want_C=False, inplace=True)
         assert pk is not None and shape.ldf == ldf
+        state = []
         for b in range(B):
             Rr, Sr, _ = ref_full_step(to_np(F[b]), to_np(V[b]), to_np(S0[b]), 0.5, init, "bf16")
             assert_close(to_np(R[b, :, :D]), Rr, "bf16", "R in place", floor_of=to_np(F[b]))
             assert_close(to_np(S[b]), Sr, "f32", "S")
+            state.append((Rr, Sr))
         assert torch.equal(R[:, :, D:].cpu(), buf[:, :, D:])
-    Rc = R.clone()
     pkg.svdcache_forecast(shape, S, V.to(DEV), pk, R[:, :, :D], R[:, :, :D])
     torch.cuda.synchronize()
     for b in range(B):
-        assert_close(to_np(R[b, :, :D]), ref_forecast(to_np(S[b]), to_np(V[b]), to_np(Rc[b, :, :D]), "bf16"),
+        assert_close(to_np(R[b, :, :D]), ref_forecast(state[b][1], to_np(V[b]), state[b][0], "bf16"),
                      "bf16", "Fhat in place")
 
 
@@ -343,8 +347,7 @@ def test_mfma_fast_precision_mode_is_within_the_bf16_tolerance(B, N, D, k):
             assert_close(to_np(R[b]), Rr, "bf16", f"R[{b}] mode {mode}", floor_of=to_np(F[b]))
             assert_close(to_np(S[b]), Sr, "bf16", f"S[{b}] mode {mode}")
             assert_close(to_np(Cc[b]), Cr, "bf16", f"C[{b}] mode {mode}")
-            assert_close(to_np(Fh[b]), ref_forecast(to_np(S[b]), to_np(V[b]), to_np(R[b]), "bf16"), "bf16",
-                         f"Fhat[{b}] mode {mode}")
+            assert_close(to_np(Fh[b]), ref_forecast(Sr, to_np(V[b]), Rr, "bf16"), "bf16", f"Fhat[{b}] mode {mode}")
             worst = max(worst, rel_err(to_np(R[b]), Rr))
         errs[mode] = worst
     assert errs[pkg.SVDC_PRECISE] <= 3e-3 and errs[pkg.SVDC_FAST] <= 1.5e-2
@@ -356,42 +359,54 @@ def test_mfma_fast_precision_mode_is_within_the_bf16_tolerance(B, N, D, k):
 
 def _sampled_row_parity(wl, B, blocks_to_check, n_rows, precision=0):
     """Run fit + pack + two full steps + one cached step at full size on GPU-generated features and
-    recompute sampled token rows with the oracle (rows are independent given V and S)."""
-    feats = []
-    for t in (0, wl.interval):
-        Ft = torch.empty(B, wl.N, wl.D, device=DEV, dtype=torch.bfloat16)
-        for b in range(B):
-            Ft[b] = FeatureStream(wl, b, device=DEV).at(t)
-        feats.append(Ft)
+    recompute sampled token rows with the oracle (rows are independent given V and S).  Nothing the GPU
+    computed is handed to the oracle: it gets the generated features, the generator's basis and its own state."""
+    feats = [torch.empty(B, wl.N, wl.D, device=DEV, dtype=torch.bfloat16) for _ in range(2)]
+    Vgen = torch.empty(B, wl.D, wl.k, device=DEV)
+    for b in range(B):
+        fs = FeatureStream(wl, b, device=DEV)
+        feats[0][b], feats[1][b] = fs.at(0), fs.at(wl.interval)
+        Vgen[b] = fs.V[:, :wl.k].float()          # the generator's leading directions: the basis of both sides
+        del fs
     shape = pkg.make_shape(feats[0], wl.k, precision=precision)
     assert pkg.svdcache_has_mfma_path(shape)
-    V, sigma, fro2 = pkg.fit_basis(feats[0], wl.k)
-    pk = pkg.pack_basis(shape, V)
     R = torch.empty_like(feats[0])
     S = torch.empty(B, wl.N, wl.k, device=DEV)
     Cc = torch.empty_like(S)
     Fh = torch.empty_like(R)
+    # fit + pack + step with the FITTED basis, checked by an identity that needs no oracle: right after the
+    # first full step the cached step gives the feature back (up to the bf16 rounding of R and Fhat)
+    V, sigma, fro2 = pkg.fit_basis(feats[0], wl.k)
+    pk = pkg.pack_basis(shape, V)
     pkg.svdcache_full_step(shape, feats[0], V, pk, R, S, None, wl.alpha, True)
-    S0 = S.clone()
-    pkg.svdcache_full_step(shape, feats[1], V, pk, R, S, Cc, wl.alpha, False)
     pkg.svdcache_forecast(shape, S, V, pk, R, Fh)
+    torch.cuda.synchronize()
+    for b in blocks_to_check:
+        Vb = to_np(V[b])
+        assert np.abs(Vb.T @ Vb - np.eye(wl.k)).max() <= 1e-5
+        assert rel_err(to_np(Fh[b][:512]), to_np(feats[0][b][:512])) <= (6e-3 if precision == 0 else 2e-2)
+    # parity of the steps against the oracle, both sides on the generator's basis
+    pk = pkg.pack_basis(shape, Vgen)
+    pkg.svdcache_full_step(shape, feats[0], Vgen, pk, R, S, None, wl.alpha, True)
+    S0 = S.clone()
+    pkg.svdcache_full_step(shape, feats[1], Vgen, pk, R, S, Cc, wl.alpha, False)
+    pkg.svdcache_forecast(shape, S, Vgen, pk, R, Fh)
     torch.cuda.synchronize()
     assert torch.isfinite(R.float()).all() and torch.isfinite(Fh.float()).all() and torch.isfinite(S).all()
     g = torch.Generator().manual_seed(wl.config_id)
     for b in blocks_to_check:
         rows = torch.cat([torch.tensor([0, 1, 15, 16, 31, 32, wl.N - 17, wl.N - 16, wl.N - 1]),
                           torch.randint(0, wl.N, (n_rows,), generator=g)]).unique()
-        Vb = to_np(V[b])
-        assert np.abs(Vb.T @ Vb - np.eye(wl.k)).max() <= 1e-5
+        Vb = to_np(Vgen[b])
         F0r, F1r = to_np(feats[0][b][rows]), to_np(feats[1][b][rows])
         _, S0r, _ = ref_full_step(F0r, Vb, None, wl.alpha, True, "bf16")
         coef_store = "f32" if precision == 0 else "bf16"   # SVDC_FAST rounds V to bf16 in the projection
         assert_close(to_np(S0[b][rows]), S0r, coef_store, f"S after init, block {b}")
-        Rr, S1r, C1r = ref_full_step(F1r, Vb, to_np(S0[b][rows]), wl.alpha, False, "bf16")
+        Rr, S1r, C1r = ref_full_step(F1r, Vb, S0r, wl.alpha, False, "bf16")       # the oracle's own state
         assert_close(to_np(R[b][rows]), Rr, "bf16", f"R block {b}", floor_of=F1r)
         assert_close(to_np(S[b][rows]), S1r, coef_store, f"S block {b}")
         assert_close(to_np(Cc[b][rows]), C1r, coef_store, f"C block {b}")
-        Fr = ref_forecast(to_np(S[b][rows]), Vb, to_np(R[b][rows]), "bf16")
+        Fr = ref_forecast(S1r, Vb, Rr, "bf16")
         assert_close(to_np(Fh[b][rows]), Fr, "bf16", f"Fhat block {b}")
     return sigma, fro2, feats
 
@@ -448,7 +463,7 @@ def test_mfma_float32_features(B, N, D, k):
             assert_close(to_np(R[b]), Rr, "f32", f"R[{b}]", floor_of=to_np(F[b]))
             assert_close(to_np(S[b]), Sr, "f32", f"S[{b}]")
             assert_close(to_np(Cc[b]), Cr, "f32", f"C[{b}]")
-            Fr = ref_forecast(to_np(S[b]), to_np(V[b]), to_np(R[b]), "f32")
+            Fr = ref_forecast(Sr, to_np(V[b]), Rr, "f32")       # the oracle's own state
             assert_close(to_np(Fh[b]), Fr, "f32", f"Fhat[{b}]")
 
 
@@ -490,7 +505,7 @@ def test_flux_block_trajectory_against_a_free_running_oracle():
     fs = FeatureStream(wl, 0, device=DEV)
     F0 = fs.at(0).unsqueeze(0).contiguous()
     shape = pkg.make_shape(F0, wl.k)
-    V, _, _ = pkg.fit_basis(F0, wl.k)
+    V = fs.V[:, :wl.k].float().unsqueeze(0).contiguous()          # the generator's leading directions
     pk = pkg.pack_basis(shape, V)
     assert pk is not None
     Vn = to_np(V[0])

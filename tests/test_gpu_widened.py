@@ -260,8 +260,8 @@ def test_basis_overlap_and_rebase(B, N, D, k):
     assert torch.equal(Sip, Sn)
     for b in range(B):
         Mr = ref_basis_overlap(to_np(Vo[b]), to_np(Vn[b]))
-        assert np.abs(to_np(M[b]) - Mr).max() <= 2e-6
-        assert_close(to_np(Sn[b]), ref_rebase_state(to_np(S[b]), to_np(M[b]), "f32"), "f32", f"rebase block {b}")
+        assert np.abs(to_np(M[b]) - Mr).max() <= 5e-6          # float32 sums over D products of unit vectors
+        assert_close(to_np(Sn[b]), ref_rebase_state(to_np(S[b]), Mr, "f32"), "f32", f"rebase block {b}")
     # exact carry-over inside the same subspace: the cached step gives the same feature before and after
     Vrot = (Vo.double() @ Q).float().contiguous()
     pkg.svdcache_basis_overlap(shape, Vo.to(DEV), Vrot.to(DEV), M)
@@ -274,16 +274,19 @@ def test_basis_overlap_and_rebase(B, N, D, k):
 
 
 def test_refit_on_a_drifted_feature_keeps_the_state_useful():
-    """Fit on F_0, run full steps, refit on a later feature whose subspace has drifted, carry the EMA state
-    over, and compare the cached step in the new basis with the oracle fed the same inputs."""
+    """Full step in the basis of F_0, refit on a later feature whose subspace has drifted, carry the EMA state
+    over and continue.  The two bases are the oracle's exact fits (handed to the GPU, never the other way round)
+    and the oracle runs the same chain on its own state."""
     from oracle import ref_basis_overlap, ref_rebase_state, ref_forecast
     wl = WORKLOADS["flux1"].with_(N=512)
     fs = FeatureStream(wl, 0, device=DEV)
     F0, F1 = fs.at(0).unsqueeze(0).contiguous(), fs.at(wl.interval).unsqueeze(0).contiguous()
     k = wl.k
     shape = pkg.make_shape(F0, k)
-    V0, s0, _ = pkg.fit_basis(F0, k)
-    V1, s1, _ = pkg.fit_basis(F1, k)
+    V0r = ref_fit_basis(to_np(F0[0]), k)[0].astype(np.float32).astype(np.float64)
+    V1r = ref_fit_basis(to_np(F1[0]), k)[0].astype(np.float32).astype(np.float64)
+    V0 = torch.from_numpy(V0r).float().unsqueeze(0).contiguous().to(DEV)
+    V1 = torch.from_numpy(V1r).float().unsqueeze(0).contiguous().to(DEV)
     pk0, pk1 = pkg.pack_basis(shape, V0), pkg.pack_basis(shape, V1)
     R = torch.empty_like(F0)
     S = torch.empty(1, wl.N, k, device=DEV)
@@ -292,21 +295,23 @@ def test_refit_on_a_drifted_feature_keeps_the_state_useful():
     pkg.svdcache_basis_overlap(shape, V0, V1, M)
     S1 = torch.empty_like(S)
     pkg.svdcache_rebase_state(shape, M, S, S1)
-    Cn = torch.empty_like(S)
-    pkg.svdcache_full_step(shape, F1, V1, pk1, R, S1, Cn, 0.5, False)     # EMA continues in the new basis
+    pkg.svdcache_full_step(shape, F1, V1, pk1, R, S1, None, 0.5, False)     # EMA continues in the new basis
     Fh = torch.empty_like(F0)
     pkg.svdcache_forecast(shape, S1, V1, pk1, R, Fh)
+    torch.cuda.synchronize()
+    _, S0r, _ = ref_full_step(to_np(F0[0]), V0r, None, 0.5, True, "bf16")
+    Mr = ref_basis_overlap(V0r, V1r)
+    assert np.abs(to_np(M[0]) - Mr).max() <= 5e-6
+    Rr, Sr, _ = ref_full_step(to_np(F1[0]), V1r, ref_rebase_state(S0r, Mr, "f32"), 0.5, False, "bf16")
+    assert_close(to_np(S1[0]), Sr, "f32", "EMA state after re-basing")
+    assert_close(to_np(Fh[0]), ref_forecast(Sr, V1r, Rr, "bf16"), "bf16", "Fhat")
+    # the synthetic stream keeps its subspace: the GPU's own fits of the two features stay similar (Fig. 1(b))
+    Vg0, s0, _ = pkg.fit_basis(F0, k)
+    Vg1, s1, _ = pkg.fit_basis(F1, k)
     sim_dir = torch.empty(1, k, device=DEV)
     sim_sig = torch.empty(1, device=DEV)
-    pkg.svdcache_basis_similarity(shape, V0, s0, V1, s1, sim_dir, sim_sig)
+    pkg.svdcache_basis_similarity(shape, Vg0, s0, Vg1, s1, sim_dir, sim_sig)
     torch.cuda.synchronize()
-    Mr = ref_basis_overlap(to_np(V0[0]), to_np(V1[0]))
-    assert np.abs(to_np(M[0]) - Mr).max() <= 2e-6
-    S_carry = ref_rebase_state(to_np(S[0]), Mr, "f32")
-    Rr, Sr, Cr = ref_full_step(to_np(F1[0]), to_np(V1[0]), S_carry, 0.5, False, "bf16")
-    assert_close(to_np(S1[0]), Sr, "f32", "EMA state after re-basing")
-    assert_close(to_np(Fh[0]), ref_forecast(to_np(S1[0]), to_np(V1[0]), to_np(R[0]), "bf16"), "bf16", "Fhat")
-    # the synthetic stream keeps its subspace: the leading directions and the spectrum stay similar (Fig. 1(b))
     assert float(sim_sig) > 0.8 and float(sim_dir[0, 0]) > 0.8
 
 
