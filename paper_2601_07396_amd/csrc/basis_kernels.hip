@@ -13,6 +13,7 @@ constexpr int kOvMaxRank = 128;  // overlap / re-basing work up to this rank
 
 // M[b][i][j] = sum_d V_old[b][d][i] * V_new[b][d][j].  Grid (ceil(k / 16), B); thread (ti, tj) of the
 // 16 x 16 arrangement owns M[i0 + ti][tj + 16 c], c = 0..7.  The sum runs over d in ascending order.
+template <int KC>   // column tiles of 16 that hold data: ceil(k / 16), a compile-time loop bound
 __global__ __launch_bounds__(256) void basis_overlap_kernel(const float* __restrict__ Vo,
                                                             const float* __restrict__ Vn, float* M, int D, int k) {
   __shared__ float so[kOvDepth][kOvRows + 1];
@@ -20,31 +21,30 @@ __global__ __launch_bounds__(256) void basis_overlap_kernel(const float* __restr
   const int b = blockIdx.y, i0 = blockIdx.x * kOvRows, t = threadIdx.x, ti = t >> 4, tj = t & 15;
   const float* vo = Vo + (int64_t)b * D * k;
   const float* vn = Vn + (int64_t)b * D * k;
-  float acc[kOvMaxRank / 16];
+  float acc[KC];
 #pragma unroll
-  for (int c = 0; c < kOvMaxRank / 16; ++c) acc[c] = 0.f;
+  for (int c = 0; c < KC; ++c) acc[c] = 0.f;
   for (int d0 = 0; d0 < D; d0 += kOvDepth) {
     for (int e = t; e < kOvDepth * kOvRows; e += 256) {
       const int dd = e / kOvRows, ii = e % kOvRows, d = d0 + dd, i = i0 + ii;
       so[dd][ii] = (d < D && i < k) ? vo[(int64_t)d * k + i] : 0.f;
     }
-    for (int e = t; e < kOvDepth * k; e += 256) {
-      const int dd = e / k, jj = e % k, d = d0 + dd;
-      sn[dd][jj] = d < D ? vn[(int64_t)d * k + jj] : 0.f;
+    for (int e = t; e < kOvDepth * 16 * KC; e += 256) {       // columns beyond k are staged as zeros
+      const int dd = e / (16 * KC), jj = e % (16 * KC), d = d0 + dd;
+      sn[dd][jj] = (d < D && jj < k) ? vn[(int64_t)d * k + jj] : 0.f;
     }
     __syncthreads();
-#pragma unroll 4
+#pragma unroll 8
     for (int dd = 0; dd < kOvDepth; ++dd) {
       const float a = so[dd][ti];
 #pragma unroll
-      for (int c = 0; c < kOvMaxRank / 16; ++c)
-        if (tj + 16 * c < k) acc[c] = __builtin_fmaf(a, sn[dd][tj + 16 * c], acc[c]);
+      for (int c = 0; c < KC; ++c) acc[c] = __builtin_fmaf(a, sn[dd][tj + 16 * c], acc[c]);
     }
     __syncthreads();
   }
   if (i0 + ti < k) {
 #pragma unroll
-    for (int c = 0; c < kOvMaxRank / 16; ++c)
+    for (int c = 0; c < KC; ++c)
       if (tj + 16 * c < k) M[((int64_t)b * k + i0 + ti) * k + tj + 16 * c] = acc[c];
   }
 }
@@ -120,7 +120,16 @@ bool rebase_rank_supported(int k) { return k >= 1 && k <= kOvMaxRank; }
 
 int32_t launch_basis_overlap(const svdc_shape& s, const float* V_old, const float* V_new, float* M, hipStream_t st) {
   dim3 grid((s.k + kOvRows - 1) / kOvRows, s.B);
-  basis_overlap_kernel<<<grid, 256, 0, st>>>(V_old, V_new, M, s.D, s.k);
+  switch ((s.k + 15) / 16) {
+    case 1: basis_overlap_kernel<1><<<grid, 256, 0, st>>>(V_old, V_new, M, s.D, s.k); break;
+    case 2: basis_overlap_kernel<2><<<grid, 256, 0, st>>>(V_old, V_new, M, s.D, s.k); break;
+    case 3: basis_overlap_kernel<3><<<grid, 256, 0, st>>>(V_old, V_new, M, s.D, s.k); break;
+    case 4: basis_overlap_kernel<4><<<grid, 256, 0, st>>>(V_old, V_new, M, s.D, s.k); break;
+    case 5: basis_overlap_kernel<5><<<grid, 256, 0, st>>>(V_old, V_new, M, s.D, s.k); break;
+    case 6: basis_overlap_kernel<6><<<grid, 256, 0, st>>>(V_old, V_new, M, s.D, s.k); break;
+    case 7: basis_overlap_kernel<7><<<grid, 256, 0, st>>>(V_old, V_new, M, s.D, s.k); break;
+    default: basis_overlap_kernel<8><<<grid, 256, 0, st>>>(V_old, V_new, M, s.D, s.k); break;
+  }
   return launch_status();
 }
 
