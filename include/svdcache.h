@@ -11,7 +11,15 @@
  *                        EMA update of the coefficient state (Eq. 8-11)
  *   svdcache_forecast    cached step: Fhat = S V_k^T + R (Sec. 3.4-3.5)
  *
- * all batched over B independent blocks of equal shape.
+ * all batched over B independent blocks of equal shape, and around them
+ *
+ *   svdcache_select_rank / svdcache_truncate_basis       rank by retained energy (Eq. 6), per-block ranks
+ *   svdcache_forecast_combine / svdcache_extrapolation_weights
+ *                                                        cached step with forecasters linear in stored
+ *                                                        coefficient states, optional fused add (Sec. 5.3)
+ *   svdcache_full_step_residual_ema                      full step that smooths the residual too (Sec. 4.5)
+ *   svdcache_basis_overlap / svdcache_rebase_state / svdcache_basis_similarity
+ *                                                        basis reuse across prompts and refits (Sec. 3.3)
  *
  * General conventions
  *   - Every data pointer is a DEVICE pointer (HIP global memory) unless the
