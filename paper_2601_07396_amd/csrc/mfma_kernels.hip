@@ -1,4 +1,4 @@
-// Matrix-core (MFMA) kernels for bf16 features on gfx950.
+// Matrix-core (MFMA) kernels for bf16 and float32 features on gfx950 (float32 operands are split into bf16 parts).
 //
 // All contractions go through v_mfma_f32_16x16x32_bf16 (wave64):
 //     D[m][n] += sum_kk A[m][kk] * B[kk][n],   m, n in 0..15, kk in 0..31
