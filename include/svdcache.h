@@ -73,7 +73,8 @@ typedef enum {
 #define SVDC_MAX_STATES 4
 
 /* One batched problem: B independent blocks of identical shape.
- *   1 <= k <= min(N, D), k <= 1024;  ldf >= D;  block_stride >= (N-1)*ldf + D.
+ *   1 <= B <= 65535;  1 <= k <= min(N, D), k <= 1024;  ldf >= D;  block_stride >= (N-1)*ldf + D;
+ *   N*ldf and B*block_stride at most 2^48 elements (SVDC_E_SHAPE beyond).
  *   Base pointers of F/R/Fhat must be 16-byte aligned; with dtype BF16, D, ldf
  *   and block_stride must be multiples of 8 elements, with F32 multiples of 4. */
 typedef struct {
@@ -183,7 +184,8 @@ int32_t svdcache_truncate_basis(const svdc_shape* shape, float* V, float* sigma,
  * polynomial of degree `order` through x(t), x(t - interval), ..., x(t - order*interval).  order 0 is plain
  * reuse, order 1 the linear trend.  This is how a finite-difference forecaster applied to the principal
  * coefficients (Sec. 5.3) enters svdcache_forecast_combine.
- *   order in 0..SVDC_MAX_STATES-1;  interval != 0;  weights: host array of order+1 floats */
+ *   order in 0..SVDC_MAX_STATES-1;  offset and interval finite, interval != 0 (SVDC_E_PARAM otherwise);
+ *   weights: host array of order+1 floats */
 int32_t svdcache_extrapolation_weights(int32_t order, double offset, double interval, float* weights);
 
 /* Cached step with a forecaster that is linear in stored coefficient states (Sec. 5.3: other predictors

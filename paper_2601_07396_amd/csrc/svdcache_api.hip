@@ -15,8 +15,11 @@ int32_t check_shape(const svdc_shape* s) {
   if (s->precision != SVDC_PRECISE && s->precision != SVDC_FAST) return SVDC_E_PARAM;
   if (s->B < 1 || s->B > 65535 || s->N < 1 || s->D < 1 || s->k < 1) return SVDC_E_SHAPE;
   if (s->k > s->N || s->k > s->D || s->k > 1024) return SVDC_E_SHAPE;
-  if (s->ldf < s->D) return SVDC_E_SHAPE;
-  if (s->block_stride < (int64_t)(s->N - 1) * s->ldf + s->D) return SVDC_E_SHAPE;
+  // At most 2^48 elements from the first to the last block: more than any device holds, and small enough
+  // that no offset or byte count computed from these strides leaves the int64 range.
+  constexpr int64_t kMaxElems = int64_t(1) << 48;
+  if (s->ldf < s->D || s->ldf > kMaxElems / s->N) return SVDC_E_SHAPE;
+  if (s->block_stride < (int64_t)(s->N - 1) * s->ldf + s->D || s->block_stride > kMaxElems / s->B) return SVDC_E_SHAPE;
   const int64_t unit = s->dtype == SVDC_BF16 ? 8 : 4;
   if (s->D % unit || s->ldf % unit || s->block_stride % unit) return SVDC_E_ALIGN;
   return SVDC_OK;
@@ -157,7 +160,8 @@ int32_t svdcache_truncate_basis(const svdc_shape* shape, float* V, float* sigma,
 
 int32_t svdcache_extrapolation_weights(int32_t order, double offset, double interval, float* weights) {
   if (!weights) return SVDC_E_NULL;
-  if (order < 0 || order >= SVDC_MAX_STATES || interval == 0.0 || !(interval == interval) || !(offset == offset))
+  const auto finite = [](double v) { return v - v == 0.0; };   // false for NaN and for +-inf
+  if (order < 0 || order >= SVDC_MAX_STATES || interval == 0.0 || !finite(interval) || !finite(offset))
     return SVDC_E_PARAM;
   // Lagrange weights at x = offset / interval for the nodes 0, -1, ..., -order
   const double x = offset / interval;

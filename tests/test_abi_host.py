@@ -47,6 +47,7 @@ def _shape(**kw):
     (dict(dtype=7), -3), (dict(precision=2), -5), (dict(B=0), -2), (dict(k=0), -2), (dict(k=65), -2), (dict(N=4, k=8), -2),
     (dict(ldf=32), -2), (dict(block_stride=100), -2), (dict(D=66, ldf=66, block_stride=66 * 64), -4),
     (dict(dtype=1, D=68, ldf=68, block_stride=68 * 64), -4),
+    (dict(ldf=1 << 60, block_stride=(1 << 63) - 64), -2), (dict(B=4096, block_stride=1 << 40), -2),   # offsets would leave int64 / 2^48
 ])
 def test_bad_shapes_are_rejected_on_the_host(lib, kw, code):
     s = _shape(**kw)
