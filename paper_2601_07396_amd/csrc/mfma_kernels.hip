@@ -36,6 +36,12 @@ __device__ __forceinline__ f32x4 mfma16(const u32x4& a, const u32x4& b, const f3
                                                  0, 0, 0);
 }
 
+// Direct global-to-LDS load of 16 bytes per lane: lane l's bytes land at lds_wave_base + 16 l.  Counts in vmcnt
+// like any other vector memory load; lds_wave_base must be the same in all lanes of the wave.
+__device__ __forceinline__ void load_to_lds16(const void* gsrc_lane, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds(gsrc_lane, lds_wave_base, 16, 0, 0);
+}
+
 int num_compute_units() {
   int dev = 0, n = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 256;
@@ -292,9 +298,13 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const CoefStates cs,
 // S1 / S2: use the low parts of the basis (and of C) in phase 1 / phase 2.
 // REMA: the residual state is smoothed as well (ablation of Sec. 4.5): R = (1 - alpha_r) Rp + alpha_r (F - C V^T),
 // with the previous residual Rp read chunk by chunk a few chunks ahead; Rp may be the buffer R.
-// F and R may alias: a tile is completely in registers before it is overwritten.
+// LT = 1 (bf16 only): one more row tile per workgroup tile lives in LDS, as an image of the registers it would
+// occupy (96 KB at 3072 channels).  It arrives by direct global-to-LDS loads (lane l's 16 bytes land at
+// base + 16 l), each wave reads back only what it loaded itself, and every basis operand then serves RT + 1
+// row tiles: a third less basis traffic from L2 per token row at RT = 2.
+// F and R may alias: a tile is completely on chip (registers, LDS) before it is overwritten.
 // ---------------------------------------------------------------------------
-template <typename T, int CH, int RT, int KT2, bool S1, bool S2, int RD, bool REMA>
+template <typename T, int CH, int RT, int KT2, bool S1, bool S2, int RD, bool REMA, int LT = 0>
 __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const uint16_t* __restrict__ P,
                                                              T* R, const T* Rp, float alpha_r, float* S, float* C,
                                                              int N, int k, int64_t ldf, int64_t bstride,
@@ -302,7 +312,10 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
                                                              int total) {
   constexpr int KP = KT2 * 32, KT = KT2 * 2, D = CH * 128;
   constexpr int M = CH * KT;   // basis operand items per wave and phase (a high + a low 16-byte word per lane each)
-  __shared__ f32x4 part[kWavesPerGroup][KT][RT][64];
+  constexpr int RA = RT + LT;  // row tiles per workgroup tile: RT in registers, LT in LDS
+  static_assert(LT == 0 || (LT == 1 && !REMA && sizeof(T) == 2), "the LDS row tile is for bf16 features, plain residual");
+  __shared__ f32x4 part[kWavesPerGroup][KT][RA][64];
+  __shared__ u32x4 ftile[LT ? kWavesPerGroup : 1][LT ? CH : 1][LT ? 64 : 1];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
   const int64_t per = (int64_t)D * KP;
   const int cg0 = wave * CH;
@@ -317,8 +330,12 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
     const T* fbase = F + (int64_t)b * bstride + 32 * (cg0 + c) + 8 * g;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const int row = min(tile * 16 * RT + 16 * rt + r, N - 1);
+      const int row = min(tile * 16 * RA + 16 * rt + r, N - 1);
       f[rt][c].load(fbase + (int64_t)row * ldf);
+    }
+    if constexpr (LT > 0) {
+      const int row = min(tile * 16 * RA + 16 * RT + r, N - 1);
+      load_to_lds16(fbase + (int64_t)row * ldf, &ftile[wave][c][0]);
     }
   };
 #pragma unroll
@@ -330,7 +347,7 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
     const u32x4* P1lo = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + per) + lane;
     const u32x4* P2hi = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 2 * per) + lane;
     const u32x4* P2lo = reinterpret_cast<const u32x4*>(P + (int64_t)b * 4 * per + 3 * per) + lane;
-    const int row0 = tile * 16 * RT;
+    const int row0 = tile * 16 * RA;
     T* obase = R + (int64_t)b * bstride + 8 * g;
 
     // ---- phase 1: acc[jt][rt] = C^T[j = 16 jt + 4 g + i][row = 16 rt + r] over this wave's channels.
@@ -344,17 +361,23 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
         rh[m] = p1h[m * 64];
         if (S1) rl[m] = p1l[m * 64];
       }
-    f32x4 acc[KT][RT];
+    f32x4 acc[KT][RA];
 #pragma unroll
     for (int jt = 0; jt < KT; ++jt)
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) acc[jt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int rt = 0; rt < RA; ++rt) acc[jt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    u32x4 lnext;            // the LDS row tile's piece of the next chunk, read one chunk ahead
+    if constexpr (LT > 0) lnext = ftile[wave][0][lane];
     __builtin_amdgcn_sched_barrier(0);
-    u32x4 bh[RT], bl[RT];   // feature operand of the current chunk: exact for bf16; high + low parts for float32
+    u32x4 bh[RA], bl[RA];   // feature operand of the current chunk: exact for bf16; high + low parts for float32
 #pragma unroll
     for (int m = 0; m < M; ++m) {
       const int c = m / KT, jt = m % KT, slot = m % RD;
       if (jt == 0) {
+        if constexpr (LT > 0) {
+          bh[RT] = lnext;
+          if (c + 1 < CH) lnext = ftile[wave][c + 1][lane];
+        }
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
           if constexpr (kF32) {
@@ -367,7 +390,7 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
         }
       }
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
+      for (int rt = 0; rt < RA; ++rt) {
         acc[jt][rt] = mfma16(rh[slot], bh[rt], acc[jt][rt]);
         if (kF32) acc[jt][rt] = mfma16(rh[slot], bl[rt], acc[jt][rt]);
         if (S1) acc[jt][rt] = mfma16(rl[slot], bh[rt], acc[jt][rt]);
@@ -416,12 +439,12 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
 #pragma unroll
     for (int jt = 0; jt < KT; ++jt)
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) part[wave][jt][rt][lane] = acc[jt][rt];
+      for (int rt = 0; rt < RA; ++rt) part[wave][jt][rt][lane] = acc[jt][rt];
     __syncthreads();
 #pragma unroll
     for (int jt = 0; jt < KT; ++jt)
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
+      for (int rt = 0; rt < RA; ++rt) {
         f32x4 s = part[0][jt][rt][lane];
 #pragma unroll
         for (int w = 1; w < kWavesPerGroup; ++w) {
@@ -434,7 +457,7 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
 
     // EMA update (Eq. 11, alpha = 1 - beta) and coefficient output, one wave per row tile
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
+    for (int rt = 0; rt < RA; ++rt) {
       if ((rt % kWavesPerGroup) != wave) continue;
       const int row = row0 + 16 * rt + r;
       if (row >= N) continue;
@@ -456,9 +479,9 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
     }
 
     // coefficient operand of the reconstruction: kk = 8 g + 4 t + i  <->  j = 32 kt + 16 t + 4 g + i
-    u32x4 chi[RT][KT2], clo[RT][KT2];
+    u32x4 chi[RA][KT2], clo[RA][KT2];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
+    for (int rt = 0; rt < RA; ++rt)
 #pragma unroll
       for (int kt = 0; kt < KT2; ++kt) {
         float c8[8];
@@ -468,21 +491,29 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
           for (int i = 0; i < 4; ++i) c8[4 * t + i] = acc[2 * kt + t][rt][i];
         split_operand(c8, &chi[rt][kt], &clo[rt][kt]);
       }
+    if constexpr (LT > 0) lnext = ftile[wave][0][lane];
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- phase 2: residual, chunk by chunk
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-      f32x4 x[RT][2];
+      f32x4 x[RA][2];
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
         for (int t = 0; t < 2; ++t) x[rt][t] = f[rt][c].half(t);
+      if constexpr (LT > 0) {
+        RowPiece<bf16_t> piece;
+        piece.w = lnext;
+        if (c + 1 < CH) lnext = ftile[wave][c + 1][lane];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) x[RT][t] = piece.half(t);
+      }
 #pragma unroll
       for (int tk = 0; tk < 2 * KT2; ++tk) {
         const int t = tk / KT2, kt = tk % KT2, n = c * 2 * KT2 + tk, slot = n % RD;
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
+        for (int rt = 0; rt < RA; ++rt) {
           x[rt][t] = mfma16(qh[slot], chi[rt][kt], x[rt][t]);
           if (S2) {
             x[rt][t] = mfma16(qh[slot], clo[rt][kt], x[rt][t]);
@@ -495,7 +526,7 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
         }
       }
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
+      for (int rt = 0; rt < RA; ++rt) {
         if constexpr (REMA) {
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
@@ -598,14 +629,14 @@ int32_t forecast_by_width(const svdc_shape& s, const CoefStates& cs, const void*
   return forecast_launch<T, 1, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
 }
 
-template <typename T, int CH, int RT, int KT2, bool SPLIT, int RD, bool REMA>
+template <typename T, int CH, int RT, int KT2, bool SPLIT, int RD, bool REMA, int LT = 0>
 int32_t full_step_launch(const svdc_shape& s, const void* F, const void* packed, void* R, float* S, float* C,
                          float alpha, int init, ResidualEma re, hipStream_t st) {
-  const int tiles = (s.N + 16 * RT - 1) / (16 * RT);
+  const int tiles = (s.N + 16 * (RT + LT) - 1) / (16 * (RT + LT));
   const int64_t total = (int64_t)tiles * s.B;
   if (total > 0x7fffffff) return SVDC_E_SHAPE;
   const int grid = (int)std::min<int64_t>(total, num_compute_units());
-  full_step_mfma_kernel<T, CH, RT, KT2, SPLIT, SPLIT, RD, REMA><<<grid, 256, 0, st>>>(
+  full_step_mfma_kernel<T, CH, RT, KT2, SPLIT, SPLIT, RD, REMA, LT><<<grid, 256, 0, st>>>(
       (const T*)F, (const uint16_t*)packed, (T*)R, (const T*)re.prev, re.alpha_r, S, C, s.N, s.k, s.ldf,
       s.block_stride, alpha, init, tiles, (int)total);
   return launch_status();
@@ -643,6 +674,19 @@ int32_t full_step_by_size(const svdc_shape& s, const void* F, const void* packed
   // the variant that also smooths the residual keeps a few chunks of the previous residual in flight: one row
   // tile less
   if (re.prev) return full_step_launch<T, CH, (RT > 1 ? RT - 1 : 1), KT2, SPLIT, RD, true>(s, F, packed, R, S, C, alpha, init, re, st);
+  // bf16 at 3072 channels, rank 33..64: a third row tile in LDS.  Measured at the HunyuanVideo shape: 4 % (split
+  // operands) to 8 % (single operands) less time per launch, 8-10 % on a single 18432-row block.  At rank <= 32 the
+  // packed-basis stream is small enough that a fourth tile gains nothing, at rank 128 the LDS tile only replaces
+  // the second register tile at equal speed.  A taller tile can leave more of the last round of the persistent
+  // grid empty, so the choice compares rounds x tile height x cost per row (0.92 of the register-only tile's).
+  if constexpr (CH == 24 && W == 1 && KT2 == 2) {
+    constexpr int RDL = SPLIT ? 12 : 16;
+    const int64_t cus = num_compute_units();
+    auto tile_count = [&](int ra) { return (int64_t)((s.N + 16 * ra - 1) / (16 * ra)) * s.B; };
+    auto rounds = [&](int ra) { return (double)((tile_count(ra) + cus - 1) / cus); };
+    if (tile_count(RT + 1) >= cus && rounds(RT + 1) * (RT + 1) * 0.92 <= rounds(RT) * RT)
+      return full_step_launch<T, CH, RT, KT2, SPLIT, RDL, false, 1>(s, F, packed, R, S, C, alpha, init, re, st);
+  }
   if constexpr (RT > 1) {
     const int64_t tiles = (int64_t)((s.N + 16 * RT - 1) / (16 * RT)) * s.B;
     if (tiles < num_compute_units())

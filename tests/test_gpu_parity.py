@@ -353,6 +353,36 @@ def test_mfma_fast_precision_mode_is_within_the_bf16_tolerance(B, N, D, k):
     assert errs[pkg.SVDC_PRECISE] <= 3e-3 and errs[pkg.SVDC_FAST] <= 1.5e-2
 
 
+@pytest.mark.parametrize("B,N,k", [(4, 4090, 32), (4, 3060, 64), (2, 4090, 128)])
+def test_full_step_tiles_with_a_row_tile_in_lds(B, N, k):
+    """3072 channels and one round of 256 or more workgroup tiles, each block ending in a partly filled tile.  At
+    rank 64 these are the launches that keep the third row tile of a workgroup tile in LDS (both operand modes);
+    ranks 32 and 128 run the register-only tiles at the same sizes.  Every element is compared, out of place and
+    in place (R aliases F), with and without the coefficient output."""
+    D = 3072
+    F, V, S0 = _lowrank_problem(B, N, D, k, seed=N + k)
+    ref = [ref_full_step(to_np(F[b]), to_np(V[b]), to_np(S0[b]), 0.3, False, "bf16") for b in range(B)]
+    Vd = V.to(DEV)
+    for mode in (pkg.SVDC_PRECISE, pkg.SVDC_FAST):
+        coef = "f32" if mode == pkg.SVDC_PRECISE else "bf16"
+        for inplace in (False, True):
+            Fd = F.to(DEV)
+            shape = pkg.make_shape(Fd, k, precision=mode)
+            pk = pkg.pack_basis(shape, Vd)
+            R = Fd if inplace else torch.full_like(Fd, 7.0)
+            S = S0.clone().to(DEV)
+            Cc = None if inplace else torch.empty(B, N, k, device=DEV)
+            pkg.svdcache_full_step(shape, Fd, Vd, pk, R, S, Cc, 0.3, False)
+            torch.cuda.synchronize()
+            for b in range(B):
+                Rr, Sr, Cr = ref[b]
+                assert_close(to_np(R[b]), Rr, "bf16", f"R[{b}] mode {mode} inplace {inplace}", floor_of=to_np(F[b]))
+                assert_close(to_np(S[b]), Sr, coef, f"S[{b}] mode {mode}")
+                if Cc is not None:
+                    assert_close(to_np(Cc[b]), Cr, coef, f"C[{b}] mode {mode}")
+                assert rel_err(to_np(R[b]), Rr) <= (3e-3 if mode == pkg.SVDC_PRECISE else 1.5e-2)
+
+
 # ---------------------------------------------------------------------------------------------
 # full-size launches (the configurations bench.py times), checked on sampled rows
 # ---------------------------------------------------------------------------------------------
