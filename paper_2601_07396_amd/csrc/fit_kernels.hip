@@ -380,7 +380,7 @@ __global__ __launch_bounds__(256) void chol_inv_reg_kernel(double* G, double* Mi
     for (int jj = 0; jj < BS; ++jj) {
       const int i = BS * ti + ii, j = BS * tj + jj;
       const double v = (j <= i) ? a[ii][jj] : 0.0;
-      Ls[i * LM + j] = v;
+      if (Minv) Ls[i * LM + j] = v;   // the dynamic LDS is only there when the inverse factor is asked for
       if (i < l && j < l) g[(int64_t)i * l + j] = v;
       if (rdiag && i == j && i < l) rdiag[(int64_t)b * l + i] = 1.0 / v;
     }
@@ -524,10 +524,13 @@ __global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* __rest
 //   Lfac  in   [l x l] lower-triangular Cholesky factor of H = Y^T Y
 //   Wout  out  [l x l] row-major, column r = right singular vector of rank r
 //   sigma out  [k] leading singular values
+// acc_w: the rotations are accumulated in W (needs a second l x l matrix).  Without it (65 < l <= 128, where
+// only A fits in LDS) the vectors are recovered at the end from A_final = L^T W by back substitution with L^T,
+// in place, four threads per column; its error is eps64 x cond(L), far below the float32 output.
 // ---------------------------------------------------------------------------
 constexpr int kJacobiThreads = 512;
 
-template <bool a_in_lds, bool w_in_lds>   // compile-time so that LDS accesses are ds_* instructions, not flat ones
+template <bool a_in_lds, bool w_in_lds, bool acc_w>   // compile-time so that LDS accesses are ds_* instructions, not flat ones
 __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __restrict__ Lfac, double* Wout, float* sigma,
                                                      double* gA, double* gW, int l, int k,
                                                      const double* fro_acc, float* fro2) {
@@ -543,7 +546,7 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
   for (int idx = t; idx < l * l; idx += NT) {
     const int c = idx / l, r = idx % l;
     A[c * la + r] = (r <= c) ? Lf[idx] : 0.0;   // A[r][c] = L[c][r]
-    W[c * la + r] = (r == c) ? 1.0 : 0.0;
+    if constexpr (acc_w) W[c * la + r] = (r == c) ? 1.0 : 0.0;
   }
   if (t == 0 && fro2) fro2[b] = (float)fro_acc[b];
   __syncthreads();
@@ -595,15 +598,23 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
           cs = cs * (1.5 - 0.5 * n2 * cs * cs);
           cs = cs * (1.5 - 0.5 * n2 * cs * cs);
           const double sn = cs * tt;
-          double* wp = W + (int64_t)p * la;
-          double* wq = W + (int64_t)q * la;
-          for (int r = gl; r < l; r += tp) {
-            const double x = ap[r], y = aq[r];
-            ap[r] = cs * x - sn * y;
-            aq[r] = sn * x + cs * y;
-            const double u = wp[r], v = wq[r];
-            wp[r] = cs * u - sn * v;
-            wq[r] = sn * u + cs * v;
+          if constexpr (acc_w) {
+            double* wp = W + (int64_t)p * la;
+            double* wq = W + (int64_t)q * la;
+            for (int r = gl; r < l; r += tp) {
+              const double x = ap[r], y = aq[r];
+              ap[r] = cs * x - sn * y;
+              aq[r] = sn * x + cs * y;
+              const double u = wp[r], v = wq[r];
+              wp[r] = cs * u - sn * v;
+              wq[r] = sn * u + cs * v;
+            }
+          } else {
+            for (int r = gl; r < l; r += tp) {
+              const double x = ap[r], y = aq[r];
+              ap[r] = cs * x - sn * y;
+              aq[r] = sn * x + cs * y;
+            }
           }
           if (gl == 0) atomicAdd(&s_rot, 1);
         }
@@ -621,6 +632,24 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
     nrm[j] = s;
   }
   __syncthreads();
+  if constexpr (!acc_w) {
+    // A_final = L^T W: solve for W column by column, in place.  Threads 4 j .. 4 j + 3 share column j: each sums
+    // every fourth term of  x_i = (a_i - sum_{m > i} L[m][i] x_m) / L[i][i],  i = l - 1 .. 0.
+    const int j = t >> 2, part = t & 3;
+    if (j < l) {
+      double* xj = A + (int64_t)j * la;
+      for (int i = l - 1; i >= 0; --i) {
+        double acc = 0.0;
+        for (int m = i + 1 + part; m < l; m += 4) acc += Lf[(int64_t)m * l + i] * xj[m];
+        acc += __shfl_xor(acc, 1, kWave);
+        acc += __shfl_xor(acc, 2, kWave);
+        // all four lanes hold the same sum and store the same value: every lane's later loads follow its own store
+        xj[i] = (xj[i] - acc) / Lf[(int64_t)i * l + i];
+      }
+    }
+    __syncthreads();
+    W = A;
+  }
   double* wo = Wout + (int64_t)b * l * l;
   for (int j = t; j < l; j += NT) {
     const double nj = nrm[j];
@@ -737,9 +766,13 @@ void gram(const float* A, double* G, double* Gpart, int B, int rows, int l, hipS
 int32_t chol_inv(double* G, double* Minv, int B, int l, hipStream_t st, double* rdiag = nullptr) {
   if (l <= 64) {
     constexpr int LM = 64;
-    const size_t bytes = ((size_t)LM * LM + (size_t)LM * (LM + 1)) * sizeof(double);
+    const size_t bytes = Minv ? ((size_t)LM * LM + (size_t)LM * (LM + 1)) * sizeof(double) : 0;
     if (set_dyn_lds((const void*)chol_inv_reg_kernel<4>, bytes) != SVDC_OK) return SVDC_E_HIP;
     chol_inv_reg_kernel<4><<<B, 256, bytes, st>>>(G, Minv, rdiag, l, 1e-14);
+    return SVDC_OK;
+  }
+  if (l <= 128 && !Minv) {   // factor only (8 x 8 block per thread); the inverse would not fit in LDS beside it
+    chol_inv_reg_kernel<8><<<B, 256, 0, st>>>(G, nullptr, rdiag, l, 1e-14);
     return SVDC_OK;
   }
   const size_t bytes = (size_t)l * l * sizeof(double);
@@ -769,13 +802,14 @@ int32_t rows_times_small(const float* In, const double* M, float* Out, int B, in
 // orthonormality at float32 round-off; the result is then back in Zin.
 // Out = In * L^-T with L the Cholesky factor of In^T In (left in G by chol_inv)
 int32_t cholqr_apply(const float* In, float* Out, double* G, double* M, int B, int rows, int l, hipStream_t st) {
-  if (l <= 64) {
+  if (l <= 128) {
     // M receives the reciprocal diagonal of L (its first l entries per block)
     if (chol_inv(G, nullptr, B, l, st, M) != SVDC_OK) return SVDC_E_HIP;
     dim3 grid((rows + 255) / 256, B);
     if (l <= 16) tri_solve_rows_kernel<16><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
     else if (l <= 32) tri_solve_rows_kernel<32><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
-    else tri_solve_rows_kernel<64><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
+    else if (l <= 64) tri_solve_rows_kernel<64><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
+    else tri_solve_rows_kernel<128><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
     return SVDC_OK;
   }
   if (chol_inv(G, M, B, l, st) != SVDC_OK) return SVDC_E_HIP;
@@ -851,18 +885,18 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
     sumsq_kernel<T><<<dim3((s.N + rpg - 1) / rpg, B), 256, 0, st>>>(F, misc, s.N, s.D, s.ldf, s.block_stride, rpg);
   }
   const size_t mat = (size_t)l * (l + 1) * sizeof(double);
-  const int a_in_lds = mat <= kLdsBudget;
-  const int w_in_lds = 2 * mat <= kLdsBudget;
+  const bool a_in_lds = mat <= kLdsBudget;          // l <= 138 (129 KB at l = 128)
+  const bool w_in_lds = 2 * mat <= kLdsBudget;      // l <= 97
   const size_t lds = (a_in_lds ? mat : 0) + (w_in_lds ? mat : 0);
   double* gW = Wg + (int64_t)B * l * (l + 1);
   if (a_in_lds && w_in_lds) {
-    if (set_dyn_lds((const void*)jacobi_kernel<true, true>, lds) != SVDC_OK) return SVDC_E_HIP;
-    jacobi_kernel<true, true><<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+    if (set_dyn_lds((const void*)jacobi_kernel<true, true, true>, lds) != SVDC_OK) return SVDC_E_HIP;
+    jacobi_kernel<true, true, true><<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
   } else if (a_in_lds) {
-    if (set_dyn_lds((const void*)jacobi_kernel<true, false>, lds) != SVDC_OK) return SVDC_E_HIP;
-    jacobi_kernel<true, false><<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+    if (set_dyn_lds((const void*)jacobi_kernel<true, false, false>, lds) != SVDC_OK) return SVDC_E_HIP;
+    jacobi_kernel<true, false, false><<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
   } else {
-    jacobi_kernel<false, false><<<B, kJacobiThreads, 0, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+    jacobi_kernel<false, false, true><<<B, kJacobiThreads, 0, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
   }
   if (rows_times_small(Q, M, V, B, s.D, l, s.k, l, st) != SVDC_OK) return SVDC_E_HIP;
   return launch_status();

@@ -318,6 +318,24 @@ def test_fit_basis_mfma_path(N, D, k):
         _fit_checks(F[b], V[b], sigma[b], fro2[b], k, "bf16")
 
 
+@pytest.mark.parametrize("dtype,k,p,rank", [(torch.float32, 50, 50, 55), (torch.float32, 60, 64, 124),
+                                             (torch.bfloat16, 56, 56, 60)], ids=["f32-l100", "f32-l124", "bf16-l112"])
+def test_fit_basis_wide_sketch_low_rank_features(dtype, k, p, rank):
+    """Sketch widths 98..128: the small SVD keeps only one l x l matrix on chip and recovers the right vectors
+    from the Cholesky factor at the end.  Features of exact rank < l (float32) make that factor as ill conditioned
+    as the diagonal shift allows; the leading k directions must still come out orthonormal and exact."""
+    store = "f32" if dtype == torch.float32 else "bf16"
+    g = torch.Generator().manual_seed(k * 100 + rank)
+    N, D = 400, 256
+    left = torch.linalg.qr(torch.randn(N, rank, generator=g, dtype=torch.float64))[0]
+    right = torch.linalg.qr(torch.randn(D, rank, generator=g, dtype=torch.float64))[0]
+    spec = 10.0 * torch.arange(1, rank + 1, dtype=torch.float64) ** -0.8
+    F = ((left * spec) @ right.T).to(dtype).unsqueeze(0).contiguous()
+    V, sigma, fro2 = pkg.fit_basis(F.to(DEV), k, p=p, q=4)
+    torch.cuda.synchronize()
+    _fit_checks(F[0], V[0], sigma[0], fro2[0], k, store)
+
+
 def test_fit_basis_flux_block_full_size():
     """One FLUX-shaped block (4608 x 3072 bf16, k = 32) at full size against the exact decomposition."""
     wl = WORKLOADS["flux1"]
@@ -449,6 +467,14 @@ def test_flux57_full_size_launch_sampled_rows():
     _, sr, fr = ref_fit_basis(to_np(feats[0][56]), wl.k)
     assert np.abs(to_np(sigma[56]) / sr - 1).max() <= TOL["bf16"]
     assert abs(float(fro2[56]) / fr - 1) <= 1e-5
+
+
+@pytest.mark.parametrize("k", [16, 64])
+def test_flux57_full_size_launch_other_ranks(k):
+    """Config 3 lists the ranks 16, 32 and 64: the same 57-block launches at the other two ranks (rank 64 runs the
+    full step with 48-row tiles whose third row tile sits in LDS, over 22 rounds of the persistent grid)."""
+    wl = WORKLOADS["flux57"].with_(k=k)
+    _sampled_row_parity(wl, wl.B, blocks_to_check=[0, 31, 56], n_rows=64)
 
 
 def test_flux57_full_size_launch_fast_mode():
