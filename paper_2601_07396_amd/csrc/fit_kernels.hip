@@ -305,24 +305,23 @@ __global__ __launch_bounds__(256) void rows_times_small_kernel(const float* __re
 }
 
 // ---------------------------------------------------------------------------
-// Register-blocked version of chol_inv_kernel for l <= 16 * BS (BS = 4 or 8):
+// Register-blocked Cholesky factor for l <= 16 * BS (BS = 4 or 8), factor only:
 // thread (ti, tj) of a 16 x 16 grid owns the BS x BS block (ti, tj) of the matrix
-// in registers.  Right-looking Cholesky: per column c the owners publish the
-// column through LDS (double buffered, one barrier per column) and every thread
-// applies the rank-1 update to its block.  The inverse factor is then formed
-// column by column (one thread per column) from the factor in LDS.
+// in registers; a wave owns four block columns, so the 16 threads that hold the
+// current column sit in one wave and the waves whose columns are finished only
+// pass the barrier.  Right-looking: per column c the owners publish the column
+// through LDS (double buffered, one barrier per column) and every thread at or
+// below the diagonal and right of c applies the rank-1 update to its block; only
+// the block column that contains c needs per-element conditions.
+//   G      in/out  lower triangle = L with G + shift I = L L^T, upper triangle zeroed
+//   rdiag  out     (nullable) 1 / L[i][i]
 // ---------------------------------------------------------------------------
 template <int BS>
-__global__ __launch_bounds__(256) void chol_inv_reg_kernel(double* G, double* Minv, double* rdiag, int l,
-                                                         double rel_shift) {
+__global__ __launch_bounds__(256) void chol_reg_kernel(double* G, double* rdiag, int l, double rel_shift) {
   constexpr int LM = 16 * BS;          // padded matrix size
-  constexpr int LX = LM + 1;           // padded row stride of the inverse (bank spread)
-  extern __shared__ double dyn_lds[];
-  double* Ls = dyn_lds;                // [LM][LM] factor, row-major
-  double* Xs = dyn_lds + LM * LM;      // [LM][LX] row j = column j of L^-1
   __shared__ double colbuf[2][LM];
   __shared__ double s_shift;
-  const int b = blockIdx.x, t = threadIdx.x, ti = t >> 4, tj = t & 15;
+  const int b = blockIdx.x, t = threadIdx.x, tj = t >> 4, ti = t & 15;
   double* g = G + (int64_t)b * l * l;
   if (t < kWave) {
     double mx = 0.0;
@@ -342,17 +341,21 @@ __global__ __launch_bounds__(256) void chol_inv_reg_kernel(double* G, double* Mi
       if (i == j && i < l) v += s_shift;
       a[ii][jj] = v;
     }
+  const bool below = ti > tj;          // every element of the block is below the diagonal
   for (int c = 0; c < l; ++c) {
     double* col = colbuf[c & 1];
-    if (tj == c / BS) {
-      const int jj = c % BS;
+    const int cb = c / BS, cq = c % BS;
+    if (tj == cb && ti >= tj) {        // publish rows BS ti .. BS ti + BS - 1 of column c
 #pragma unroll
-      for (int ii = 0; ii < BS; ++ii)
+      for (int ii = 0; ii < BS; ++ii) {
+        double v = a[ii][0];
 #pragma unroll
-        for (int q = 0; q < BS; ++q)
-          if (q == jj) col[BS * ti + ii] = a[ii][q];
+        for (int q = 1; q < BS; ++q) v = (q == cq) ? a[ii][q] : v;
+        col[BS * ti + ii] = v;
+      }
     }
     __syncthreads();
+    if (tj < cb || ti < tj) continue;  // block column finished, or block above the diagonal
     const double piv2 = fmax(col[c], 1e-300);
     // 1 / sqrt(piv2): hardware estimate refined by two Newton steps (an exact sqrt and a division per
     // column would dominate this kernel)
@@ -360,19 +363,32 @@ __global__ __launch_bounds__(256) void chol_inv_reg_kernel(double* G, double* Mi
     rs = rs * (1.5 - 0.5 * piv2 * rs * rs);
     rs = rs * (1.5 - 0.5 * piv2 * rs * rs);
     const double piv = piv2 * rs, inv = rs * rs;
-    double ci[BS], cj[BS];
+    double ci[BS], cjs[BS];
 #pragma unroll
     for (int ii = 0; ii < BS; ++ii) ci[ii] = col[BS * ti + ii];
 #pragma unroll
-    for (int jj = 0; jj < BS; ++jj) cj[jj] = col[BS * tj + jj];
+    for (int jj = 0; jj < BS; ++jj) cjs[jj] = col[BS * tj + jj] * inv;
+    if (tj > cb) {                     // all columns of the block are right of c
+      if (below) {
 #pragma unroll
-    for (int ii = 0; ii < BS; ++ii)
+        for (int ii = 0; ii < BS; ++ii)
 #pragma unroll
-      for (int jj = 0; jj < BS; ++jj) {
-        const int i = BS * ti + ii, j = BS * tj + jj;
-        if (j > c && i >= j) a[ii][jj] -= ci[ii] * cj[jj] * inv;
-        else if (j == c && i >= c) a[ii][jj] = (i == c) ? piv : ci[ii] * rs;
+          for (int jj = 0; jj < BS; ++jj) a[ii][jj] -= ci[ii] * cjs[jj];
+      } else {
+#pragma unroll
+        for (int ii = 0; ii < BS; ++ii)
+#pragma unroll
+          for (int jj = 0; jj <= ii; ++jj) a[ii][jj] -= ci[ii] * cjs[jj];
       }
+    } else {                           // the block column that contains c
+#pragma unroll
+      for (int ii = 0; ii < BS; ++ii)
+#pragma unroll
+        for (int jj = 0; jj < BS; ++jj) {
+          if (jj > cq && (below || ii >= jj)) a[ii][jj] -= ci[ii] * cjs[jj];
+          else if (jj == cq && (below || ii >= cq)) a[ii][jj] = (!below && ii == cq) ? piv : ci[ii] * rs;
+        }
+    }
   }
 #pragma unroll
   for (int ii = 0; ii < BS; ++ii)
@@ -380,28 +396,9 @@ __global__ __launch_bounds__(256) void chol_inv_reg_kernel(double* G, double* Mi
     for (int jj = 0; jj < BS; ++jj) {
       const int i = BS * ti + ii, j = BS * tj + jj;
       const double v = (j <= i) ? a[ii][jj] : 0.0;
-      if (Minv) Ls[i * LM + j] = v;   // the dynamic LDS is only there when the inverse factor is asked for
       if (i < l && j < l) g[(int64_t)i * l + j] = v;
       if (rdiag && i == j && i < l) rdiag[(int64_t)b * l + i] = 1.0 / v;
     }
-  __syncthreads();
-  if (!Minv) return;
-  // column j of L^-1 by forward substitution, one thread per column
-  for (int j = t; j < l; j += 256) {
-    double* xj = Xs + j * LX;
-    xj[j] = 1.0 / Ls[j * LM + j];
-    for (int i = j + 1; i < l; ++i) {
-      double sacc = 0.0;
-      for (int mm = j; mm < i; ++mm) sacc += Ls[i * LM + mm] * xj[mm];
-      xj[i] = -sacc / Ls[i * LM + i];
-    }
-  }
-  __syncthreads();
-  double* m = Minv + (int64_t)b * l * l;
-  for (int idx = t; idx < l * l; idx += 256) {
-    const int j = idx / l, i = idx % l;
-    m[idx] = (i >= j) ? Xs[j * LX + i] : 0.0;    // row j of Minv = column j of L^-1  (Minv = L^-T)
-  }
 }
 
 // ---------------------------------------------------------------------------
@@ -528,6 +525,24 @@ __global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* __rest
 // only A fits in LDS) the vectors are recovered at the end from A_final = L^T W by back substitution with L^T,
 // in place, four threads per column; its error is eps64 x cond(L), far below the float32 output.
 // ---------------------------------------------------------------------------
+// x from the lane that the DPP control word selects (both halves of the double)
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double x) {
+  const int lo = __double2loint(x), hi = __double2hiint(x);
+  return __hiloint2double(__builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xf, 0xf, true),
+                          __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xf, 0xf, true));
+}
+// Sum over aligned groups of min(width, 16) lanes (width a power of two); every lane of a group gets the sum.
+// Lane i adds lane i^1, then i^2 (quad permutations); once the quads are uniform, mirroring a half row (i <-> 7-i)
+// and then a row (i <-> 15-i) brings in the other quads.
+__device__ __forceinline__ double row_sum(double x, int width) {
+  if (width >= 2) x += dpp_move<0xB1>(x);    // quad_perm [1,0,3,2]
+  if (width >= 4) x += dpp_move<0x4E>(x);    // quad_perm [2,3,0,1]
+  if (width >= 8) x += dpp_move<0x141>(x);   // row_half_mirror
+  if (width >= 16) x += dpp_move<0x140>(x);  // row_mirror
+  return x;
+}
+
 constexpr int kJacobiThreads = 512;
 
 template <bool a_in_lds, bool w_in_lds, bool acc_w>   // compile-time so that LDS accesses are ds_* instructions, not flat ones
@@ -575,7 +590,10 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
           const double x = ap[r], y = aq[r];
           al += x * x; be += y * y; ga += x * y;
         }
-        for (int o = tp >> 1; o > 0; o >>= 1) {
+        // sums over the tp lanes of the pair: inside a row of 16 lanes with data-parallel-primitive moves (no LDS
+        // round trip as in a shuffle), across rows with shuffles
+        al = row_sum(al, tp); be = row_sum(be, tp); ga = row_sum(ga, tp);
+        for (int o = tp >> 1; o >= 16; o >>= 1) {
           al += __shfl_xor(al, o, kWave);
           be += __shfl_xor(be, o, kWave);
           ga += __shfl_xor(ga, o, kWave);
@@ -764,15 +782,9 @@ void gram(const float* A, double* G, double* Gpart, int B, int rows, int l, hipS
 }
 
 int32_t chol_inv(double* G, double* Minv, int B, int l, hipStream_t st, double* rdiag = nullptr) {
-  if (l <= 64) {
-    constexpr int LM = 64;
-    const size_t bytes = Minv ? ((size_t)LM * LM + (size_t)LM * (LM + 1)) * sizeof(double) : 0;
-    if (set_dyn_lds((const void*)chol_inv_reg_kernel<4>, bytes) != SVDC_OK) return SVDC_E_HIP;
-    chol_inv_reg_kernel<4><<<B, 256, bytes, st>>>(G, Minv, rdiag, l, 1e-14);
-    return SVDC_OK;
-  }
-  if (l <= 128 && !Minv) {   // factor only (8 x 8 block per thread); the inverse would not fit in LDS beside it
-    chol_inv_reg_kernel<8><<<B, 256, 0, st>>>(G, nullptr, rdiag, l, 1e-14);
+  if (!Minv && l <= 128) {   // factor only: register blocked
+    if (l <= 64) chol_reg_kernel<4><<<B, 256, 0, st>>>(G, rdiag, l, 1e-14);
+    else chol_reg_kernel<8><<<B, 256, 0, st>>>(G, rdiag, l, 1e-14);
     return SVDC_OK;
   }
   const size_t bytes = (size_t)l * l * sizeof(double);
