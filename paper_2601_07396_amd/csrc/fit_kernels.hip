@@ -545,7 +545,10 @@ __device__ __forceinline__ double row_sum(double x, int width) {
 
 constexpr int kJacobiThreads = 512;
 
-template <bool a_in_lds, bool w_in_lds, bool acc_w>   // compile-time so that LDS accesses are ds_* instructions, not flat ones
+// NE > 0 (matrices in LDS): a lane handles exactly NE elements of a column, NE >= ceil(l / lanes per pair), so the
+// element loops unroll with a fixed trip count, their LDS loads are issued together, and the elements of A stay in
+// registers between the dot products and the rotation.  NE = 0: loops of run-time length (matrices in global memory).
+template <bool a_in_lds, bool w_in_lds, bool acc_w, int NE>   // compile-time so that LDS accesses are ds_* instructions, not flat ones
 __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __restrict__ Lfac, double* Wout, float* sigma,
                                                      double* gA, double* gW, int l, int k,
                                                      const double* fro_acc, float* fro2) {
@@ -586,9 +589,23 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
         double* ap = A + (int64_t)p * la;
         double* aq = A + (int64_t)q * la;
         double al = 0.0, be = 0.0, ga = 0.0;
-        for (int r = gl; r < l; r += tp) {
-          const double x = ap[r], y = aq[r];
-          al += x * x; be += y * y; ga += x * y;
+        double xs[NE > 0 ? NE : 1], ys[NE > 0 ? NE : 1];
+        if constexpr (NE > 0) {
+#pragma unroll
+          for (int e = 0; e < NE; ++e) {
+            const int r = gl + e * tp;
+            xs[e] = r < l ? ap[r] : 0.0;
+            ys[e] = r < l ? aq[r] : 0.0;
+          }
+#pragma unroll
+          for (int e = 0; e < NE; ++e) {
+            al += xs[e] * xs[e]; be += ys[e] * ys[e]; ga += xs[e] * ys[e];
+          }
+        } else {
+          for (int r = gl; r < l; r += tp) {
+            const double x = ap[r], y = aq[r];
+            al += x * x; be += y * y; ga += x * y;
+          }
         }
         // sums over the tp lanes of the pair: inside a row of 16 lanes with data-parallel-primitive moves (no LDS
         // round trip as in a shuffle), across rows with shuffles
@@ -616,7 +633,31 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
           cs = cs * (1.5 - 0.5 * n2 * cs * cs);
           cs = cs * (1.5 - 0.5 * n2 * cs * cs);
           const double sn = cs * tt;
-          if constexpr (acc_w) {
+          if constexpr (NE > 0) {
+            double* wp = W + (int64_t)p * la;
+            double* wq = W + (int64_t)q * la;
+            double us[acc_w ? NE : 1], vs[acc_w ? NE : 1];
+            if constexpr (acc_w) {
+#pragma unroll
+              for (int e = 0; e < NE; ++e) {
+                const int r = gl + e * tp;
+                us[e] = r < l ? wp[r] : 0.0;
+                vs[e] = r < l ? wq[r] : 0.0;
+              }
+            }
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+              const int r = gl + e * tp;
+              if (r < l) {
+                ap[r] = cs * xs[e] - sn * ys[e];
+                aq[r] = sn * xs[e] + cs * ys[e];
+                if constexpr (acc_w) {
+                  wp[r] = cs * us[e] - sn * vs[e];
+                  wq[r] = sn * us[e] + cs * vs[e];
+                }
+              }
+            }
+          } else if constexpr (acc_w) {
             double* wp = W + (int64_t)p * la;
             double* wq = W + (int64_t)q * la;
             for (int r = gl; r < l; r += tp) {
@@ -897,19 +938,35 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
     sumsq_kernel<T><<<dim3((s.N + rpg - 1) / rpg, B), 256, 0, st>>>(F, misc, s.N, s.D, s.ldf, s.block_stride, rpg);
   }
   const size_t mat = (size_t)l * (l + 1) * sizeof(double);
-  const bool a_in_lds = mat <= kLdsBudget;          // l <= 138 (129 KB at l = 128)
+  const bool a_in_lds = l <= 128;                   // 129 KB at l = 128
   const bool w_in_lds = 2 * mat <= kLdsBudget;      // l <= 97
   const size_t lds = (a_in_lds ? mat : 0) + (w_in_lds ? mat : 0);
   double* gW = Wg + (int64_t)B * l * (l + 1);
+  // elements of a column per lane, as the kernel derives them: lanes per pair = largest power of two <= 64 with
+  // pairs x lanes <= threads
+  const int npairs = ((l + 1) & ~1) / 2;
+  int tp = 64;
+  while (tp > 1 && tp * npairs > kJacobiThreads) tp >>= 1;
+  const int ne = (l + tp - 1) / tp;
+  auto launch = [&](auto kernel) -> int32_t {
+    if (set_dyn_lds((const void*)kernel, lds) != SVDC_OK) return SVDC_E_HIP;
+    kernel<<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+    return SVDC_OK;
+  };
+  int32_t jrc = SVDC_OK;
   if (a_in_lds && w_in_lds) {
-    if (set_dyn_lds((const void*)jacobi_kernel<true, true, true>, lds) != SVDC_OK) return SVDC_E_HIP;
-    jacobi_kernel<true, true, true><<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+    if (ne <= 1) jrc = launch(jacobi_kernel<true, true, true, 1>);
+    else if (ne <= 2) jrc = launch(jacobi_kernel<true, true, true, 2>);
+    else if (ne <= 4) jrc = launch(jacobi_kernel<true, true, true, 4>);
+    else if (ne <= 8) jrc = launch(jacobi_kernel<true, true, true, 8>);
+    else jrc = launch(jacobi_kernel<true, true, true, 16>);
   } else if (a_in_lds) {
-    if (set_dyn_lds((const void*)jacobi_kernel<true, false, false>, lds) != SVDC_OK) return SVDC_E_HIP;
-    jacobi_kernel<true, false, false><<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+    if (ne <= 8) jrc = launch(jacobi_kernel<true, false, false, 8>);
+    else jrc = launch(jacobi_kernel<true, false, false, 16>);
   } else {
-    jacobi_kernel<false, false, true><<<B, kJacobiThreads, 0, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+    jacobi_kernel<false, false, true, 0><<<B, kJacobiThreads, 0, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
   }
+  if (jrc != SVDC_OK) return jrc;
   if (rows_times_small(Q, M, V, B, s.D, l, s.k, l, st) != SVDC_OK) return SVDC_E_HIP;
   return launch_status();
 }
