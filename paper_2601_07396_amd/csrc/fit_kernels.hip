@@ -473,7 +473,9 @@ __global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* __rest
   // broadcasts (as scalar loads its 32 KB at l = 64 overflow the scalar cache)
   __shared__ double Lf[LMAX * LMAX];
   __shared__ double rd[LMAX];
-  for (int e = t; e < l * l; e += 256) Lf[e] = Lfac[(int64_t)b * l * l + e];
+  // rows of L at a compile-time stride: every LDS offset below is then a constant and neighbouring elements of a
+  // row are fetched by one wide read
+  for (int e = t; e < l * l; e += 256) Lf[(e / l) * LMAX + e % l] = Lfac[(int64_t)b * l * l + e];
   if (t < l) rd[t] = rdiag[(int64_t)b * l + t];
   __syncthreads();
   const int64_t row = (int64_t)blockIdx.x * 256 + t;
@@ -498,7 +500,7 @@ __global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* __rest
     if (j < l) {
       double s = q[j];
 #pragma unroll
-      for (int i = 0; i < j; ++i) s -= q[i] * Lf[j * l + i];
+      for (int i = 0; i < j; ++i) s -= q[i] * Lf[j * LMAX + i];
       q[j] = s * rd[j];
     }
   }
