@@ -769,7 +769,11 @@ bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan)
   const size_t B = s.B;
   plan->off_Q = off; off = align_up(off + B * s.D * l * sizeof(float), 256);
   plan->off_Z = off; off = align_up(off + B * s.D * l * sizeof(float), 256);
-  plan->off_Y = off; off = align_up(off + B * (size_t)s.N * l * sizeof(float), 256);
+  // Y as float32 rows; the matrix-core path also keeps its packed bf16 form there between a projection and the
+  // back-projection that follows (never both at once)
+  size_t y_bytes = B * (size_t)s.N * l * sizeof(float);
+  if (fit_mfma_supported(s, l)) y_bytes = std::max(y_bytes, fit_mfma_packed_y_bytes(s, l));
+  plan->off_Y = off; off = align_up(off + y_bytes, 256);
   plan->off_G = off; off = align_up(off + B * l * l * sizeof(double), 256);
   plan->off_Gp = off; off = align_up(off + B * kGramSlices * (size_t)l * l * sizeof(double), 256);
   plan->off_M = off; off = align_up(off + B * l * l * sizeof(double), 256);
@@ -913,7 +917,7 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   auto project = [&](bool last) {
     if (pl.mfma) {
       fit_mfma_pack_q(s, l, Q, Qp, st);
-      fit_mfma_project(s, l, F, Qp, Y, (last && want_fro) ? misc : nullptr, last, st);
+      fit_mfma_project(s, l, F, Qp, Y, last ? nullptr : (void*)Y, (last && want_fro) ? misc : nullptr, last, st);
       if (last && want_fro) fro_done = true;
     } else {
       gemm_fq<T>(s, l, F, Q, Y, st);
@@ -922,7 +926,7 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   for (int it = 0; it < pl.q; ++it) {
     project(false);
     if (pl.mfma) {
-      fit_mfma_backproject(s, l, F, Y, Z, st);
+      fit_mfma_backproject(s, l, F, Y, Y, Z, st);   // Y holds the packed form here
     } else {
       gemm_fty<T>(s, l, F, Y, Z, st);
     }

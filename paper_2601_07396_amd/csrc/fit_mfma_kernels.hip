@@ -40,6 +40,22 @@ __global__ __launch_bounds__(256) void pack_q_kernel(const float* __restrict__ Q
   p[per + idx] = __builtin_bit_cast(uint16_t, lo);
 }
 
+// Packed Y for the back-projection: Y rounded to bf16, already in the layout of its MFMA operand, so that the
+// back-projection fetches an operand with one 16-byte load per lane instead of 8 scalar loads and 4 conversions.
+// A 32-row step s and coefficient tile jt form one 1 KB word; lane (r, g), element e holds
+//   Y[32 s + 16 (e / 4) + 4 g + e % 4][16 jt + r]      (0 for rows >= N),
+// i.e. the lane's four accumulator rows of the step's first 16-row tile followed by those of the second.  The
+// back-projection contracts over the rows of a step in this same order.  Index: ((b nsteps + s) KT + jt) 64 + lane.
+__device__ __forceinline__ u32x4 pack_y_word(const f32x4& t0, const f32x4& t1, int row, int N) {
+  f32x4 a = t0, c = t1;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (row + i >= N) a[i] = 0.f;
+    if (row + 16 + i >= N) c[i] = 0.f;
+  }
+  return u32x4{pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(c[0], c[1]), pack_bf16(c[2], c[3])};
+}
+
 // ---------------------------------------------------------------------------
 // project: Y = F Q for a group of TG 16-row tiles per workgroup, no atomics.
 // The workgroup walks over the channel slabs (128 * NCW channels each); for one
@@ -56,8 +72,9 @@ __global__ __launch_bounds__(256) void pack_q_kernel(const float* __restrict__ Q
 template <int NCW, int KT, int TG, bool SPLIT, bool FRO>
 __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __restrict__ F,
                                                                const uint16_t* __restrict__ Qp, float* Y,
-                                                               double* fro_acc, int N, int D, int l, int64_t ldf,
-                                                               int64_t bstride, int NS, int groups_per_block) {
+                                                               u32x4* Yp, double* fro_acc, int N, int D, int l,
+                                                               int64_t ldf, int64_t bstride, int NS,
+                                                               int groups_per_block) {
   constexpr int PD = 2;
   static_assert(TG % PD == 0, "prefetch ring must divide the tile group");
   __shared__ f32x4 part[kWaves][2][KT][64];
@@ -134,6 +151,7 @@ __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __r
 
   // add the four waves' partial sums, two row tiles per round
   float* ybase = Y + (int64_t)b * N * l;
+  const int nsteps = (N + 31) / 32;
 #pragma unroll
   for (int rd = 0; rd < TG / 2; ++rd) {
 #pragma unroll
@@ -141,6 +159,28 @@ __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __r
 #pragma unroll
       for (int jt = 0; jt < KT; ++jt) part[wave][tt][jt][lane] = acc[2 * rd + tt][jt];
     __syncthreads();
+    if (Yp) {
+      // packed output for the back-projection: the two tiles of this round are one 32-row step (see pack_y_word)
+      const int step = (tile0 + 2 * rd) / 2;
+#pragma unroll
+      for (int jt = 0; jt < KT; ++jt) {
+        if ((jt % kWaves) != wave) continue;
+        f32x4 s2[2];
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          f32x4 s = part[0][tt][jt][lane];
+#pragma unroll
+          for (int w = 1; w < kWaves; ++w) {
+            const f32x4 p = part[w][tt][jt][lane];
+            s[0] += p[0]; s[1] += p[1]; s[2] += p[2]; s[3] += p[3];
+          }
+          s2[tt] = s;
+        }
+        if (step < nsteps) Yp[(((int64_t)b * nsteps + step) * KT + jt) * 64 + lane] = pack_y_word(s2[0], s2[1], 32 * step + 4 * g, N);
+      }
+      __syncthreads();
+      continue;
+    }
 #pragma unroll
     for (int item = 0; item < 2 * KT; ++item) {
       if ((item % kWaves) != wave) continue;
@@ -176,8 +216,9 @@ __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __r
 template <int KT, int RTW, int SC, bool SPLIT, bool FRO>
 __global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __restrict__ F,
                                                                const uint16_t* __restrict__ Qp, float* Y,
-                                                               double* fro_acc, int N, int D, int l, int64_t ldf,
-                                                               int64_t bstride, int groups_per_block) {
+                                                               u32x4* Yp, double* fro_acc, int N, int D, int l,
+                                                               int64_t ldf, int64_t bstride,
+                                                               int groups_per_block) {
   constexpr int PD = 2;                       // chunks of F in flight per wave
   constexpr int NP = SPLIT ? 2 : 1;           // operand parts (high, low)
   constexpr int WPW = SC * KT / kWaves;       // operand words a wave stages per slab and part
@@ -266,6 +307,17 @@ __global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __r
     const double s = wave_sum((double)ssq);
     if (lane == 0) atomicAdd(fro_acc + b, s);
   }
+  if constexpr (RTW == 2) {
+    if (Yp) {   // packed output for the back-projection: the wave's two tiles are one 32-row step
+      const int nsteps = (N + 31) / 32, step = tile0 / 2;
+      if (step < nsteps) {
+#pragma unroll
+        for (int jt = 0; jt < KT; ++jt)
+          Yp[(((int64_t)b * nsteps + step) * KT + jt) * 64 + lane] = pack_y_word(acc[0][jt], acc[1][jt], 32 * step + 4 * g, N);
+      }
+      return;
+    }
+  }
   float* ybase = Y + (int64_t)b * N * l;
 #pragma unroll
   for (int t = 0; t < RTW; ++t)
@@ -292,9 +344,12 @@ __global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __r
 //   D[m = 4 g + i][n = r]  ->  Z[32 chunk + 2 (4 g + i) + parity][16 jt + r]
 // Accumulators (NCW chunks x 2 parities x KT tiles) stay in registers over all rows.
 // ---------------------------------------------------------------------------
-template <int NCW, int KT>
+// PACKED: Y comes as the operand words that the projection wrote (pack_y_word); the rows of a 32-row step are then
+// contracted in that word's order, kk = 8 g + e  <->  row 16 (e / 4) + 4 g + e % 4.
+template <int NCW, int KT, bool PACKED>
 __global__ __launch_bounds__(256) void fit_backproject_mfma_kernel(const bf16_t* __restrict__ F,
-                                                                   const float* __restrict__ Y, float* Z, int N,
+                                                                   const float* __restrict__ Y,
+                                                                   const u32x4* __restrict__ Yp, float* Z, int N,
                                                                    int D, int l, int64_t ldf, int64_t bstride,
                                                                    int NS, int groups_per_block,
                                                                    int rows_per_group) {
@@ -318,28 +373,40 @@ __global__ __launch_bounds__(256) void fit_backproject_mfma_kernel(const bf16_t*
       for (int jt = 0; jt < KT; ++jt) acc[c][p][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   uint32_t fw[NCW][8];
-  float yv[KT][8];
+  float yv[PACKED ? 1 : KT][8];
+  u32x4 yw[PACKED ? KT : 1];
+  const int nsteps = (N + 31) / 32;
   auto load_step = [&](int row0) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const int row = row0 + 8 * g + e;
+      const int row = PACKED ? row0 + 16 * (e / 4) + 4 * g + e % 4 : row0 + 8 * g + e;
       const int rowc = min(row, N - 1);
 #pragma unroll
       for (int c = 0; c < NCW; ++c) fw[c][e] = fbase[(int64_t)rowc * ldw + 16 * c];
+      if constexpr (!PACKED) {
 #pragma unroll
-      for (int jt = 0; jt < KT; ++jt) {
-        const int j = 16 * jt + r;
-        yv[jt][e] = (row < row_end && j < l) ? ybase[(int64_t)row * l + j] : 0.f;
+        for (int jt = 0; jt < KT; ++jt) {
+          const int j = 16 * jt + r;
+          yv[jt][e] = (row < row_end && j < l) ? ybase[(int64_t)row * l + j] : 0.f;
+        }
       }
+    }
+    if constexpr (PACKED) {   // row groups start at multiples of 32 rows; rows >= N are zero in the packed words
+#pragma unroll
+      for (int jt = 0; jt < KT; ++jt) yw[jt] = Yp[(((int64_t)b * nsteps + row0 / 32) * KT + jt) * 64 + lane];
     }
   };
   if (row_begin < row_end) load_step(row_begin);
   for (int row0 = row_begin; row0 < row_end; row0 += 32) {
     u32x4 yop[KT];
 #pragma unroll
-    for (int jt = 0; jt < KT; ++jt)
-      yop[jt] = u32x4{pack_bf16(yv[jt][0], yv[jt][1]), pack_bf16(yv[jt][2], yv[jt][3]),
-                      pack_bf16(yv[jt][4], yv[jt][5]), pack_bf16(yv[jt][6], yv[jt][7])};
+    for (int jt = 0; jt < KT; ++jt) {
+      if constexpr (PACKED)
+        yop[jt] = yw[jt];
+      else
+        yop[jt] = u32x4{pack_bf16(yv[jt][0], yv[jt][1]), pack_bf16(yv[jt][2], yv[jt][3]),
+                        pack_bf16(yv[jt][4], yv[jt][5]), pack_bf16(yv[jt][6], yv[jt][7])};
+    }
     u32x4 fop[NCW][2];
 #pragma unroll
     for (int c = 0; c < NCW; ++c)
@@ -380,8 +447,8 @@ template <int KT>
 constexpr int width_for() { return KT <= 2 ? 12 : (KT == 4 ? 6 : 3); }
 
 template <int NCW, int KT>
-void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, double* fro_acc,
-                    bool split, hipStream_t st) {
+void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, u32x4* Yp,
+                    double* fro_acc, bool split, hipStream_t st) {
   // 4 row tiles per workgroup from sketch width 64 on: with a 4-chunk slab that is about 250 registers, so two
   // workgroups share a compute unit and one streams F while the other loads its Q operands (measured 8 % / 13 %
   // faster than 8 tiles x 6 chunks at 3072 channels, plain / split operands)
@@ -402,41 +469,45 @@ void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, f
       const int g = rows_grid();
       if (fro_acc)
         fit_project_rows_kernel<KT, RTW, SC, true, true><<<(unsigned)((int64_t)g * s.B), 256, 0, st>>>(
-            f, q, Y, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g);
+            f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g);
       else
         fit_project_rows_kernel<KT, RTW, SC, true, false><<<(unsigned)((int64_t)g * s.B), 256, 0, st>>>(
-            f, q, Y, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g);
+            f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g);
       return;
     }
     if constexpr (KT == 8) {
       const int g = rows_grid();
       fit_project_rows_kernel<KT, RTW, 4, false, false><<<(unsigned)((int64_t)g * s.B), 256, 0, st>>>(
-          f, q, Y, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g);
+          f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g);
       return;
     }
   }
   if (split) {
     const int NS = s.D / (128 * NCWS);
     if (fro_acc)
-      fit_project_mfma_kernel<NCWS, KT, TG, true, true><<<grid, 256, 0, st>>>(f, q, Y, fro_acc, s.N, s.D, l, s.ldf,
+      fit_project_mfma_kernel<NCWS, KT, TG, true, true><<<grid, 256, 0, st>>>(f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf,
                                                                             s.block_stride, NS, gpb);
     else
-      fit_project_mfma_kernel<NCWS, KT, TG, true, false><<<grid, 256, 0, st>>>(f, q, Y, fro_acc, s.N, s.D, l, s.ldf,
+      fit_project_mfma_kernel<NCWS, KT, TG, true, false><<<grid, 256, 0, st>>>(f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf,
                                                                              s.block_stride, NS, gpb);
   } else {
     const int NS = s.D / (128 * NCW);
-    fit_project_mfma_kernel<NCW, KT, TG, false, false><<<grid, 256, 0, st>>>(f, q, Y, fro_acc, s.N, s.D, l, s.ldf,
+    fit_project_mfma_kernel<NCW, KT, TG, false, false><<<grid, 256, 0, st>>>(f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf,
                                                                            s.block_stride, NS, gpb);
   }
 }
 
 template <int NCW, int KT>
-void backproject_launch(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, int gpb, int rows,
+void backproject_launch(const svdc_shape& s, int l, const void* F, const float* Y, const u32x4* Yp, float* Z, int gpb, int rows,
                         hipStream_t st) {
   const int NS = s.D / (128 * NCW);
   const unsigned grid = (unsigned)((int64_t)NS * gpb * s.B);
-  fit_backproject_mfma_kernel<NCW, KT><<<grid, 256, 0, st>>>((const bf16_t*)F, Y, Z, s.N, s.D, l, s.ldf,
-                                                            s.block_stride, NS, gpb, rows);
+  if (Yp)
+    fit_backproject_mfma_kernel<NCW, KT, true><<<grid, 256, 0, st>>>((const bf16_t*)F, Y, Yp, Z, s.N, s.D, l, s.ldf,
+                                                                    s.block_stride, NS, gpb, rows);
+  else
+    fit_backproject_mfma_kernel<NCW, KT, false><<<grid, 256, 0, st>>>((const bf16_t*)F, Y, Yp, Z, s.N, s.D, l, s.ldf,
+                                                                     s.block_stride, NS, gpb, rows);
 }
 
 __global__ void clear_f32_kernel(float* p, int64_t n) {
@@ -474,38 +545,40 @@ void by_width(int m, Fn12 f12, Fn6 f6, Fn4 f4, Fn3 f3, Fn2 f2, Fn1 f1) {
 }
 
 template <int KT>
-void project_kt(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, double* fro, bool split,
+void project_kt(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, u32x4* Yp, double* fro, bool split,
                 hipStream_t st) {
   constexpr int cap = KT == 4 ? 4 : width_for<KT>();
   by_width<KT, cap>(
-      s.D / 128, [&] { project_launch<(cap >= 12 ? 12 : 1), KT>(s, l, F, Qp, Y, fro, split, st); },
-      [&] { project_launch<(cap >= 6 ? 6 : 1), KT>(s, l, F, Qp, Y, fro, split, st); },
-      [&] { project_launch<(cap >= 4 ? 4 : 1), KT>(s, l, F, Qp, Y, fro, split, st); },
-      [&] { project_launch<3, KT>(s, l, F, Qp, Y, fro, split, st); },
-      [&] { project_launch<2, KT>(s, l, F, Qp, Y, fro, split, st); },
-      [&] { project_launch<1, KT>(s, l, F, Qp, Y, fro, split, st); });
+      s.D / 128, [&] { project_launch<(cap >= 12 ? 12 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, st); },
+      [&] { project_launch<(cap >= 6 ? 6 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, st); },
+      [&] { project_launch<(cap >= 4 ? 4 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, st); },
+      [&] { project_launch<3, KT>(s, l, F, Qp, Y, Yp, fro, split, st); },
+      [&] { project_launch<2, KT>(s, l, F, Qp, Y, Yp, fro, split, st); },
+      [&] { project_launch<1, KT>(s, l, F, Qp, Y, Yp, fro, split, st); });
 }
 
 template <int NCW, int KT>
-void backproject_one(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, hipStream_t st) {
+void backproject_one(const svdc_shape& s, int l, const void* F, const float* Y, const u32x4* Yp, float* Z,
+                     hipStream_t st) {
   int gpb, rows;
   backproject_groups<NCW>(s, &gpb, &rows);
   if (gpb > 1) {   // atomics accumulate into Z
     const int64_t n = (int64_t)s.B * s.D * l;
     clear_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(Z, n);
   }
-  backproject_launch<NCW, KT>(s, l, F, Y, Z, gpb, rows, st);
+  backproject_launch<NCW, KT>(s, l, F, Y, Yp, Z, gpb, rows, st);
 }
 
 template <int KT>
-void backproject_kt(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, hipStream_t st) {
+void backproject_kt(const svdc_shape& s, int l, const void* F, const float* Y, const u32x4* Yp, float* Z,
+                    hipStream_t st) {
   constexpr int cap = width_for<KT>();
   by_width<KT, cap>(
-      s.D / 128, [&] { backproject_one<(cap >= 12 ? 12 : 1), KT>(s, l, F, Y, Z, st); },
-      [&] { backproject_one<(cap >= 6 ? 6 : 1), KT>(s, l, F, Y, Z, st); },
-      [&] { backproject_one<(cap >= 4 ? 4 : 1), KT>(s, l, F, Y, Z, st); },
-      [&] { backproject_one<3, KT>(s, l, F, Y, Z, st); }, [&] { backproject_one<2, KT>(s, l, F, Y, Z, st); },
-      [&] { backproject_one<1, KT>(s, l, F, Y, Z, st); });
+      s.D / 128, [&] { backproject_one<(cap >= 12 ? 12 : 1), KT>(s, l, F, Y, Yp, Z, st); },
+      [&] { backproject_one<(cap >= 6 ? 6 : 1), KT>(s, l, F, Y, Yp, Z, st); },
+      [&] { backproject_one<(cap >= 4 ? 4 : 1), KT>(s, l, F, Y, Yp, Z, st); },
+      [&] { backproject_one<3, KT>(s, l, F, Y, Yp, Z, st); }, [&] { backproject_one<2, KT>(s, l, F, Y, Yp, Z, st); },
+      [&] { backproject_one<1, KT>(s, l, F, Y, Yp, Z, st); });
 }
 
 }  // namespace
@@ -519,25 +592,31 @@ size_t fit_mfma_packed_q_bytes(const svdc_shape& s, int l) {
   return (size_t)s.B * 2 * s.D * KT * 16 * sizeof(uint16_t);
 }
 
+size_t fit_mfma_packed_y_bytes(const svdc_shape& s, int l) {
+  const int KT = l <= 16 ? 1 : (l <= 32 ? 2 : (l <= 64 ? 4 : 8));
+  return (size_t)s.B * ((s.N + 31) / 32) * KT * 1024;
+}
+
 void fit_mfma_pack_q(const svdc_shape& s, int l, const float* Q, void* Qp, hipStream_t st) {
   const int KT = l <= 16 ? 1 : (l <= 32 ? 2 : (l <= 64 ? 4 : 8));
   const int64_t per = (int64_t)s.D * KT * 16;
   pack_q_kernel<<<dim3((unsigned)((per + 255) / 256), s.B), 256, 0, st>>>(Q, (uint16_t*)Qp, s.D, l, KT);
 }
 
-void fit_mfma_project(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, double* fro_acc,
+void fit_mfma_project(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, void* Ypacked, double* fro_acc,
                       bool split, hipStream_t st) {
-  if (l <= 16) project_kt<1>(s, l, F, Qp, Y, fro_acc, split, st);
-  else if (l <= 32) project_kt<2>(s, l, F, Qp, Y, fro_acc, split, st);
-  else if (l <= 64) project_kt<4>(s, l, F, Qp, Y, fro_acc, split, st);
-  else project_kt<8>(s, l, F, Qp, Y, fro_acc, split, st);
+  if (l <= 16) project_kt<1>(s, l, F, Qp, Y, (u32x4*)Ypacked, fro_acc, split, st);
+  else if (l <= 32) project_kt<2>(s, l, F, Qp, Y, (u32x4*)Ypacked, fro_acc, split, st);
+  else if (l <= 64) project_kt<4>(s, l, F, Qp, Y, (u32x4*)Ypacked, fro_acc, split, st);
+  else project_kt<8>(s, l, F, Qp, Y, (u32x4*)Ypacked, fro_acc, split, st);
 }
 
-void fit_mfma_backproject(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, hipStream_t st) {
-  if (l <= 16) backproject_kt<1>(s, l, F, Y, Z, st);
-  else if (l <= 32) backproject_kt<2>(s, l, F, Y, Z, st);
-  else if (l <= 64) backproject_kt<4>(s, l, F, Y, Z, st);
-  else backproject_kt<8>(s, l, F, Y, Z, st);
+void fit_mfma_backproject(const svdc_shape& s, int l, const void* F, const float* Y, const void* Ypacked, float* Z,
+                          hipStream_t st) {
+  if (l <= 16) backproject_kt<1>(s, l, F, Y, (const u32x4*)Ypacked, Z, st);
+  else if (l <= 32) backproject_kt<2>(s, l, F, Y, (const u32x4*)Ypacked, Z, st);
+  else if (l <= 64) backproject_kt<4>(s, l, F, Y, (const u32x4*)Ypacked, Z, st);
+  else backproject_kt<8>(s, l, F, Y, (const u32x4*)Ypacked, Z, st);
 }
 
 }  // namespace svdc

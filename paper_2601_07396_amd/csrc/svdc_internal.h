@@ -69,10 +69,14 @@ int32_t run_fit(const svdc_shape& s, const FitPlan& plan, const void* F, float* 
 bool fit_mfma_supported(const svdc_shape& s, int l);
 size_t fit_mfma_packed_q_bytes(const svdc_shape& s, int l);
 void fit_mfma_pack_q(const svdc_shape& s, int l, const float* Q, void* Qp, hipStream_t st);
-// Y = F Q;  fro_acc (nullable) += ||F||_F^2;  split: bf16 high + low parts of Q
-void fit_mfma_project(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, double* fro_acc,
-                      bool split, hipStream_t st);
-// Z = F^T Y
-void fit_mfma_backproject(const svdc_shape& s, int l, const void* F, const float* Y, float* Z, hipStream_t st);
+// Bytes of Y rounded to bf16 in the operand layout of the back-projection (written by fit_mfma_project when asked)
+size_t fit_mfma_packed_y_bytes(const svdc_shape& s, int l);
+// Y = F Q;  fro_acc (nullable) += ||F||_F^2;  split: bf16 high + low parts of Q.
+// Ypacked != nullptr (plain operands only): the result goes there in packed bf16 form and Y is not written.
+void fit_mfma_project(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, void* Ypacked,
+                      double* fro_acc, bool split, hipStream_t st);
+// Z = F^T Y, with Y as float32 rows or (Ypacked != nullptr) in the packed form
+void fit_mfma_backproject(const svdc_shape& s, int l, const void* F, const float* Y, const void* Ypacked, float* Z,
+                          hipStream_t st);
 
 }  // namespace svdc
