@@ -73,7 +73,7 @@ typedef enum {
 #define SVDC_MAX_STATES 4
 
 /* One batched problem: B independent blocks of identical shape.
- *   1 <= B <= 65535;  1 <= k <= min(N, D), k <= 1024;  ldf >= D;  block_stride >= (N-1)*ldf + D;
+ *   1 <= B <= 65535;  N, D <= 2^30;  1 <= k <= min(N, D), k <= 1024;  ldf >= D;  block_stride >= (N-1)*ldf + D;
  *   N*ldf and B*block_stride at most 2^48 elements (SVDC_E_SHAPE beyond).
  *   Base pointers of F/R/Fhat must be 16-byte aligned; with dtype BF16, D, ldf
  *   and block_stride must be multiples of 8 elements, with F32 multiples of 4. */

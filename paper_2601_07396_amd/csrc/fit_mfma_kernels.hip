@@ -594,7 +594,7 @@ size_t fit_mfma_packed_q_bytes(const svdc_shape& s, int l) {
 
 size_t fit_mfma_packed_y_bytes(const svdc_shape& s, int l) {
   const int KT = l <= 16 ? 1 : (l <= 32 ? 2 : (l <= 64 ? 4 : 8));
-  return (size_t)s.B * ((s.N + 31) / 32) * KT * 1024;
+  return (size_t)s.B * (((size_t)s.N + 31) / 32) * KT * 1024;
 }
 
 void fit_mfma_pack_q(const svdc_shape& s, int l, const float* Q, void* Qp, hipStream_t st) {

@@ -14,6 +14,7 @@ int32_t check_shape(const svdc_shape* s) {
   if (s->dtype != SVDC_F32 && s->dtype != SVDC_BF16) return SVDC_E_DTYPE;
   if (s->precision != SVDC_PRECISE && s->precision != SVDC_FAST) return SVDC_E_PARAM;
   if (s->B < 1 || s->B > 65535 || s->N < 1 || s->D < 1 || s->k < 1) return SVDC_E_SHAPE;
+  if (s->N > (1 << 30) || s->D > (1 << 30)) return SVDC_E_SHAPE;   // tile counts such as (N + 31) / 32 stay in int
   if (s->k > s->N || s->k > s->D || s->k > 1024) return SVDC_E_SHAPE;
   // At most 2^48 elements from the first to the last block: more than any device holds, and small enough
   // that no offset or byte count computed from these strides leaves the int64 range.
