@@ -306,7 +306,7 @@ def test_mfma_inplace_and_strided(k):
 # ---------------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("N,D,k", [(300, 256, 16), (1000, 512, 32), (600, 3072, 32), (333, 384, 8), (700, 768, 64),
-                                   (200, 128, 4)])
+                                   (200, 128, 4), (20, 128, 4), (33, 128, 8), (65, 256, 40), (97, 128, 64)])
 def test_fit_basis_mfma_path(N, D, k):
     wl = WORKLOADS["flux1"].with_(N=N, D=D, k=k, signal_rank=min(96, D, N))
     F = torch.stack([FeatureStream(wl, b).at(0) for b in range(2)])
