@@ -5,6 +5,8 @@
 // (operand layouts: see mfma_kernels.hip).  project stores Y directly; backproject
 // stores Z directly when one workgroup covers all rows of a block and otherwise
 // combines the partial results of its row groups with float atomics (it clears Z itself).
+#include <type_traits>
+
 #include "svdc_device.h"
 #include "svdc_internal.h"
 
@@ -209,8 +211,8 @@ __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __r
 // buffered, one barrier per slab) and every wave reads them from there.  Per token row the packed sketch is then
 // read from L2 once per 64 RTW rows and from LDS once per 16 RTW rows; with the operands stationary in registers
 // (kernel above) it is read from L2 once per 64 rows, which at sketch width 128 is twice the bytes of F itself.
-// Same operand roles and output mapping as above.  Measured at 57 x 4608 x 3072: 0.49 ms against 0.63 ms at width
-// 128 (0.69 against 0.88 ms with split operands), 0.42 against 0.53 ms at width 64 with split operands; at width
+// Same operand roles and output mapping as above.  Measured at 57 x 4608 x 3072: 0.47 ms against 0.63 ms at width
+// 128 (0.66 against 0.88 ms with split operands), 0.41 against 0.53 ms at width 64 with split operands; at width
 // 64 with plain operands the register-stationary kernel stays ahead (0.36 against 0.42 ms).
 // ---------------------------------------------------------------------------
 template <int KT, int RTW, int SC, bool SPLIT, bool FRO>
@@ -219,7 +221,13 @@ __global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __r
                                                                u32x4* Yp, double* fro_acc, int N, int D, int l,
                                                                int64_t ldf, int64_t bstride,
                                                                int groups_per_block) {
-  constexpr int PD = 2;                       // chunks of F in flight per wave
+  // Chunks of F in flight per wave.  With split operands they are requested two at a time (PD = 4): the two
+  // 64-byte pieces of a 128-byte line belong to neighbouring chunks, and asked for a whole chunk's work apart the
+  // line comes from L2 twice (4 % slower).  With plain operands at width 128 the extra registers cost more than
+  // that (11 % slower), so there a slot is refilled as soon as its chunk is done (PD = 2).
+  constexpr bool PAIRED = SPLIT;
+  constexpr int PD = PAIRED ? 4 : 2;
+  static_assert(SC == 2 || SC == 4, "slab of 2 or 4 chunks");
   constexpr int NP = SPLIT ? 2 : 1;           // operand parts (high, low)
   constexpr int WPW = SC * KT / kWaves;       // operand words a wave stages per slab and part
   static_assert(SC * KT % kWaves == 0, "staging must divide among the waves");
@@ -269,13 +277,16 @@ __global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __r
   __syncthreads();
 
   float ssq = 0.f;
-  for (int slab = 0; slab < NS; ++slab) {
-    const int buf = slab & 1;
+  // one slab; with paired requests PAR = slab & 1 is a compile-time value, so that the ring slots are static
+  auto do_slab = [&](int slab, auto par) {
+    constexpr int PAR = decltype(par)::value;
+    const int buf = PAIRED ? PAR : (slab & 1);
     if (slab + 1 < NS) load_stage(slab + 1);
 #pragma unroll
     for (int c = 0; c < SC; ++c) {
       const int chunk = slab * SC + c;
-      const int u = c % PD;                   // SC is a multiple of PD
+      constexpr int kSlotBase = (PAR * SC) % PD;
+      const int u = (kSlotBase + c) % PD;     // = chunk % PD
 #pragma unroll
       for (int jt = 0; jt < KT; ++jt) {
         const u32x4 bh = qs[buf][0][c * KT + jt][lane];
@@ -298,10 +309,25 @@ __global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __r
             }
           }
       }
-      if (chunk + PD < NC) load_chunk(chunk + PD, fin[u]);
+      if constexpr (PAIRED) {
+        if (c % 2 == 1) {                     // chunks c - 1 and c are done: refill both slots together
+          if (chunk - 1 + PD < NC) load_chunk(chunk - 1 + PD, fin[(kSlotBase + c - 1) % PD]);
+          if (chunk + PD < NC) load_chunk(chunk + PD, fin[u]);
+        }
+      } else {
+        if (chunk + PD < NC) load_chunk(chunk + PD, fin[u]);
+      }
     }
     if (slab + 1 < NS) store_stage(buf ^ 1);
     __syncthreads();
+  };
+  if constexpr (PAIRED) {
+    for (int slab = 0; slab < NS; slab += 2) {
+      do_slab(slab, std::integral_constant<int, 0>{});
+      if (slab + 1 < NS) do_slab(slab + 1, std::integral_constant<int, 1>{});
+    }
+  } else {
+    for (int slab = 0; slab < NS; ++slab) do_slab(slab, std::integral_constant<int, 0>{});
   }
   if (FRO) {
     const double s = wave_sum((double)ssq);
