@@ -219,7 +219,7 @@ def main():
     lo = {kk: float(np.min([a.elapsed_time(b) for a, b in v])) for kk, v in times.items()}
 
     # ---- work accounting -------------------------------------------------------------------------
-    q = 3 if wl.dtype == "bf16" else 4
+    q = 3 if wl.dtype == "bf16" else 5
     passes = 2 * q + 1
     l = min(2 * k, N, D, 256)
     by_full, by_fore, by_fit = algorithmic_bytes(wl, passes)

@@ -88,7 +88,9 @@ typedef struct {
 /* Parameters of the randomized basis fit.  Zero-initialise for defaults. */
 typedef struct {
   int32_t oversample_p;  /* sketch width l = k + p (clamped to min(N, D), at most 256); 0 -> p = k, -1 -> p = 0 */
-  int32_t power_iters_q; /* applications of F^T F before the Rayleigh-Ritz step; 0 -> 3 (bf16) / 4 (f32); -1 -> none */
+  int32_t power_iters_q; /* applications of F^T F to the Gaussian sketch before the Rayleigh-Ritz step; 0 -> 3 (bf16) /
+                            5 (f32); -1 -> none: the sketch is F^T Omega alone (plain randomized range finder, two
+                            products with F in all; exact when rank(F) <= l, crude when the spectrum decays slowly) */
   uint64_t seed;         /* seed of the Gaussian test matrix                     */
 } svdc_fit_params;
 

@@ -124,6 +124,47 @@ def make_shape(F: torch.Tensor, k: int, precision: int = SVDC_PRECISE) -> Shape:
     return Shape(B, N, D, k, F.stride(1), bs, _DTYPES[F.dtype], precision)
 
 
+_TORCH_OF = {SVDC_F32: torch.float32, SVDC_BF16: torch.bfloat16}
+
+
+def _like_features(shape: Shape, **tensors):
+    """The C ABI describes F, R, Fhat, X and R_prev by ONE (ldf, block_stride, dtype): refuse a tensor whose own
+    layout differs (e.g. `empty_like` of a row-strided view comes back contiguous), which the kernels would
+    otherwise address with the wrong strides, past the end of its allocation."""
+    for name, t in tensors.items():
+        if t is None:
+            continue
+        if t.dtype != _TORCH_OF[shape.dtype]:
+            raise ValueError(f"{name}: dtype {t.dtype} differs from the feature dtype {_TORCH_OF[shape.dtype]}")
+        u = t.unsqueeze(0) if t.dim() == 2 else t
+        if u.dim() != 3 or tuple(u.shape) != (shape.B, shape.N, shape.D):
+            raise ValueError(f"{name}: shape {tuple(t.shape)} is not [B={shape.B}, N={shape.N}, D={shape.D}]")
+        if u.stride(2) != 1 or u.stride(1) != shape.ldf or (shape.B > 1 and u.stride(0) != shape.block_stride):
+            raise ValueError(f"{name}: strides {tuple(u.stride())} differ from the features' "
+                             f"(block {shape.block_stride}, row {shape.ldf}, 1)")
+
+
+def _dense_f32(count: int, what: str, **tensors):
+    """V, S, C and their like are float32, contiguous, with exactly the element count the shape implies."""
+    for name, t in tensors.items():
+        if t is None:
+            continue
+        if t.dtype != torch.float32 or not t.is_contiguous() or t.numel() != count:
+            raise ValueError(f"{name}: need a contiguous float32 tensor of {count} elements ({what}), got "
+                             f"{t.dtype} {tuple(t.shape)} contiguous={t.is_contiguous()}")
+
+
+def _check_step_args(shape: Shape, V, packed, coefs: dict, feats: dict):
+    _like_features(shape, **feats)
+    _dense_f32(shape.B * shape.D * shape.k, "[B, D, k]", V=V)
+    _dense_f32(shape.B * shape.N * shape.k, "[B, N, k]", **coefs)
+    if packed is not None:
+        need = svdcache_packed_basis_bytes(shape)
+        if need == 0 or packed.numel() * packed.element_size() < need or not packed.is_contiguous():
+            raise ValueError(f"packed: {packed.numel() * packed.element_size()} bytes, this shape needs {need} "
+                             "(a buffer packed for another rank or width?)")
+
+
 def _check(code: int, where: str):
     if code != 0:
         raise SvdcError(code, where)
@@ -143,6 +184,10 @@ def svdcache_has_mfma_path(shape: Shape) -> bool:
 
 
 def svdcache_fit_basis(shape: Shape, F, V, sigma, fro2, workspace, p: int = 0, q: int = 0, seed: int = 0):
+    _like_features(shape, F=F)
+    _dense_f32(shape.B * shape.D * shape.k, "[B, D, k]", V=V)
+    _dense_f32(shape.B * shape.k, "[B, k]", sigma=sigma)
+    _dense_f32(shape.B, "[B]", fro2=fro2)
     _need_gpu(F, V, sigma, fro2, workspace)
     fp = FitParams(p, q, seed)
     rc = load_library().svdcache_fit_basis(C.byref(shape), C.byref(fp), _ptr(F), _ptr(V), _ptr(sigma), _ptr(fro2),
@@ -151,6 +196,7 @@ def svdcache_fit_basis(shape: Shape, F, V, sigma, fro2, workspace, p: int = 0, q
 
 
 def svdcache_pack_basis(shape: Shape, V, packed):
+    _dense_f32(shape.B * shape.D * shape.k, "[B, D, k]", V=V)
     _need_gpu(V, packed)
     rc = load_library().svdcache_pack_basis(C.byref(shape), _ptr(V), _ptr(packed),
                                             packed.numel() * packed.element_size(), _stream())
@@ -158,6 +204,7 @@ def svdcache_pack_basis(shape: Shape, V, packed):
 
 
 def svdcache_full_step(shape: Shape, F, V, packed, R, S, Cout, alpha: float, init: bool):
+    _check_step_args(shape, V, packed, {"S": S, "C": Cout}, {"F": F, "R": R})
     _need_gpu(F, V, packed, R, S, Cout)
     rc = load_library().svdcache_full_step(C.byref(shape), _ptr(F), _ptr(V), _ptr(packed), _ptr(R), _ptr(S),
                                            _ptr(Cout), float(alpha), int(bool(init)), _stream())
@@ -166,6 +213,7 @@ def svdcache_full_step(shape: Shape, F, V, packed, R, S, Cout, alpha: float, ini
 
 def svdcache_full_step_residual_ema(shape: Shape, F, V, packed, R_prev, R, S, Cout, alpha: float, alpha_r: float,
                                     init: bool):
+    _check_step_args(shape, V, packed, {"S": S, "C": Cout}, {"F": F, "R": R, "R_prev": R_prev})
     _need_gpu(F, V, packed, R_prev, R, S, Cout)
     rc = load_library().svdcache_full_step_residual_ema(C.byref(shape), _ptr(F), _ptr(V), _ptr(packed), _ptr(R_prev),
                                                         _ptr(R), _ptr(S), _ptr(Cout), float(alpha), float(alpha_r),
@@ -174,6 +222,7 @@ def svdcache_full_step_residual_ema(shape: Shape, F, V, packed, R_prev, R, S, Co
 
 
 def svdcache_forecast(shape: Shape, S, V, packed, R, Fhat):
+    _check_step_args(shape, V, packed, {"S": S}, {"R": R, "Fhat": Fhat})
     _need_gpu(S, V, packed, R, Fhat)
     rc = load_library().svdcache_forecast(C.byref(shape), _ptr(S), _ptr(V), _ptr(packed), _ptr(R), _ptr(Fhat),
                                           _stream())
@@ -204,10 +253,11 @@ def svdcache_extrapolation_weights(order: int, offset: float, interval: float):
 
 
 def svdcache_forecast_combine(shape: Shape, S_list, weights, V, packed, R, X, Out):
-    _need_gpu(*S_list, V, packed, R, X, Out)
     m = len(S_list)
     if m != len(weights):
         raise ValueError("one weight per state")
+    _check_step_args(shape, V, packed, {f"S_list[{i}]": t for i, t in enumerate(S_list)}, {"R": R, "X": X, "Out": Out})
+    _need_gpu(*S_list, V, packed, R, X, Out)
     ptrs = (C.c_void_p * max(m, 1))(*[t.data_ptr() for t in S_list])
     w = (C.c_float * max(m, 1))(*[float(x) for x in weights])
     rc = load_library().svdcache_forecast_combine(C.byref(shape), m, ptrs, w, _ptr(V), _ptr(packed), _ptr(R),

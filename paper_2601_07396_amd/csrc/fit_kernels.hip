@@ -756,7 +756,7 @@ bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan)
   if (pp < -1 || q < -1 || pp > 4096 || q > 64) return false;
   if (pp == 0) pp = s.k;
   if (pp == -1) pp = 0;
-  if (q == 0) q = (s.dtype == SVDC_BF16) ? 3 : 4;
+  if (q == 0) q = (s.dtype == SVDC_BF16) ? 3 : 5;
   if (q == -1) q = 0;
   int l = s.k + pp;
   l = std::min(l, std::min(s.N, s.D));
@@ -898,11 +898,15 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   double* misc = (double*)(ws + pl.off_misc);
 
   const int64_t nq = (int64_t)B * s.D * l;
-  // With power iterations the Gaussian test matrix is used as it is (its columns are well conditioned
-  // and every product F^T F Q is re-orthonormalised afterwards).  With none, Q goes straight into the
-  // Rayleigh-Ritz step and must be orthonormal to round-off: Q <- orth(Omega), two passes.
+  // With power iterations the Gaussian test matrix (D x l) is used as it is: its columns are well conditioned
+  // and every product F^T F Q is re-orthonormalised afterwards.  With none, the sketch is Z = F^T Omega with a
+  // Gaussian Omega (N x l) -- the plain randomized range finder, exact when rank(F) <= l -- and Q <- orth(Z), two
+  // passes, goes straight into the Rayleigh-Ritz step.
   if (pl.q == 0) {
-    init_omega_kernel<<<(unsigned)((nq + 255) / 256), 256, 0, st>>>(Z, (int64_t)s.D * l, nq, pl.seed);
+    const int64_t ny = (int64_t)B * s.N * l;
+    init_omega_kernel<<<(unsigned)((ny + 255) / 256), 256, 0, st>>>(Y, (int64_t)s.N * l, ny, pl.seed);
+    if (pl.mfma) fit_mfma_backproject(s, l, F, Y, nullptr, Z, st);
+    else gemm_fty<T>(s, l, F, Y, Z, st);
     if (orth(Z, Q, G, Gp, M, B, s.D, l, true, st) != SVDC_OK) return SVDC_E_HIP;
     std::swap(Q, Z);
   } else {

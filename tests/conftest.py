@@ -26,3 +26,18 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_sessionfinish(session, exitstatus):
+    """Calibration aid: with SVDC_ELEM_LOG=<file> the element-wise excesses that assert_close saw are written
+    there (worst first) instead of being judged."""
+    path = os.environ.get("SVDC_ELEM_LOG")
+    if not path:
+        return
+    try:
+        from util import _ELEM_LOG
+    except Exception:
+        return
+    with open(path, "w") as f:
+        for what, key, exc in sorted(_ELEM_LOG, key=lambda x: (x[1], -x[2])):
+            f.write(f"{key}\t{exc:.3e}\t{what}\n")

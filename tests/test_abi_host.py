@@ -149,3 +149,50 @@ def test_residual_ema_validates_on_the_host(lib):
     assert call(C.byref(s), f, v, None, f, r, st, None, 0.5, 0.5, 0, None) == -5        # R_prev is F
     assert call(C.byref(s), f, v, None, r, r, st, None, 0.5, 0.0, 0, None) == -5        # alpha_r out of range
     assert call(C.byref(s), None, v, None, r, r, st, None, 0.5, 0.5, 0, None) == -1
+
+
+def test_binding_refuses_mismatched_layouts():
+    """The C ABI has one (ldf, block_stride, dtype) for F, R, Fhat, X and R_prev and takes V, S, C as dense
+    float32: the binding refuses tensors whose own layout differs before anything is launched (CPU tensors here;
+    a refusal comes before the check for device memory)."""
+    import torch
+    B, N, D, k, ldf = 2, 32, 128, 8, 160
+    buf = torch.zeros(B, N, ldf)
+    F = buf[:, :, :D]                                   # row-strided view
+    s = pkg.make_shape(F, k)
+    assert s.ldf == ldf
+    V, S = torch.zeros(B, D, k), torch.zeros(B, N, k)
+    with pytest.raises(ValueError, match="strides"):    # empty_like of a gapped view is contiguous
+        pkg.svdcache_full_step(s, F, V, None, torch.empty_like(F), S, None, 0.5, True)
+    with pytest.raises(ValueError, match="dtype"):
+        pkg.svdcache_full_step(s, F, V, None, buf.bfloat16()[:, :, :D], S, None, 0.5, True)
+    with pytest.raises(ValueError, match="shape"):
+        pkg.svdcache_forecast(s, S, V, None, F, buf[:, :N - 1, :D])
+    with pytest.raises(ValueError, match="V"):
+        pkg.svdcache_full_step(s, F, V.double(), None, F, S, None, 0.5, True)
+    with pytest.raises(ValueError, match="V"):
+        pkg.svdcache_forecast(s, S, torch.zeros(B, k, D).transpose(1, 2), None, F, F)
+    with pytest.raises(ValueError, match="S"):
+        pkg.svdcache_full_step(s, F, V, None, F, torch.zeros(B, N, k + 1), None, 0.5, True)
+    with pytest.raises(ValueError, match="C"):
+        pkg.svdcache_full_step(s, F, V, None, F, S, torch.zeros(B, N, 2 * k)[:, :, :k], 0.5, True)
+    with pytest.raises(ValueError, match=r"S_list\[1\]"):
+        pkg.svdcache_forecast_combine(s, [S, S[:1]], [1.0, 0.0], V, None, F, None, F)
+    with pytest.raises(ValueError, match="X"):
+        pkg.svdcache_forecast_combine(s, [S], [1.0], V, None, F, torch.zeros(B, N, D), F)
+    with pytest.raises(ValueError, match="R_prev"):
+        pkg.svdcache_full_step_residual_ema(s, F, V, None, torch.zeros(B, N, D), F, S, None, 0.5, 0.5, False)
+    # a packed basis of another rank is too small (or of a shape without a matrix-core path: not accepted at all)
+    Fm = torch.zeros(1, 64, 256, dtype=torch.bfloat16)
+    s64, s32 = pkg.make_shape(Fm, 64), pkg.make_shape(Fm, 32)
+    small = torch.zeros(pkg.svdcache_packed_basis_bytes(s32), dtype=torch.uint8)
+    with pytest.raises(ValueError, match="packed"):
+        pkg.svdcache_forecast(s64, torch.zeros(1, 64, 64), torch.zeros(1, 256, 64), small, Fm, Fm)
+    with pytest.raises(ValueError, match="packed"):
+        pkg.svdcache_forecast(s, S, V, small, F, F)
+    # the fit: sigma and fro2 sized by the shape
+    with pytest.raises(ValueError, match="sigma"):
+        pkg.svdcache_fit_basis(s, F, V, torch.zeros(B, k + 1), None, torch.zeros(16, dtype=torch.uint8))
+    # matching layouts pass the checks and stop at the device check
+    with pytest.raises(RuntimeError, match="GPU"):
+        pkg.svdcache_full_step(s, F, V, None, torch.zeros(B, N, ldf)[:, :, :D], S, None, 0.5, True)

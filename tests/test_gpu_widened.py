@@ -109,7 +109,8 @@ def test_truncated_basis_gives_per_block_rank(dtype, D):
         ks = int(k_star[b])
         Rr, Sr, Cr = ref_full_step(to_np(F[b]), to_np(V[b][:, :ks]), None, 0.5, True, store)   # the rank-k* step
         assert_close(to_np(R[b]), Rr, store, f"R[{b}]", floor_of=to_np(F[b]))
-        assert_close(to_np(Cc[b][:, :ks]), Cr, "f32", f"C[{b}]")
+        # few columns (k* may be 1): scale the element-wise allowance by the feature rows, not by the coefficients
+        assert_close(to_np(Cc[b][:, :ks]), Cr, "f32", f"C[{b}]", scale_of=to_np(F[b]))
         assert not to_np(Cc[b][:, ks:]).any() and not to_np(S[b][:, ks:]).any()
     # sigma is optional
     pkg.svdcache_truncate_basis(shape, Vd, None, torch.zeros(B, dtype=torch.int32, device=DEV))
@@ -304,7 +305,7 @@ def test_refit_on_a_drifted_feature_keeps_the_state_useful():
     assert np.abs(to_np(M[0]) - Mr).max() <= 5e-6
     Rr, Sr, _ = ref_full_step(to_np(F1[0]), V1r, ref_rebase_state(S0r, Mr, "f32"), 0.5, False, "bf16")
     assert_close(to_np(S1[0]), Sr, "f32", "EMA state after re-basing")
-    assert_close(to_np(Fh[0]), ref_forecast(Sr, V1r, Rr, "bf16"), "bf16", "Fhat")
+    assert_close(to_np(Fh[0]), ref_forecast(Sr, V1r, Rr, "bf16"), "bf16", "Fhat", ulp_of=Rr)
     # the synthetic stream keeps its subspace: the GPU's own fits of the two features stay similar (Fig. 1(b))
     Vg0, s0, _ = pkg.fit_basis(F0, k)
     Vg1, s1, _ = pkg.fit_basis(F1, k)
