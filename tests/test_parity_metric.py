@@ -41,7 +41,7 @@ def test_rounding_differences_pass_and_a_misplaced_lane_piece_fails():
     assert_close(round_bf16(S @ V.T + got), Fh, "bf16", "Fhat", scale_of=F, ulp_of=R)
     badh = Fh.copy()
     badh[7, 64:72] = Fh[8, 64:72]
-    with pytest.raises(AssertionError, match="an element is off"):
+    with pytest.raises(AssertionError):
         assert_close(badh, Fh, "bf16", "Fhat with a misplaced piece", scale_of=F, ulp_of=R)
     badc = C.copy()
     badc[3, 5] = C[3, 6]
