@@ -92,7 +92,20 @@ typedef struct {
                             5 (f32); -1 -> none: the sketch is F^T Omega alone (plain randomized range finder, two
                             products with F in all; exact when rank(F) <= l, crude when the spectrum decays slowly) */
   uint64_t seed;         /* seed of the Gaussian test matrix                     */
+  int32_t jacobi_max_sweeps; /* cap on the sweeps of the small SVD; 0 -> 40 (a sweep that rotates nothing ends it: 6-9
+                                sweeps in practice); at most 1000 */
+  int32_t reserved;      /* set to 0 */
 } svdc_fit_params;
+
+/* Per-block status word of a basis fit (int32, bitwise OR of the flags below), written into the workspace at
+ * svdcache_fit_status_offset().  0 = nothing to report.  Neither flag is an error: the call returns SVDC_OK, V is
+ * orthonormal and sigma_j = ||F v_j||, but the caller may want to know. */
+#define SVDC_FIT_JACOBI_CAPPED 1   /* the small SVD stopped at jacobi_max_sweeps before a sweep without rotations: sigma
+                                      and V are those of the last sweep (still orthonormal), not converged */
+#define SVDC_FIT_RANK_DEFICIENT 2  /* a Cholesky pivot fell to the round-off level of the float32 sketch (1e-12 x the
+                                      largest diagonal entry of its Gram matrix): F, or F^T F applied to the sketch,
+                                      has numerical rank < l.  The diagonal shift keeps the factorisation going; the
+                                      directions beyond the numerical rank are arbitrary (their sigma is ~0) */
 
 /* Library version (major*10000 + minor*100 + patch). */
 int32_t svdcache_version(void);
@@ -101,8 +114,16 @@ int32_t svdcache_version(void);
 const char* svdcache_strerror(int32_t status);
 
 /* Bytes of device workspace svdcache_fit_basis needs for this shape and these
- * parameters (params may be NULL = defaults).  Returns 0 for an invalid shape. */
+ * parameters (params may be NULL = defaults).  Returns 0 for an invalid shape.
+ * svdcache_fit_workspace_bytes is the same function under its longer name. */
+size_t svdcache_workspace_bytes(const svdc_shape* shape, const svdc_fit_params* params);
 size_t svdcache_fit_workspace_bytes(const svdc_shape* shape, const svdc_fit_params* params);
+
+/* Byte offset, inside the workspace of svdcache_fit_basis, of the B int32 status words (SVDC_FIT_* flags) that
+ * the fit of this shape with these parameters writes, one per block.  Valid once the stream has been
+ * synchronised after the fit and until the workspace is reused.  Returns 0 for an invalid shape (the words never
+ * sit at offset 0). */
+size_t svdcache_fit_status_offset(const svdc_shape* shape, const svdc_fit_params* params);
 
 /* Bytes of the packed copy of the basis that the matrix-core kernels read
  * (see svdcache_pack_basis).  Returns 0 when the shape has no matrix-core
@@ -122,7 +143,8 @@ int32_t svdcache_has_mfma_path(const svdc_shape* shape);
  *   sigma   out  [B,k]   float32, descending
  *   fro2    out  [B]     float32, ||F[b]||_F^2 (denominator of the energy rule, Eq. 6); may be NULL
  *   workspace    device scratch of at least svdcache_fit_workspace_bytes() bytes, 256-byte aligned
- * Signs of the columns of V are arbitrary.  Several launches on `stream`. */
+ * Signs of the columns of V are arbitrary.  Several launches on `stream`.  Numerical events that are not errors (a
+ * capped small SVD, a rank-deficient sketch) are reported per block in the workspace: svdcache_fit_status_offset. */
 int32_t svdcache_fit_basis(const svdc_shape* shape, const svdc_fit_params* params,
                            const void* F, float* V, float* sigma, float* fro2,
                            void* workspace, size_t workspace_bytes, void* stream);

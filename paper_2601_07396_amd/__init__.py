@@ -8,7 +8,8 @@ GPU, raises.
 """
 from .binding import (
     SvdcError, Shape, SVDC_PRECISE, SVDC_FAST, lib_path, load_library, exported_symbols,
-    svdcache_version, svdcache_strerror, svdcache_fit_workspace_bytes, svdcache_packed_basis_bytes,
+    svdcache_version, svdcache_strerror, svdcache_fit_workspace_bytes, svdcache_workspace_bytes,
+    svdcache_fit_status_offset, SVDC_FIT_JACOBI_CAPPED, SVDC_FIT_RANK_DEFICIENT, svdcache_packed_basis_bytes,
     svdcache_has_mfma_path, svdcache_fit_basis, svdcache_pack_basis, svdcache_full_step, svdcache_forecast,
     svdcache_full_step_residual_ema,
     svdcache_select_rank, svdcache_truncate_basis, svdcache_extrapolation_weights, svdcache_forecast_combine,
@@ -18,7 +19,8 @@ from .binding import (
 
 __all__ = [
     "SvdcError", "Shape", "SVDC_PRECISE", "SVDC_FAST", "lib_path", "load_library", "exported_symbols",
-    "svdcache_version", "svdcache_strerror", "svdcache_fit_workspace_bytes", "svdcache_packed_basis_bytes",
+    "svdcache_version", "svdcache_strerror", "svdcache_fit_workspace_bytes", "svdcache_workspace_bytes",
+    "svdcache_fit_status_offset", "SVDC_FIT_JACOBI_CAPPED", "SVDC_FIT_RANK_DEFICIENT", "svdcache_packed_basis_bytes",
     "svdcache_has_mfma_path", "svdcache_fit_basis", "svdcache_pack_basis", "svdcache_full_step",
     "svdcache_forecast", "svdcache_full_step_residual_ema", "svdcache_select_rank", "svdcache_truncate_basis", "svdcache_extrapolation_weights",
     "svdcache_forecast_combine", "svdcache_basis_overlap", "svdcache_rebase_state", "svdcache_basis_similarity",

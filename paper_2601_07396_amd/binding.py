@@ -28,13 +28,16 @@ class Shape(C.Structure):
 
 class FitParams(C.Structure):
     """Mirror of svdc_fit_params."""
-    _fields_ = [("oversample_p", C.c_int32), ("power_iters_q", C.c_int32), ("seed", C.c_uint64)]
+    _fields_ = [("oversample_p", C.c_int32), ("power_iters_q", C.c_int32), ("seed", C.c_uint64),
+                ("jacobi_max_sweeps", C.c_int32), ("reserved", C.c_int32)]
 
 
 EXPORTS = {
     "svdcache_version": (C.c_int32, []),
     "svdcache_strerror": (C.c_char_p, [C.c_int32]),
     "svdcache_fit_workspace_bytes": (C.c_size_t, [C.POINTER(Shape), C.POINTER(FitParams)]),
+    "svdcache_workspace_bytes": (C.c_size_t, [C.POINTER(Shape), C.POINTER(FitParams)]),
+    "svdcache_fit_status_offset": (C.c_size_t, [C.POINTER(Shape), C.POINTER(FitParams)]),
     "svdcache_packed_basis_bytes": (C.c_size_t, [C.POINTER(Shape)]),
     "svdcache_has_mfma_path": (C.c_int32, [C.POINTER(Shape)]),
     "svdcache_fit_basis": (C.c_int32, [C.POINTER(Shape), C.POINTER(FitParams), C.c_void_p, C.c_void_p, C.c_void_p,
@@ -170,9 +173,22 @@ def _check(code: int, where: str):
         raise SvdcError(code, where)
 
 
-def svdcache_fit_workspace_bytes(shape: Shape, p: int = 0, q: int = 0, seed: int = 0) -> int:
-    fp = FitParams(p, q, seed)
+SVDC_FIT_JACOBI_CAPPED, SVDC_FIT_RANK_DEFICIENT = 1, 2
+
+
+def svdcache_fit_workspace_bytes(shape: Shape, p: int = 0, q: int = 0, seed: int = 0, max_sweeps: int = 0) -> int:
+    fp = FitParams(p, q, seed, max_sweeps, 0)
     return load_library().svdcache_fit_workspace_bytes(C.byref(shape), C.byref(fp))
+
+
+def svdcache_workspace_bytes(shape: Shape, p: int = 0, q: int = 0, seed: int = 0, max_sweeps: int = 0) -> int:
+    fp = FitParams(p, q, seed, max_sweeps, 0)
+    return load_library().svdcache_workspace_bytes(C.byref(shape), C.byref(fp))
+
+
+def svdcache_fit_status_offset(shape: Shape, p: int = 0, q: int = 0, seed: int = 0, max_sweeps: int = 0) -> int:
+    fp = FitParams(p, q, seed, max_sweeps, 0)
+    return load_library().svdcache_fit_status_offset(C.byref(shape), C.byref(fp))
 
 
 def svdcache_packed_basis_bytes(shape: Shape) -> int:
@@ -183,13 +199,14 @@ def svdcache_has_mfma_path(shape: Shape) -> bool:
     return bool(load_library().svdcache_has_mfma_path(C.byref(shape)))
 
 
-def svdcache_fit_basis(shape: Shape, F, V, sigma, fro2, workspace, p: int = 0, q: int = 0, seed: int = 0):
+def svdcache_fit_basis(shape: Shape, F, V, sigma, fro2, workspace, p: int = 0, q: int = 0, seed: int = 0,
+                       max_sweeps: int = 0):
     _like_features(shape, F=F)
     _dense_f32(shape.B * shape.D * shape.k, "[B, D, k]", V=V)
     _dense_f32(shape.B * shape.k, "[B, k]", sigma=sigma)
     _dense_f32(shape.B, "[B]", fro2=fro2)
     _need_gpu(F, V, sigma, fro2, workspace)
-    fp = FitParams(p, q, seed)
+    fp = FitParams(p, q, seed, max_sweeps, 0)
     rc = load_library().svdcache_fit_basis(C.byref(shape), C.byref(fp), _ptr(F), _ptr(V), _ptr(sigma), _ptr(fro2),
                                            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "svdcache_fit_basis")
@@ -286,19 +303,25 @@ def svdcache_basis_similarity(shape: Shape, V_a, sigma_a, V_b, sigma_b, sim_dir,
 
 # ---- conveniences that only allocate (torch owns the memory) ------------------------------------
 
-def fit_basis(F: torch.Tensor, k: int, p: int = 0, q: int = 0, seed: int = 0):
-    """Allocate outputs + workspace and call svdcache_fit_basis. Returns (V [B,D,k], sigma [B,k], fro2 [B])."""
+def fit_basis(F: torch.Tensor, k: int, p: int = 0, q: int = 0, seed: int = 0, max_sweeps: int = 0,
+              return_status: bool = False):
+    """Allocate outputs + workspace and call svdcache_fit_basis. Returns (V [B,D,k], sigma [B,k], fro2 [B]) and,
+    with return_status, the per-block status words [B] int32 (SVDC_FIT_* flags) copied out of the workspace."""
     shape = make_shape(F, k)
     dev = F.device
     V = torch.empty(shape.B, shape.D, k, device=dev, dtype=torch.float32)
     sigma = torch.empty(shape.B, k, device=dev, dtype=torch.float32)
     fro2 = torch.empty(shape.B, device=dev, dtype=torch.float32)
-    nbytes = svdcache_fit_workspace_bytes(shape, p, q, seed)
+    nbytes = svdcache_workspace_bytes(shape, p, q, seed, max_sweeps)
     if nbytes == 0:
-        raise SvdcError(-2, "svdcache_fit_workspace_bytes")
+        raise SvdcError(-2, "svdcache_workspace_bytes")
     ws = torch.empty(nbytes, device=dev, dtype=torch.uint8)
-    svdcache_fit_basis(shape, F, V, sigma, fro2, ws, p, q, seed)
-    return V, sigma, fro2
+    svdcache_fit_basis(shape, F, V, sigma, fro2, ws, p, q, seed, max_sweeps)
+    if not return_status:
+        return V, sigma, fro2
+    off = svdcache_fit_status_offset(shape, p, q, seed, max_sweeps)
+    status = ws[off:off + 4 * shape.B].view(torch.int32).clone()
+    return V, sigma, fro2, status
 
 
 def fit_basis_for_energy(F: torch.Tensor, tau: float = 0.85, k_init: int = 32, k_max: int = 128, p: int = 0,

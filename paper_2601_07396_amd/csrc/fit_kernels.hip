@@ -11,8 +11,8 @@
 // condition number of F's leading part and its Gram matrix squares it again.
 // The tall matrices Q, Z (D x l) and Y (N x l) are float32.
 //
-// This file holds the general (vector-ALU) kernels; the two products with F have
-// matrix-core versions in mfma_kernels.hip.
+// This file holds the small-matrix kernels, the host orchestration and the general (vector-ALU) versions of the two
+// products with F; their matrix-core versions are in fit_mfma_kernels.hip.
 #include <algorithm>
 #include <utility>
 
@@ -215,6 +215,12 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restri
   G[(int64_t)b * ll + e] = s;
 }
 
+// A pivot of the Cholesky factorisation below kRankTol x the largest diagonal entry of the Gram matrix means that a
+// column of the sketch depends on the others to within (1e-6)^2, the round-off of the float32 sketch itself: the
+// matrix has numerical rank < l.  The shift keeps the factorisation going (the result stays orthonormal, directions
+// beyond the numerical rank are arbitrary) and the block's status word reports it.
+constexpr double kRankTol = 1e-12;
+
 // ---------------------------------------------------------------------------
 // Cholesky factor of a (shifted) Gram matrix and the transposed inverse factor.
 //   in : G [l x l] symmetric positive semi-definite, float64
@@ -223,7 +229,7 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restri
 // One workgroup per block.  The matrix lives in LDS when it fits.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void chol_inv_kernel(double* G, double* Minv, int l, int use_lds,
-                                                       double rel_shift) {
+                                                       double rel_shift, int32_t* info) {
   extern __shared__ double dyn_lds[];
   __shared__ double s_shift;
   const int b = blockIdx.x, t = threadIdx.x;
@@ -242,8 +248,10 @@ __global__ __launch_bounds__(256) void chol_inv_kernel(double* G, double* Minv, 
   for (int i = t; i < l; i += 256) A[i * l + i] += s_shift;
   __syncthreads();
 
+  bool dependent = false;   // a pivot at the level of the sketch's float32 round-off (see kRankTol)
   for (int c = 0; c < l; ++c) {
     const double piv = sqrt(fmax(A[c * l + c], 1e-300));
+    dependent |= A[c * l + c] < s_shift * (kRankTol / rel_shift);
     __syncthreads();
     if (t == 0) A[c * l + c] = piv;
     for (int i = c + 1 + t; i < l; i += 256) A[i * l + c] /= piv;
@@ -256,6 +264,7 @@ __global__ __launch_bounds__(256) void chol_inv_kernel(double* G, double* Minv, 
     __syncthreads();
   }
 
+  if (t == 0 && dependent && info) atomicOr(info + b, SVDC_FIT_RANK_DEFICIENT);
   if (Minv) {
     // column j of L^-1 by forward substitution, stored as row j of Minv = L^-T
     double* m = Minv + (int64_t)b * l * l;
@@ -317,7 +326,8 @@ __global__ __launch_bounds__(256) void rows_times_small_kernel(const float* __re
 //   rdiag  out     (nullable) 1 / L[i][i]
 // ---------------------------------------------------------------------------
 template <int BS>
-__global__ __launch_bounds__(256) void chol_reg_kernel(double* G, double* rdiag, int l, double rel_shift) {
+__global__ __launch_bounds__(256) void chol_reg_kernel(double* G, double* rdiag, int l, double rel_shift,
+                                                       int32_t* info) {
   constexpr int LM = 16 * BS;          // padded matrix size
   __shared__ double colbuf[2][LM];
   __shared__ double s_shift;
@@ -342,6 +352,7 @@ __global__ __launch_bounds__(256) void chol_reg_kernel(double* G, double* rdiag,
       a[ii][jj] = v;
     }
   const bool below = ti > tj;          // every element of the block is below the diagonal
+  bool dependent = false;
   for (int c = 0; c < l; ++c) {
     double* col = colbuf[c & 1];
     const int cb = c / BS, cq = c % BS;
@@ -357,6 +368,7 @@ __global__ __launch_bounds__(256) void chol_reg_kernel(double* G, double* rdiag,
     __syncthreads();
     if (tj < cb || ti < tj) continue;  // block column finished, or block above the diagonal
     const double piv2 = fmax(col[c], 1e-300);
+    dependent |= col[c] < s_shift * (kRankTol / rel_shift);
     // 1 / sqrt(piv2): hardware estimate refined by two Newton steps (an exact sqrt and a division per
     // column would dominate this kernel)
     double rs = __builtin_amdgcn_rsq(piv2);
@@ -399,6 +411,8 @@ __global__ __launch_bounds__(256) void chol_reg_kernel(double* G, double* rdiag,
       if (i < l && j < l) g[(int64_t)i * l + j] = v;
       if (rdiag && i == j && i < l) rdiag[(int64_t)b * l + i] = 1.0 / v;
     }
+  // the thread that owns the last diagonal block has seen every pivot
+  if (info && dependent && ti == tj && ti == (l - 1) / BS) atomicOr(info + b, SVDC_FIT_RANK_DEFICIENT);
 }
 
 // ---------------------------------------------------------------------------
@@ -553,7 +567,8 @@ constexpr int kJacobiThreads = 512;
 template <bool a_in_lds, bool w_in_lds, bool acc_w, int NE>   // compile-time so that LDS accesses are ds_* instructions, not flat ones
 __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __restrict__ Lfac, double* Wout, float* sigma,
                                                      double* gA, double* gW, int l, int k,
-                                                     const double* fro_acc, float* fro2) {
+                                                     const double* fro_acc, float* fro2, int max_sweeps,
+                                                     int32_t* info) {
   extern __shared__ double dyn_lds[];
   __shared__ double nrm[256];
   constexpr int NT = kJacobiThreads;
@@ -578,7 +593,8 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
   const int group = t / tp, gl = t % tp;
   const bool active = group < npairs;
 
-  for (int sweep = 0; sweep < 40; ++sweep) {
+  bool converged = false;
+  for (int sweep = 0; sweep < max_sweeps; ++sweep) {
     if (t == 0) s_rot = 0;
     __syncthreads();
     for (int step = 0; step < le - 1; ++step) {
@@ -684,8 +700,9 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
     }
     const int rot = s_rot;
     __syncthreads();
-    if (rot == 0) break;
+    if (rot == 0) { converged = true; break; }
   }
+  if (t == 0 && !converged && info) atomicOr(info + b, SVDC_FIT_JACOBI_CAPPED);
 
   for (int j = t; j < l; j += NT) {
     double s = 0.0;
@@ -765,6 +782,9 @@ bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan)
   plan->l = l;
   plan->q = q;
   plan->seed = p ? p->seed : 0;
+  const int sweeps = p ? p->jacobi_max_sweeps : 0;
+  if (sweeps < 0 || sweeps > 1000) return false;
+  plan->max_sweeps = sweeps == 0 ? 40 : sweeps;
   size_t off = 0;
   const size_t B = s.B;
   plan->off_Q = off; off = align_up(off + B * s.D * l * sizeof(float), 256);
@@ -778,7 +798,9 @@ bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan)
   plan->off_Gp = off; off = align_up(off + B * kGramSlices * (size_t)l * l * sizeof(double), 256);
   plan->off_M = off; off = align_up(off + B * l * l * sizeof(double), 256);
   plan->off_W = off; off = align_up(off + 2 * B * l * (l + 1) * sizeof(double), 256);
+  // ||F||_F^2 accumulators (B doubles) followed by the status words (B int32, see svdcache_fit_status_offset)
   plan->off_misc = off; off = align_up(off + B * sizeof(double), 256);
+  plan->off_info = off; off = align_up(off + B * sizeof(int32_t), 256);
   plan->mfma = fit_mfma_supported(s, l);
   plan->off_Qp = off;
   if (plan->mfma) off = align_up(off + fit_mfma_packed_q_bytes(s, l), 256);
@@ -828,16 +850,16 @@ void gram(const float* A, double* G, double* Gpart, int B, int rows, int l, hipS
   gram_reduce_kernel<<<dim3((unsigned)((ll + 255) / 256), B), 256, 0, st>>>(Gpart, G, nslice, ll);
 }
 
-int32_t chol_inv(double* G, double* Minv, int B, int l, hipStream_t st, double* rdiag = nullptr) {
+int32_t chol_inv(double* G, double* Minv, int B, int l, int32_t* info, hipStream_t st, double* rdiag = nullptr) {
   if (!Minv && l <= 128) {   // factor only: register blocked
-    if (l <= 64) chol_reg_kernel<4><<<B, 256, 0, st>>>(G, rdiag, l, 1e-14);
-    else chol_reg_kernel<8><<<B, 256, 0, st>>>(G, rdiag, l, 1e-14);
+    if (l <= 64) chol_reg_kernel<4><<<B, 256, 0, st>>>(G, rdiag, l, 1e-14, info);
+    else chol_reg_kernel<8><<<B, 256, 0, st>>>(G, rdiag, l, 1e-14, info);
     return SVDC_OK;
   }
   const size_t bytes = (size_t)l * l * sizeof(double);
   const int use_lds = bytes <= kLdsBudget;
   if (use_lds && set_dyn_lds((const void*)chol_inv_kernel, bytes) != SVDC_OK) return SVDC_E_HIP;
-  chol_inv_kernel<<<B, 256, use_lds ? bytes : 0, st>>>(G, Minv, l, use_lds, 1e-14);
+  chol_inv_kernel<<<B, 256, use_lds ? bytes : 0, st>>>(G, Minv, l, use_lds, 1e-14, info);
   return SVDC_OK;
 }
 
@@ -860,10 +882,11 @@ int32_t rows_times_small(const float* In, const double* M, float* Out, int B, in
 // power iteration well conditioned.  two_pass repeats the step on the result (CholeskyQR2), giving
 // orthonormality at float32 round-off; the result is then back in Zin.
 // Out = In * L^-T with L the Cholesky factor of In^T In (left in G by chol_inv)
-int32_t cholqr_apply(const float* In, float* Out, double* G, double* M, int B, int rows, int l, hipStream_t st) {
+int32_t cholqr_apply(const float* In, float* Out, double* G, double* M, int B, int rows, int l, int32_t* info,
+                     hipStream_t st) {
   if (l <= 128) {
     // M receives the reciprocal diagonal of L (its first l entries per block)
-    if (chol_inv(G, nullptr, B, l, st, M) != SVDC_OK) return SVDC_E_HIP;
+    if (chol_inv(G, nullptr, B, l, info, st, M) != SVDC_OK) return SVDC_E_HIP;
     dim3 grid((rows + 255) / 256, B);
     if (l <= 16) tri_solve_rows_kernel<16><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
     else if (l <= 32) tri_solve_rows_kernel<32><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
@@ -871,17 +894,19 @@ int32_t cholqr_apply(const float* In, float* Out, double* G, double* M, int B, i
     else tri_solve_rows_kernel<128><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
     return SVDC_OK;
   }
-  if (chol_inv(G, M, B, l, st) != SVDC_OK) return SVDC_E_HIP;
+  if (chol_inv(G, M, B, l, info, st) != SVDC_OK) return SVDC_E_HIP;
   return rows_times_small(In, M, Out, B, rows, l, l, l, st);
 }
 
 int32_t orth(float* Zin, float* Qout, double* G, double* Gpart, double* M, int B, int rows, int l, bool two_pass,
-             hipStream_t st) {
+             int32_t* info, hipStream_t st) {
   gram(Zin, G, Gpart, B, rows, l, st);
-  if (cholqr_apply(Zin, Qout, G, M, B, rows, l, st) != SVDC_OK) return SVDC_E_HIP;
+  if (cholqr_apply(Zin, Qout, G, M, B, rows, l, info, st) != SVDC_OK) return SVDC_E_HIP;
   if (!two_pass) return SVDC_OK;
+  // the second pass factors a matrix that is already orthonormal to float32 round-off: only the first one can
+  // meet a dependent column
   gram(Qout, G, Gpart, B, rows, l, st);
-  return cholqr_apply(Qout, Zin, G, M, B, rows, l, st);
+  return cholqr_apply(Qout, Zin, G, M, B, rows, l, nullptr, st);
 }
 
 template <typename T>
@@ -896,8 +921,11 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   double* M = (double*)(ws + pl.off_M);
   double* Wg = (double*)(ws + pl.off_W);
   double* misc = (double*)(ws + pl.off_misc);
+  int32_t* info = (int32_t*)(ws + pl.off_info);
 
   const int64_t nq = (int64_t)B * s.D * l;
+  // fro accumulators and status words are adjacent 256-byte aligned areas: one fill clears both
+  zero_f64(misc, (int64_t)((pl.off_info - pl.off_misc) + align_up((size_t)B * sizeof(int32_t), 8)) / 8, st);
   // With power iterations the Gaussian test matrix (D x l) is used as it is: its columns are well conditioned
   // and every product F^T F Q is re-orthonormalised afterwards.  With none, the sketch is Z = F^T Omega with a
   // Gaussian Omega (N x l) -- the plain randomized range finder, exact when rank(F) <= l -- and Q <- orth(Z), two
@@ -907,7 +935,7 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
     init_omega_kernel<<<(unsigned)((ny + 255) / 256), 256, 0, st>>>(Y, (int64_t)s.N * l, ny, pl.seed);
     if (pl.mfma) fit_mfma_backproject(s, l, F, Y, nullptr, Z, st);
     else gemm_fty<T>(s, l, F, Y, Z, st);
-    if (orth(Z, Q, G, Gp, M, B, s.D, l, true, st) != SVDC_OK) return SVDC_E_HIP;
+    if (orth(Z, Q, G, Gp, M, B, s.D, l, true, info, st) != SVDC_OK) return SVDC_E_HIP;
     std::swap(Q, Z);
   } else {
     init_omega_kernel<<<(unsigned)((nq + 255) / 256), 256, 0, st>>>(Q, (int64_t)s.D * l, nq, pl.seed);
@@ -916,7 +944,6 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   void* Qp = ws + pl.off_Qp;
   const bool want_fro = fro2 != nullptr;
   bool fro_done = false;
-  if (want_fro) zero_f64(misc, B, st);
   // Y = F Q.  The last product feeds the Rayleigh-Ritz step and uses the full-precision operand split.
   auto project = [&](bool last) {
     if (pl.mfma) {
@@ -935,14 +962,14 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
       gemm_fty<T>(s, l, F, Y, Z, st);
     }
     const bool last_it = it + 1 == pl.q;
-    if (orth(Z, Q, G, Gp, M, B, s.D, l, last_it, st) != SVDC_OK) return SVDC_E_HIP;
+    if (orth(Z, Q, G, Gp, M, B, s.D, l, last_it, info, st) != SVDC_OK) return SVDC_E_HIP;
     if (last_it) std::swap(Q, Z);
   }
 
   // Rayleigh-Ritz on span(Q)
   project(true);
   gram(Y, G, Gp, B, s.N, l, st);
-  if (chol_inv(G, nullptr, B, l, st) != SVDC_OK) return SVDC_E_HIP;
+  if (chol_inv(G, nullptr, B, l, info, st) != SVDC_OK) return SVDC_E_HIP;
   if (want_fro && !fro_done) {
     const int rpg = 64;
     sumsq_kernel<T><<<dim3((s.N + rpg - 1) / rpg, B), 256, 0, st>>>(F, misc, s.N, s.D, s.ldf, s.block_stride, rpg);
@@ -960,7 +987,7 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   const int ne = (l + tp - 1) / tp;
   auto launch = [&](auto kernel) -> int32_t {
     if (set_dyn_lds((const void*)kernel, lds) != SVDC_OK) return SVDC_E_HIP;
-    kernel<<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+    kernel<<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2, pl.max_sweeps, info);
     return SVDC_OK;
   };
   int32_t jrc = SVDC_OK;
@@ -974,7 +1001,8 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
     if (ne <= 8) jrc = launch(jacobi_kernel<true, false, false, 8>);
     else jrc = launch(jacobi_kernel<true, false, false, 16>);
   } else {
-    jacobi_kernel<false, false, true, 0><<<B, kJacobiThreads, 0, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2);
+    jacobi_kernel<false, false, true, 0><<<B, kJacobiThreads, 0, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2,
+                                                                       pl.max_sweeps, info);
   }
   if (jrc != SVDC_OK) return jrc;
   if (rows_times_small(Q, M, V, B, s.D, l, s.k, l, st) != SVDC_OK) return SVDC_E_HIP;

@@ -30,7 +30,7 @@ int32_t check_shape(const svdc_shape* s) {
 
 extern "C" {
 
-int32_t svdcache_version(void) { return 200; }   // 0.2.0: entry points beyond fit / full step / cached step
+int32_t svdcache_version(void) { return 300; }   // 0.3.0: fit status words, svdcache_workspace_bytes
 
 const char* svdcache_strerror(int32_t status) {
   switch (status) {
@@ -50,6 +50,16 @@ size_t svdcache_fit_workspace_bytes(const svdc_shape* shape, const svdc_fit_para
   FitPlan plan;
   if (check_shape(shape) != SVDC_OK || !make_fit_plan(*shape, params, &plan)) return 0;
   return plan.total;
+}
+
+size_t svdcache_workspace_bytes(const svdc_shape* shape, const svdc_fit_params* params) {
+  return svdcache_fit_workspace_bytes(shape, params);
+}
+
+size_t svdcache_fit_status_offset(const svdc_shape* shape, const svdc_fit_params* params) {
+  FitPlan plan;
+  if (check_shape(shape) != SVDC_OK || !make_fit_plan(*shape, params, &plan)) return 0;
+  return plan.off_info;
 }
 
 size_t svdcache_packed_basis_bytes(const svdc_shape* shape) {

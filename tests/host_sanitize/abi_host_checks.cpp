@@ -55,8 +55,13 @@ int main() {
       const int32_t has = svdcache_has_mfma_path(&s);
       EXPECT((pk > 0) == (has == 1));
       for (int32_t pp : {0, -1, 5, 300, big, -9}) for (int32_t qq : {0, -1, 2, 1000, -9}) {
-        svdc_fit_params fp; fp.oversample_p = pp; fp.power_iters_q = qq; fp.seed = 1;
-        (void)svdcache_fit_workspace_bytes(&s, &fp);
+        svdc_fit_params fp{}; fp.oversample_p = pp; fp.power_iters_q = qq; fp.seed = 1;
+        fp.jacobi_max_sweeps = (pp == 5) ? qq : 0;
+        const size_t need = svdcache_fit_workspace_bytes(&s, &fp);
+        EXPECT(svdcache_workspace_bytes(&s, &fp) == need);
+        const size_t off = svdcache_fit_status_offset(&s, &fp);
+        EXPECT((need == 0) == (off == 0));
+        if (need) EXPECT(off % 256 == 0 && off + sizeof(int32_t) * (size_t)s.B <= need);
       }
       (void)svdcache_fit_workspace_bytes(&s, nullptr);
       // the step entry points see the same shapes with a misaligned pointer: they must refuse, whatever the shape

@@ -387,6 +387,43 @@ def test_fit_basis_without_power_iterations(dtype, N, D, k, p):
     _fit_checks(F[0], V[0], sigma[0], fro2[0], k, store, lead=max(1, k // 4))
 
 
+def test_fit_status_words():
+    """Per-block status of the fit, read from the workspace: 0 for well-conditioned features; the rank-deficiency
+    flag for features of exact rank < l (the fitted basis still passes every check); the sweep-cap flag when the
+    host allows the small SVD a single sweep (every kernel still runs to its normal end)."""
+    g = torch.Generator().manual_seed(77)
+    N, D, k = 400, 256, 24
+    r_all = min(N, D)                                           # full power-law spectrum: well conditioned
+    good = (torch.linalg.qr(torch.randn(N, r_all, generator=g, dtype=torch.float64))[0]
+            * (10.0 / torch.arange(1, r_all + 1, dtype=torch.float64))) \
+        @ torch.linalg.qr(torch.randn(D, r_all, generator=g, dtype=torch.float64))[0].T
+    rank = 30                                                   # < l = 48
+    left = torch.linalg.qr(torch.randn(N, rank, generator=g, dtype=torch.float64))[0]
+    right = torch.linalg.qr(torch.randn(D, rank, generator=g, dtype=torch.float64))[0]
+    low = ((left * (10.0 * torch.arange(1, rank + 1, dtype=torch.float64) ** -0.8)) @ right.T)
+    for dtype, store in ((torch.bfloat16, "bf16"), (torch.float32, "f32")):
+        # bf16 rounding would make the low-rank block full rank at the 2^-9 level: keep it exactly low rank by
+        # building it from bf16-representable factors only in the float32 case
+        F = torch.stack([good.to(dtype), low.to(dtype)]).contiguous()
+        V, sigma, fro2, status = pkg.fit_basis(F.to(DEV), k, q=6, return_status=True)
+        torch.cuda.synchronize()
+        status = status.cpu().tolist()
+        assert status[0] == 0, f"{store}: well-conditioned block reports {status[0]}"
+        _fit_checks(F[0], V[0], sigma[0], fro2[0], k, store)
+        if store == "f32":
+            assert status[1] == pkg.SVDC_FIT_RANK_DEFICIENT, f"rank-deficient block reports {status[1]}"
+            _fit_checks(F[1], V[1], sigma[1], fro2[1], k, store)
+        # one sweep is never enough for a 48 x 48 factor: flagged, and nothing else changes for the other flag
+        _, _, _, capped = pkg.fit_basis(F.to(DEV), k, q=6, max_sweeps=1, return_status=True)
+        torch.cuda.synchronize()
+        capped = capped.cpu().tolist()
+        assert capped[0] == pkg.SVDC_FIT_JACOBI_CAPPED
+        assert capped[1] & pkg.SVDC_FIT_JACOBI_CAPPED
+    shape = pkg.make_shape(F.to(DEV), k)
+    assert pkg.svdcache_workspace_bytes(shape) == pkg.svdcache_fit_workspace_bytes(shape) > 0
+    assert 0 < pkg.svdcache_fit_status_offset(shape) < pkg.svdcache_workspace_bytes(shape)
+
+
 def test_fit_basis_flux_block_full_size():
     """One FLUX-shaped block (4608 x 3072 bf16, k = 32) at full size against the exact decomposition."""
     wl = WORKLOADS["flux1"]
