@@ -149,6 +149,22 @@ int32_t svdcache_fit_basis(const svdc_shape* shape, const svdc_fit_params* param
                            const void* F, float* V, float* sigma, float* fro2,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* The basis fit for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, arguments and results as
+ * svdcache_fit_basis, but the workspace is a static device array of SVDC_STATIC_SCRATCH_BYTES inside the library
+ * (each GPU the library runs on holds its own copy until the process ends); the call allocates and frees nothing.
+ *   status  out  [B] int32 device, the SVDC_FIT_* status words of the blocks; may be NULL
+ * Problems whose workspace (svdcache_workspace_bytes) exceeds SVDC_STATIC_SCRATCH_BYTES are refused with
+ * SVDC_E_WORKSPACE before anything is launched: at the default parameters 32 MiB hold 7 blocks of 4608 x 3072 at
+ * rank 32, or one at rank 128.  The device that owns `stream` must be the current device.  All calls on one GPU
+ * share that GPU's array: calls that overlap in time on one GPU (different streams, different threads) race and must
+ * be serialised by the caller; consecutive calls on one stream are fine (the fit overwrites or clears every part of
+ * the array it reads).  The first call on a device looks up the array's address (no allocation). */
+#define SVDC_STATIC_SCRATCH_BYTES (32u << 20)
+int32_t svdcache_fit_basis_static(const svdc_shape* shape, const svdc_fit_params* params,
+                                  const void* F, float* V, float* sigma, float* fro2, int32_t* status,
+                                  void* stream);
+
 /* Re-lay V [B,D,k] float32 into the operand format of the matrix-core kernels
  * (bf16 high and low parts, tiled per 64-lane wavefront).  The packed buffer
  * is opaque, belongs to the caller, and stays valid for as long as V is

@@ -42,6 +42,8 @@ EXPORTS = {
     "svdcache_has_mfma_path": (C.c_int32, [C.POINTER(Shape)]),
     "svdcache_fit_basis": (C.c_int32, [C.POINTER(Shape), C.POINTER(FitParams), C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "svdcache_fit_basis_static": (C.c_int32, [C.POINTER(Shape), C.POINTER(FitParams), C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "svdcache_pack_basis": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "svdcache_full_step": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_void_p]),
@@ -210,6 +212,25 @@ def svdcache_fit_basis(shape: Shape, F, V, sigma, fro2, workspace, p: int = 0, q
     rc = load_library().svdcache_fit_basis(C.byref(shape), C.byref(fp), _ptr(F), _ptr(V), _ptr(sigma), _ptr(fro2),
                                            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "svdcache_fit_basis")
+
+
+SVDC_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def svdcache_fit_basis_static(shape: Shape, F, V, sigma, fro2, status=None, p: int = 0, q: int = 0, seed: int = 0,
+                              max_sweeps: int = 0):
+    """The fit on the library's static device workspace (no allocation inside the call)."""
+    _like_features(shape, F=F)
+    _dense_f32(shape.B * shape.D * shape.k, "[B, D, k]", V=V)
+    _dense_f32(shape.B * shape.k, "[B, k]", sigma=sigma)
+    _dense_f32(shape.B, "[B]", fro2=fro2)
+    if status is not None and (status.dtype != torch.int32 or not status.is_contiguous() or status.numel() != shape.B):
+        raise ValueError("status: need a contiguous int32 tensor of B elements")
+    _need_gpu(F, V, sigma, fro2, status)
+    fp = FitParams(p, q, seed, max_sweeps, 0)
+    rc = load_library().svdcache_fit_basis_static(C.byref(shape), C.byref(fp), _ptr(F), _ptr(V), _ptr(sigma),
+                                                  _ptr(fro2), _ptr(status), _stream())
+    _check(rc, "svdcache_fit_basis_static")
 
 
 def svdcache_pack_basis(shape: Shape, V, packed):

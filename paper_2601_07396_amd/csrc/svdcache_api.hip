@@ -1,9 +1,16 @@
 // C ABI of libsvdcache: argument validation and dispatch.  See include/svdcache.h.
 #include <stdint.h>
 
+#include <mutex>
+
 #include "svdc_internal.h"
 
 using namespace svdc;
+
+// Workspace of svdcache_fit_basis_static: one array per GPU, part of the loaded code object, so the entry point
+// never allocates.  In host code this name is only a handle for hipGetSymbolAddress; the device address it resolves
+// to (per device) is what kernels get.
+static __device__ __align__(256) unsigned char scratch[SVDC_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -24,6 +31,29 @@ int32_t check_shape(const svdc_shape* s) {
   const int64_t unit = s->dtype == SVDC_BF16 ? 8 : 4;
   if (s->D % unit || s->ldf % unit || s->block_stride % unit) return SVDC_E_ALIGN;
   return SVDC_OK;
+}
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, resolved on first use
+std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch` (looked up once per device, with that device current).
+int32_t static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SVDC_E_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SVDC_E_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return SVDC_OK;
+}
+
+__global__ void copy_status_kernel(const int32_t* __restrict__ src, int32_t* __restrict__ dst, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
 }
 
 }  // namespace
@@ -82,6 +112,27 @@ int32_t svdcache_fit_basis(const svdc_shape* shape, const svdc_fit_params* param
   if (!make_fit_plan(*shape, params, &plan)) return SVDC_E_PARAM;
   if (workspace_bytes < plan.total) return SVDC_E_WORKSPACE;
   return run_fit(*shape, plan, F, V, sigma, fro2, workspace, (hipStream_t)stream);
+}
+
+int32_t svdcache_fit_basis_static(const svdc_shape* shape, const svdc_fit_params* params, const void* F, float* V,
+                                  float* sigma, float* fro2, int32_t* status, void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!F || !V || !sigma) return SVDC_E_NULL;
+  if (!aligned(F, 16) || !aligned(V, 16) || (status && !aligned(status, 4))) return SVDC_E_ALIGN;
+  FitPlan plan;
+  if (shape->k > 256) return SVDC_E_SHAPE;
+  if (!make_fit_plan(*shape, params, &plan)) return SVDC_E_PARAM;
+  if (plan.total > (size_t)SVDC_STATIC_SCRATCH_BYTES) return SVDC_E_WORKSPACE;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != SVDC_OK) return rc;
+  // the fit clears what must start at zero (accumulators, status words) with fill kernels of its own
+  rc = run_fit(*shape, plan, F, V, sigma, fro2, ws, (hipStream_t)stream);
+  if (rc != SVDC_OK || !status) return rc;
+  copy_status_kernel<<<(shape->B + 255) / 256, 256, 0, (hipStream_t)stream>>>(
+      reinterpret_cast<const int32_t*>(static_cast<const char*>(ws) + plan.off_info), status, shape->B);
+  return launch_status();
 }
 
 int32_t svdcache_pack_basis(const svdc_shape* shape, const float* V, void* packed, size_t packed_bytes,
