@@ -26,13 +26,23 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TF = 2500.0     # dense bf16, published
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command (workload flux57,
-# k = 32, SVDC_PRECISE), each scaled by what the same counter reads for a plain 1 GiB device copy
-# (profiles/flux57_k32_hbm_traffic.md).  Only valid for that configuration.
-MEASURED_TRAFFIC = {
-    ("flux57", 32, False, "forecast_mfma_kernel"): 3403536265,
-    ("flux57", 32, False, "full_step_mfma_kernel"): 3930973209,
-}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "flux57_k32_hbm_traffic.md")
+
+
+def traffic_from_profile(kernel: str, path: str = TRAFFIC_PROFILE):
+    """HBM bytes per launch of `kernel` as recorded in the tracked rocprofv3 summary (FETCH_SIZE + WRITE_SIZE, each
+    scaled by what the same counter reads for a plain copy of known size): the last column of the row whose first
+    cell starts with the kernel's name.  Not measured by the run that prints it; valid for workload flux57, k = 32,
+    SVDC_PRECISE only.  None if the file or the row is missing."""
+    try:
+        with open(path) as f:
+            for line in f:
+                cells = [c.strip() for c in line.strip().strip("|").split("|")]
+                if len(cells) >= 8 and cells[0].startswith(kernel):
+                    return int(cells[-1])
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def algorithmic_bytes(wl, q_passes):
@@ -92,6 +102,67 @@ def sweep(args):
         del Fs, Rs, Fh
 
 
+def run_probes():
+    """Memory-system ceilings of this machine, measured with the tracked probe kernels (include/svdcache_probes.h):
+    prints one JSON line per probe.  Not the headline benchmark."""
+    import torch
+    from paper_2601_07396_amd import probes
+    dev = torch.device("cuda:0")
+    rows = 57 * 4608
+    nbytes = rows * 6144                     # one feature tensor of the default workload: 1.6 GB
+    a = torch.empty(nbytes, device=dev, dtype=torch.uint8).fill_(1)
+    b = torch.empty_like(a)
+    sink = torch.zeros(1, device=dev, dtype=torch.int32)
+
+    def timed(fn, reps=10):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0.record()
+        for _ in range(reps):
+            fn()
+        t1.record()
+        torch.cuda.synchronize()
+        return t0.elapsed_time(t1) / reps
+
+    def report(name, ms, moved, **kw):
+        print(json.dumps({"probe": name, "ms": ms, "bytes_moved": moved, "GBps": moved / ms / 1e6,
+                          "frac_of_hbm_peak": moved / ms / 1e6 / HBM_PEAK_GBS, **kw}), flush=True)
+
+    report("copy: 16 B per lane, one piece per thread, 1.6 GB in + 1.6 GB out", timed(lambda: probes.copy(b, a)), 2 * nbytes)
+    report("read-only stream, 1.6 GB", timed(lambda: probes.read(a, sink)), nbytes)
+    report("torch Tensor.copy_ (runtime's device-to-device copy), 1.6 GB in + 1.6 GB out", timed(lambda: b.copy_(a)), 2 * nbytes)
+    for tpg, inter in ((1, 0), (12, 0), (12, 1), (16, 1)):
+        report(f"tile copy, cached-step skeleton: {tpg} tile(s) per workgroup, {'interleaved' if inter else 'contiguous'}",
+               timed(lambda: probes.tile_copy(b, a, rows, tpg, inter)), 2 * nbytes)
+    for tr in (16, 32, 48):
+        report(f"burst copy, full-step skeleton: persistent workgroups, {tr}-row tiles in registers",
+               timed(lambda: probes.burst_copy(b, a, rows, tr)), 2 * nbytes)
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    for window, what in ((786432, "786 KB (packed basis of one block, rank 32)"), (1572864, "1.5 MB (rank 64)"),
+                         (196608, "192 KB")):
+        reps_in = max(1, int(4.4e9 / (window * cus)))
+        report(f"L2 -> compute units: {cus} workgroups each re-reading one {what} window {reps_in} times",
+               timed(lambda: probes.l2_stream(a, window, reps_in, cus, sink), reps=5), window * reps_in * cus,
+               note="bytes delivered to the compute units, not HBM traffic")
+    # re-read of what the previous kernel just read: Infinity Cache (256 MB) and L2
+    flush = a[nbytes // 2:]                  # another 0.8 GB, read in between to evict
+    for mb in (64, 128, 192, 256, 512):
+        n = mb << 20
+        probes.read(flush, sink)
+        torch.cuda.synchronize()
+        t0, t1, t2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        t0.record()
+        probes.read(a, sink, n)
+        t1.record()
+        probes.read(a, sink, n)
+        t2.record()
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": f"read {mb} MB, then read it again", "first_GBps": n / t0.elapsed_time(t1) / 1e6,
+                          "again_GBps": n / t1.elapsed_time(t2) / 1e6}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -107,6 +178,8 @@ def main():
     ap.add_argument("--no-widened", action="store_true",
                     help="skip the short timing of the entry points beyond fit / full step / cached step")
     ap.add_argument("--fast", action="store_true", help="SVDC_FAST arithmetic (single bf16 operands)")
+    ap.add_argument("--probes", action="store_true",
+                    help="time the memory-system probe kernels (measured ceilings of this machine) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling profiler byte counters)")
     args = ap.parse_args()
@@ -126,6 +199,9 @@ def main():
     if not os.path.exists(pkg.lib_path()):
         from paper_2601_07396_amd import build
         build.build()
+    if args.probes:
+        run_probes()
+        return
     if args.workload == "sweep":
         sweep(args)
         return
@@ -217,6 +293,8 @@ def main():
 
     avg = {kk: float(np.mean([a.elapsed_time(b) for a, b in v])) for kk, v in times.items()}
     lo = {kk: float(np.min([a.elapsed_time(b) for a, b in v])) for kk, v in times.items()}
+    med = {kk: float(np.median([a.elapsed_time(b) for a, b in v])) for kk, v in times.items()}
+    reps = {kk: len(v) for kk, v in times.items()}
 
     # ---- work accounting -------------------------------------------------------------------------
     q = 3 if wl.dtype == "bf16" else 5
@@ -227,11 +305,11 @@ def main():
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     fit_flops = B * passes * 2.0 * N * D * l
     kernels = {
-        "svdcache_forecast": {"launches_per_step": n_cached, "avg_ms": avg["fore"], "min_ms": lo["fore"],
+        "svdcache_forecast": {"launches_per_step": n_cached, "avg_ms": avg["fore"], "median_ms": med["fore"], "min_ms": lo["fore"], "timed_launches": reps["fore"],
                               "GBps": by_fore / avg["fore"] / 1e6, "bytes": by_fore},
-        "svdcache_full_step": {"launches_per_step": n_full, "avg_ms": avg["full"], "min_ms": lo["full"],
+        "svdcache_full_step": {"launches_per_step": n_full, "avg_ms": avg["full"], "median_ms": med["full"], "min_ms": lo["full"], "timed_launches": reps["full"],
                                "GBps": by_full / avg["full"] / 1e6, "bytes": by_full},
-        "svdcache_fit_basis": {"launches_per_step": 1, "avg_ms": avg["fit"], "min_ms": lo["fit"],
+        "svdcache_fit_basis": {"launches_per_step": 1, "avg_ms": avg["fit"], "median_ms": med["fit"], "min_ms": lo["fit"], "timed_launches": reps["fit"],
                                "GBps": by_fit / avg["fit"] / 1e6, "bytes": by_fit, "TFLOPs": fit_flops / avg["fit"] / 1e9,
                                "mfma_frac": fit_flops / avg["fit"] / 1e9 / MFMA_BF16_PEAK_TF,
                                "sketch_width": l, "power_iters": q, "products_with_F": passes},
@@ -245,20 +323,25 @@ def main():
         dom_kernel = dom_kernel.replace("mfma", "general")
     ach = kernels[dom]["GBps"]
     roofline = {"kernel": dom_kernel, "entry_point": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((wl.name, k, bool(args.fast), dom_kernel)) if B == WORKLOADS[wl.name].B else None,
+                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                "traffic": traffic_from_profile(dom_kernel) if (wl.name, k, bool(args.fast), B) == ("flux57", 32, False, 57) else None,
+                "traffic_source": "profiles/flux57_k32_hbm_traffic.md (rocprofv3 FETCH_SIZE + WRITE_SIZE of this command, recorded earlier; not measured by this run)",
                 "avg_launch_ms": kernels[dom]["avg_ms"], "algorithmic_bytes_per_launch": kernels[dom]["bytes"]}
 
-    # ---- empirical ceiling: a plain device-to-device copy of one feature tensor (read + write bytes / time) ----
-    Fh.copy_(R)
+    # ---- empirical ceiling: this repository's plain copy kernel (one 16-byte load + store per lane) over one feature
+    # tensor (read + write bytes / time; 3.2 GB moved at the default workload) -----------------------------------------
+    from paper_2601_07396_amd import probes
+    probes.copy(Fh, R)
     torch.cuda.synchronize()
     ca, cb = ev(), ev()
     ca.record()
     for _ in range(10):
-        Fh.copy_(R)
+        probes.copy(Fh, R)
     cb.record()
     torch.cuda.synchronize()
     copy_gbps = 2.0 * per_tensor * 10 / ca.elapsed_time(cb) / 1e6
     roofline["empirical_copy_GBps"] = copy_gbps
+    roofline["empirical_copy_bytes"] = 2 * per_tensor
     roofline["frac_of_empirical_copy"] = ach / copy_gbps
 
     # ---- entry points beyond the three basic ones (outside the timed step; reported separately) -------
@@ -336,8 +419,23 @@ def main():
             cpu_s += time.perf_counter() - t0
             nb += 1
         one_block = (by_fit + by_full + by_fore) / B
+        # the same work on ONE host thread (first block only)
+        single_s = None
+        try:
+            import threadpoolctl
+            F0 = feats[0][0].to("cpu").double().numpy()
+            with threadpoolctl.threadpool_limits(limits=1):
+                t0 = time.perf_counter()
+                Vr, _, _ = ref_fit_basis(F0, k)
+                Rr, Sr, _ = ref_full_step(F0, Vr, None, wl.alpha, True, store)
+                ref_forecast(Sr, Vr, Rr, store)
+                single_s = time.perf_counter() - t0
+        except Exception:
+            single_s = None
         cpu = {"value": nb * one_block / cpu_s / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
                "seconds": cpu_s,
+               "single_thread": None if single_s is None else {"value": one_block / single_s / 1e9, "unit": "GB/s",
+                                                                "seconds": single_s, "sample": "1 block"},
                "sample": f"{nb} of {B} blocks ({N}x{D} {wl.dtype}, k={k}), per block one exact basis fit + one full "
                          f"step + one cached step, numpy float64; bytes counted as for one GPU fit + full step + "
                          f"cached step of those blocks"}

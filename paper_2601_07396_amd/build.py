@@ -8,6 +8,7 @@ import sys
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG_DIR, "libsvdcache.so")
+PROBES_LIB_PATH = os.path.join(PKG_DIR, "libsvdcache_probes.so")   # memory-system probes for the benchmark only
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -44,6 +45,8 @@ def build(verbose: bool = False) -> str:
     with ThreadPoolExecutor(max_workers=min(len(srcs), os.cpu_count() or 1, 8)) as pool:
         list(pool.map(lambda so: run(["hipcc", *HIPCC_FLAGS, "-c", "-o", so[1], so[0]]), zip(srcs, objs)))
     run(["hipcc", "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB_PATH, *objs])
+    probe_srcs = sorted(glob.glob(os.path.join(PKG_DIR, "csrc", "probes", "*.hip")))
+    run(["hipcc", *HIPCC_FLAGS, "-shared", "-o", PROBES_LIB_PATH, *probe_srcs])
     return LIB_PATH
 
 

@@ -3,7 +3,7 @@
 //
 //   Q <- Omega                             Omega: D x l Gaussian, l = k + p
 //   repeat q times:  Y = F Q;  Z = F^T Y;  Q <- orth(Z)       (one application of F^T F)
-//   Y = F Q;  H = Y^T Y = L L^T;  L^T = U diag(sigma) W^T     (one-sided Jacobi, fp64)
+//   Y = F Q;  H = Y^T Y = L L^T;  L = W diag(sigma) X^T       (one-sided Jacobi on L, fp64: H = W diag(sigma^2) W^T)
 //   V_k = Q W[:, :k],  sigma_k = sigma[:k]
 //
 // orth() is CholeskyQR applied twice; every l x l object (Gram matrices, Cholesky
@@ -530,16 +530,18 @@ __global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* __rest
 }
 
 // ---------------------------------------------------------------------------
-// One-sided (Hestenes) Jacobi SVD of A = L^T (l x l, float64), one workgroup per
-// block: plane rotations on column pairs until all columns are orthogonal, with
-// a round-robin ordering so that l/2 disjoint pairs are rotated concurrently.
-// Then sigma_j = ||A[:, j]||, columns sorted by descending sigma.
+// Eigenvectors of H = L L^T by a one-sided (Hestenes) Jacobi SVD of the Cholesky factor L itself (l x l, float64),
+// one workgroup per block: plane rotations on column pairs until all columns are orthogonal, with a round-robin
+// ordering so that l/2 disjoint pairs are rotated concurrently.  L J_1 J_2 ... = U diag(sigma): the final columns,
+// normalised, are the LEFT singular vectors of L, which are the eigenvectors of H -- so the rotations are never
+// accumulated (half the work and half the storage of a Jacobi on L^T that tracks its right vectors), and working on
+// the columns of L instead of those of L^T means diagonalising L^T L, which is one step of the Cholesky-LR iteration
+// closer to diagonal than H = L L^T: fewer sweeps.
 //   Lfac  in   [l x l] lower-triangular Cholesky factor of H = Y^T Y
-//   Wout  out  [l x l] row-major, column r = right singular vector of rank r
-//   sigma out  [k] leading singular values
-// acc_w: the rotations are accumulated in W (needs a second l x l matrix).  Without it (65 < l <= 128, where
-// only A fits in LDS) the vectors are recovered at the end from A_final = L^T W by back substitution with L^T,
-// in place, four threads per column; its error is eps64 x cond(L), far below the float32 output.
+//   Wout  out  [l x l] row-major, column r = eigenvector of H of rank r (descending eigenvalue)
+//   sigma out  [k] leading singular values of Y = square roots of the eigenvalues
+// Columns whose norm is at round-off level (a rank-deficient sketch, kept factorisable by the diagonal shift) are
+// still orthogonalised relative to their own norm, so the normalised set stays orthonormal.
 // ---------------------------------------------------------------------------
 // x from the lane that the DPP control word selects (both halves of the double)
 template <int CTRL>
@@ -561,14 +563,13 @@ __device__ __forceinline__ double row_sum(double x, int width) {
 
 constexpr int kJacobiThreads = 512;
 
-// NE > 0 (matrices in LDS): a lane handles exactly NE elements of a column, NE >= ceil(l / lanes per pair), so the
-// element loops unroll with a fixed trip count, their LDS loads are issued together, and the elements of A stay in
-// registers between the dot products and the rotation.  NE = 0: loops of run-time length (matrices in global memory).
-template <bool a_in_lds, bool w_in_lds, bool acc_w, int NE>   // compile-time so that LDS accesses are ds_* instructions, not flat ones
+// NE > 0 (matrix in LDS): a lane handles exactly NE elements of a column, NE >= ceil(l / lanes per pair), so the
+// element loops unroll with a fixed trip count, their LDS loads are issued together, and the elements stay in
+// registers between the dot products and the rotation.  NE = 0: loops of run-time length (matrix in global memory).
+template <bool a_in_lds, int NE>   // compile-time so that LDS accesses are ds_* instructions, not flat ones
 __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __restrict__ Lfac, double* Wout, float* sigma,
-                                                     double* gA, double* gW, int l, int k,
-                                                     const double* fro_acc, float* fro2, int max_sweeps,
-                                                     int32_t* info) {
+                                                     double* gA, int l, int k, const double* fro_acc, float* fro2,
+                                                     int max_sweeps, int32_t* info) {
   extern __shared__ double dyn_lds[];
   __shared__ double nrm[256];
   constexpr int NT = kJacobiThreads;
@@ -577,11 +578,9 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
   const double* Lf = Lfac + (int64_t)b * l * l;
   const int la = l + 1;   // column stride, padded so that concurrently rotated columns spread over the LDS banks
   double* A = a_in_lds ? dyn_lds : gA + (int64_t)b * l * la;                        // column-major
-  double* W = w_in_lds ? dyn_lds + (a_in_lds ? l * la : 0) : gW + (int64_t)b * l * la;  // column-major
   for (int idx = t; idx < l * l; idx += NT) {
-    const int c = idx / l, r = idx % l;
-    A[c * la + r] = (r <= c) ? Lf[idx] : 0.0;   // A[r][c] = L[c][r]
-    if constexpr (acc_w) W[c * la + r] = (r == c) ? 1.0 : 0.0;
+    const int r = idx / l, c = idx % l;
+    A[c * la + r] = (c <= r) ? Lf[idx] : 0.0;   // A = L
   }
   if (t == 0 && fro2) fro2[b] = (float)fro_acc[b];
   __syncthreads();
@@ -652,39 +651,13 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
           cs = cs * (1.5 - 0.5 * n2 * cs * cs);
           const double sn = cs * tt;
           if constexpr (NE > 0) {
-            double* wp = W + (int64_t)p * la;
-            double* wq = W + (int64_t)q * la;
-            double us[acc_w ? NE : 1], vs[acc_w ? NE : 1];
-            if constexpr (acc_w) {
-#pragma unroll
-              for (int e = 0; e < NE; ++e) {
-                const int r = gl + e * tp;
-                us[e] = r < l ? wp[r] : 0.0;
-                vs[e] = r < l ? wq[r] : 0.0;
-              }
-            }
 #pragma unroll
             for (int e = 0; e < NE; ++e) {
               const int r = gl + e * tp;
               if (r < l) {
                 ap[r] = cs * xs[e] - sn * ys[e];
                 aq[r] = sn * xs[e] + cs * ys[e];
-                if constexpr (acc_w) {
-                  wp[r] = cs * us[e] - sn * vs[e];
-                  wq[r] = sn * us[e] + cs * vs[e];
-                }
               }
-            }
-          } else if constexpr (acc_w) {
-            double* wp = W + (int64_t)p * la;
-            double* wq = W + (int64_t)q * la;
-            for (int r = gl; r < l; r += tp) {
-              const double x = ap[r], y = aq[r];
-              ap[r] = cs * x - sn * y;
-              aq[r] = sn * x + cs * y;
-              const double u = wp[r], v = wq[r];
-              wp[r] = cs * u - sn * v;
-              wq[r] = sn * u + cs * v;
             }
           } else {
             for (int r = gl; r < l; r += tp) {
@@ -710,31 +683,14 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
     nrm[j] = s;
   }
   __syncthreads();
-  if constexpr (!acc_w) {
-    // A_final = L^T W: solve for W column by column, in place.  Threads 4 j .. 4 j + 3 share column j: each sums
-    // every fourth term of  x_i = (a_i - sum_{m > i} L[m][i] x_m) / L[i][i],  i = l - 1 .. 0.
-    const int j = t >> 2, part = t & 3;
-    if (j < l) {
-      double* xj = A + (int64_t)j * la;
-      for (int i = l - 1; i >= 0; --i) {
-        double acc = 0.0;
-        for (int m = i + 1 + part; m < l; m += 4) acc += Lf[(int64_t)m * l + i] * xj[m];
-        acc += __shfl_xor(acc, 1, kWave);
-        acc += __shfl_xor(acc, 2, kWave);
-        // all four lanes hold the same sum and store the same value: every lane's later loads follow its own store
-        xj[i] = (xj[i] - acc) / Lf[(int64_t)i * l + i];
-      }
-    }
-    __syncthreads();
-    W = A;
-  }
   double* wo = Wout + (int64_t)b * l * l;
   for (int j = t; j < l; j += NT) {
     const double nj = nrm[j];
     int rank = 0;
     for (int i = 0; i < l; ++i) rank += (nrm[i] > nj || (nrm[i] == nj && i < j)) ? 1 : 0;
     if (rank < k) sigma[(int64_t)b * k + rank] = (float)sqrt(nj);
-    for (int i = 0; i < l; ++i) wo[(int64_t)i * l + rank] = W[(int64_t)j * la + i];
+    const double inv = nj > 0.0 ? 1.0 / sqrt(nj) : 0.0;
+    for (int i = 0; i < l; ++i) wo[(int64_t)i * l + rank] = A[(int64_t)j * la + i] * inv;
   }
 }
 
@@ -797,7 +753,7 @@ bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan)
   plan->off_G = off; off = align_up(off + B * l * l * sizeof(double), 256);
   plan->off_Gp = off; off = align_up(off + B * kGramSlices * (size_t)l * l * sizeof(double), 256);
   plan->off_M = off; off = align_up(off + B * l * l * sizeof(double), 256);
-  plan->off_W = off; off = align_up(off + 2 * B * l * (l + 1) * sizeof(double), 256);
+  plan->off_W = off; off = align_up(off + B * l * (l + 1) * sizeof(double), 256);   // Jacobi matrix when l > 138
   // ||F||_F^2 accumulators (B doubles) followed by the status words (B int32, see svdcache_fit_status_offset)
   plan->off_misc = off; off = align_up(off + B * sizeof(double), 256);
   plan->off_info = off; off = align_up(off + B * sizeof(int32_t), 256);
@@ -975,10 +931,8 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
     sumsq_kernel<T><<<dim3((s.N + rpg - 1) / rpg, B), 256, 0, st>>>(F, misc, s.N, s.D, s.ldf, s.block_stride, rpg);
   }
   const size_t mat = (size_t)l * (l + 1) * sizeof(double);
-  const bool a_in_lds = l <= 128;                   // 129 KB at l = 128
-  const bool w_in_lds = 2 * mat <= kLdsBudget;      // l <= 97
-  const size_t lds = (a_in_lds ? mat : 0) + (w_in_lds ? mat : 0);
-  double* gW = Wg + (int64_t)B * l * (l + 1);
+  const bool a_in_lds = mat <= kLdsBudget;          // l <= 138
+  const size_t lds = a_in_lds ? mat : 0;
   // elements of a column per lane, as the kernel derives them: lanes per pair = largest power of two <= 64 with
   // pairs x lanes <= threads
   const int npairs = ((l + 1) & ~1) / 2;
@@ -987,22 +941,19 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   const int ne = (l + tp - 1) / tp;
   auto launch = [&](auto kernel) -> int32_t {
     if (set_dyn_lds((const void*)kernel, lds) != SVDC_OK) return SVDC_E_HIP;
-    kernel<<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2, pl.max_sweeps, info);
+    kernel<<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, l, s.k, misc, fro2, pl.max_sweeps, info);
     return SVDC_OK;
   };
   int32_t jrc = SVDC_OK;
-  if (a_in_lds && w_in_lds) {
-    if (ne <= 1) jrc = launch(jacobi_kernel<true, true, true, 1>);
-    else if (ne <= 2) jrc = launch(jacobi_kernel<true, true, true, 2>);
-    else if (ne <= 4) jrc = launch(jacobi_kernel<true, true, true, 4>);
-    else if (ne <= 8) jrc = launch(jacobi_kernel<true, true, true, 8>);
-    else jrc = launch(jacobi_kernel<true, true, true, 16>);
-  } else if (a_in_lds) {
-    if (ne <= 8) jrc = launch(jacobi_kernel<true, false, false, 8>);
-    else jrc = launch(jacobi_kernel<true, false, false, 16>);
+  if (a_in_lds) {
+    if (ne <= 1) jrc = launch(jacobi_kernel<true, 1>);
+    else if (ne <= 2) jrc = launch(jacobi_kernel<true, 2>);
+    else if (ne <= 4) jrc = launch(jacobi_kernel<true, 4>);
+    else if (ne <= 8) jrc = launch(jacobi_kernel<true, 8>);
+    else if (ne <= 16) jrc = launch(jacobi_kernel<true, 16>);
+    else jrc = launch(jacobi_kernel<true, 0>);    // l = 129..138: 65 or more pairs leave 4 lanes per pair
   } else {
-    jacobi_kernel<false, false, true, 0><<<B, kJacobiThreads, 0, st>>>(G, M, sigma, Wg, gW, l, s.k, misc, fro2,
-                                                                       pl.max_sweeps, info);
+    jacobi_kernel<false, 0><<<B, kJacobiThreads, 0, st>>>(G, M, sigma, Wg, l, s.k, misc, fro2, pl.max_sweeps, info);
   }
   if (jrc != SVDC_OK) return jrc;
   if (rows_times_small(Q, M, V, B, s.D, l, s.k, l, st) != SVDC_OK) return SVDC_E_HIP;

@@ -196,3 +196,33 @@ def test_binding_refuses_mismatched_layouts():
     # matching layouts pass the checks and stop at the device check
     with pytest.raises(RuntimeError, match="GPU"):
         pkg.svdcache_full_step(s, F, V, None, torch.zeros(B, N, ldf)[:, :, :D], S, None, 0.5, True)
+
+
+def test_probe_library_exports_its_header():
+    """libsvdcache_probes.so (memory-system probes for the benchmark) loads and exports what its header declares."""
+    from paper_2601_07396_amd import probes
+    header = open(os.path.join(ROOT, "include", "svdcache_probes.h")).read()
+    declared = set(re.findall(r"\b(svdc_probe_\w+)\s*\(", header))
+    assert declared and declared == set(probes.EXPORTS)
+    lib = probes.load_library()
+    for name in declared:
+        assert hasattr(lib, name)
+    # bad arguments are refused on the host
+    assert lib.svdc_probe_copy(None, None, 16, None) == -1
+    assert lib.svdc_probe_burst_copy(C.c_void_p(256), C.c_void_p(512), 100, 40, None) == -1
+
+
+def test_bench_reads_its_traffic_figure_from_the_tracked_profile():
+    """roofline.traffic is not a constant in bench.py: it is the figure the tracked rocprofv3 summary holds."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    text = open(bench.TRAFFIC_PROFILE).read()
+    for kernel in ("forecast_mfma_kernel", "full_step_mfma_kernel"):
+        got = bench.traffic_from_profile(kernel)
+        assert got is not None and got > 3_000_000_000
+        row = [l for l in text.splitlines() if l.startswith("| " + kernel)][0]
+        assert row.rstrip(" |").endswith(str(got))
+    assert bench.traffic_from_profile("no_such_kernel") is None
+    assert "MEASURED_TRAFFIC" not in open(os.path.join(ROOT, "bench.py")).read()

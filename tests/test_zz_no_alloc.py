@@ -57,11 +57,11 @@ def test_static_workspace_fit_matches_the_workspace_fit_twice_in_a_row():
 
 
 def test_static_workspace_fit_refuses_what_does_not_fit():
-    F = torch.zeros(8, 4608, 3072, dtype=torch.bfloat16, device=DEV)
+    F = torch.zeros(16, 4608, 3072, dtype=torch.bfloat16, device=DEV)
     shape = pkg.make_shape(F, 32)
     assert pkg.svdcache_workspace_bytes(shape) > pkg.SVDC_STATIC_SCRATCH_BYTES
-    V = torch.zeros(8, 3072, 32, device=DEV)
-    sigma, fro2 = torch.zeros(8, 32, device=DEV), torch.zeros(8, device=DEV)
+    V = torch.zeros(16, 3072, 32, device=DEV)
+    sigma, fro2 = torch.zeros(16, 32, device=DEV), torch.zeros(16, device=DEV)
     with pytest.raises(pkg.SvdcError) as e:
         pkg.svdcache_fit_basis_static(shape, F, V, sigma, fro2)
     assert e.value.code == -6
