@@ -178,6 +178,10 @@ def main():
     ap.add_argument("--no-widened", action="store_true",
                     help="skip the short timing of the entry points beyond fit / full step / cached step")
     ap.add_argument("--fast", action="store_true", help="SVDC_FAST arithmetic (single bf16 operands)")
+    ap.add_argument("--packed-state", choices=["auto", "on", "off"], default="auto",
+                    help="cached steps read the packed copy of the state that the full step writes "
+                         "(svdcache_full_step_packed / svdcache_forecast_packed) instead of the float32 state; "
+                         "auto = from rank 33 on, where it pays")
     ap.add_argument("--probes", action="store_true",
                     help="time the memory-system probe kernels (measured ceilings of this machine) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -243,6 +247,11 @@ def main():
     R = torch.empty_like(feats[0])
     Fh = torch.empty_like(feats[0])
     S = torch.empty(B, N, k, device=dev)
+    # the state in the cached step's operand format, written by the full step (matrix-core shapes)
+    # (pays from rank 33 on: -5 % per cached step at rank 64, -11 % at rank 128; nothing at rank <= 32, where the
+    # conversion it saves is hidden anyway)
+    use_ps = args.packed_state == "on" or (args.packed_state == "auto" and k > 32)
+    Sp = pkg.alloc_packed_state(shape, dev) if (packed is not None and use_ps) else None
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     times = {"fit": [], "full": [], "fore": []}
@@ -262,7 +271,10 @@ def main():
                         times["fit"].append((a, bb))
                 a, bb = ev(), ev()
                 a.record()
-                pkg.svdcache_full_step(shape, feats[fi % n_inputs], V, packed, R, S, None, wl.alpha, t == 0)
+                if Sp is not None:
+                    pkg.svdcache_full_step_packed(shape, feats[fi % n_inputs], V, packed, R, S, None, Sp, wl.alpha, t == 0)
+                else:
+                    pkg.svdcache_full_step(shape, feats[fi % n_inputs], V, packed, R, S, None, wl.alpha, t == 0)
                 bb.record()
                 if record:
                     times["full"].append((a, bb))
@@ -270,7 +282,10 @@ def main():
             else:
                 a, bb = ev(), ev()
                 a.record()
-                pkg.svdcache_forecast(shape, S, V, packed, R, Fh)
+                if Sp is not None:
+                    pkg.svdcache_forecast_packed(shape, Sp, packed, R, Fh)
+                else:
+                    pkg.svdcache_forecast(shape, S, V, packed, R, Fh)
                 bb.record()
                 if record:
                     times["fore"].append((a, bb))
@@ -301,23 +316,27 @@ def main():
     passes = 2 * q + 1
     l = min(2 * k, N, D, 256)
     by_full, by_fore, by_fit = algorithmic_bytes(wl, passes)
-    step_bytes = by_fit + n_full * by_full + n_cached * by_fore
+    step_bytes = by_fit + n_full * by_full + n_cached * by_fore      # (the packed state copy is not counted here)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     fit_flops = B * passes * 2.0 * N * D * l
+    name_fore = "svdcache_forecast_packed" if Sp is not None else "svdcache_forecast"
+    name_full = "svdcache_full_step_packed" if Sp is not None else "svdcache_full_step"
+    if Sp is not None:
+        by_full += B * N * k * 4          # the packed copy of the new state, written next to S (same size)
+
+    def stats(key, by, launches):
+        return {"launches_per_step": launches, "avg_ms": avg[key], "median_ms": med[key], "min_ms": lo[key],
+                "timed_launches": reps[key], "GBps": by / avg[key] / 1e6, "bytes": by}
     kernels = {
-        "svdcache_forecast": {"launches_per_step": n_cached, "avg_ms": avg["fore"], "median_ms": med["fore"], "min_ms": lo["fore"], "timed_launches": reps["fore"],
-                              "GBps": by_fore / avg["fore"] / 1e6, "bytes": by_fore},
-        "svdcache_full_step": {"launches_per_step": n_full, "avg_ms": avg["full"], "median_ms": med["full"], "min_ms": lo["full"], "timed_launches": reps["full"],
-                               "GBps": by_full / avg["full"] / 1e6, "bytes": by_full},
-        "svdcache_fit_basis": {"launches_per_step": 1, "avg_ms": avg["fit"], "median_ms": med["fit"], "min_ms": lo["fit"], "timed_launches": reps["fit"],
-                               "GBps": by_fit / avg["fit"] / 1e6, "bytes": by_fit, "TFLOPs": fit_flops / avg["fit"] / 1e9,
+        name_fore: stats("fore", by_fore, n_cached),
+        name_full: stats("full", by_full, n_full),
+        "svdcache_fit_basis": {**stats("fit", by_fit, 1), "TFLOPs": fit_flops / avg["fit"] / 1e9,
                                "mfma_frac": fit_flops / avg["fit"] / 1e9 / MFMA_BF16_PEAK_TF,
                                "sketch_width": l, "power_iters": q, "products_with_F": passes},
     }
-    share = {"svdcache_forecast": n_cached * avg["fore"], "svdcache_full_step": n_full * avg["full"],
-             "svdcache_fit_basis": avg["fit"]}
+    share = {name_fore: n_cached * avg["fore"], name_full: n_full * avg["full"], "svdcache_fit_basis": avg["fit"]}
     dom = max(share, key=share.get)
-    dom_kernel = {"svdcache_forecast": "forecast_mfma_kernel", "svdcache_full_step": "full_step_mfma_kernel",
+    dom_kernel = {name_fore: "forecast_mfma_kernel", name_full: "full_step_mfma_kernel",
                   "svdcache_fit_basis": "fit (several kernels)"}[dom]
     if packed is None:
         dom_kernel = dom_kernel.replace("mfma", "general")

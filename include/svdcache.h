@@ -10,6 +10,8 @@
  *   svdcache_full_step   full-compute step: C = F V_k, R = F - C V_k^T,
  *                        EMA update of the coefficient state (Eq. 8-11)
  *   svdcache_forecast    cached step: Fhat = S V_k^T + R (Sec. 3.4-3.5)
+ *                        (svdcache_full_step_packed / svdcache_forecast_packed: the same two calls with the state
+ *                        handed over in the reader's operand format)
  *
  * all batched over B independent blocks of equal shape, and around them
  *
@@ -197,6 +199,28 @@ int32_t svdcache_full_step(const svdc_shape* shape, const void* F, const float* 
  *   if the caller no longer needs R. */
 int32_t svdcache_forecast(const svdc_shape* shape, const float* S, const float* V,
                           const void* packed, const void* R, void* Fhat, void* stream);
+
+/* Coefficient state in the operand format of the matrix-core cached step (Sec. 3.4-3.5: the state that is read at
+ * every cached step changes only at full steps, so it is laid out for the reader once, by the writer).  The packed
+ * state is an opaque caller-owned buffer of svdcache_packed_state_bytes(shape) bytes, 256-byte aligned: bf16 high
+ * and low parts of S (about 16 significant bits, the same values the cached step forms from float32 S), tiled per
+ * 16 token rows.  It is a COPY for the cached step: S [B,N,k] float32 stays the state of record (the EMA update
+ * reads and writes it).
+ *
+ * svdcache_packed_state_bytes   0 when the shape has no matrix-core path (then there is no packed state)
+ * svdcache_pack_state           S_packed <- S, for a state that did not come from svdcache_full_step_packed
+ * svdcache_full_step_packed     svdcache_full_step that also writes the packed copy of the NEW state S (same
+ *                               arguments otherwise; `packed` must be given; SVDC_E_SHAPE without a matrix-core path)
+ * svdcache_forecast_packed      svdcache_forecast reading the packed state: Fhat = S V^T + R, bit for bit the result
+ *                               of svdcache_forecast on the float32 state it was packed from */
+size_t svdcache_packed_state_bytes(const svdc_shape* shape);
+int32_t svdcache_pack_state(const svdc_shape* shape, const float* S, void* S_packed, size_t S_packed_bytes,
+                            void* stream);
+int32_t svdcache_full_step_packed(const svdc_shape* shape, const void* F, const float* V, const void* packed,
+                                  void* R, float* S, float* C, void* S_packed, size_t S_packed_bytes, float alpha,
+                                  int32_t init, void* stream);
+int32_t svdcache_forecast_packed(const svdc_shape* shape, const void* S_packed, const void* packed, const void* R,
+                                 void* Fhat, void* stream);
 
 /* Rank selection by retained energy (Sec. 3.2, Eq. 6; threshold tau about 0.85 in Sec. 4.5):
  * per block the smallest k* <= k with  sum_{i <= k*} sigma_i^2  >=  tau * fro2,  where fro2 = ||F||_F^2 is the

@@ -13,6 +13,8 @@ from .binding import (
     svdcache_has_mfma_path, svdcache_fit_basis, svdcache_fit_basis_static, SVDC_STATIC_SCRATCH_BYTES,
     svdcache_pack_basis, svdcache_full_step, svdcache_forecast,
     svdcache_full_step_residual_ema,
+    svdcache_packed_state_bytes, svdcache_pack_state, svdcache_full_step_packed, svdcache_forecast_packed,
+    alloc_packed_state,
     svdcache_select_rank, svdcache_truncate_basis, svdcache_extrapolation_weights, svdcache_forecast_combine,
     svdcache_basis_overlap, svdcache_rebase_state, svdcache_basis_similarity,
     make_shape, fit_basis, fit_basis_for_energy, pack_basis, save_basis, load_basis,
@@ -24,7 +26,8 @@ __all__ = [
     "svdcache_fit_status_offset", "SVDC_FIT_JACOBI_CAPPED", "SVDC_FIT_RANK_DEFICIENT", "svdcache_packed_basis_bytes",
     "svdcache_has_mfma_path", "svdcache_fit_basis", "svdcache_fit_basis_static", "SVDC_STATIC_SCRATCH_BYTES",
     "svdcache_pack_basis", "svdcache_full_step",
-    "svdcache_forecast", "svdcache_full_step_residual_ema", "svdcache_select_rank", "svdcache_truncate_basis", "svdcache_extrapolation_weights",
+    "svdcache_forecast", "svdcache_full_step_residual_ema", "svdcache_packed_state_bytes", "svdcache_pack_state",
+    "svdcache_full_step_packed", "svdcache_forecast_packed", "alloc_packed_state", "svdcache_select_rank", "svdcache_truncate_basis", "svdcache_extrapolation_weights",
     "svdcache_forecast_combine", "svdcache_basis_overlap", "svdcache_rebase_state", "svdcache_basis_similarity",
     "make_shape", "fit_basis", "fit_basis_for_energy", "pack_basis", "save_basis", "load_basis",
 ]

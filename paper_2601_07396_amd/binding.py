@@ -52,6 +52,13 @@ EXPORTS = {
                                                     C.c_int32, C.c_void_p]),
     "svdcache_forecast": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p]),
+    "svdcache_packed_state_bytes": (C.c_size_t, [C.POINTER(Shape)]),
+    "svdcache_pack_state": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "svdcache_full_step_packed": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_float, C.c_int32,
+                                              C.c_void_p]),
+    "svdcache_forecast_packed": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_void_p]),
     "svdcache_select_rank": (C.c_int32, [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p,
                                          C.c_void_p, C.c_void_p]),
     "svdcache_truncate_basis": (C.c_int32, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -267,6 +274,52 @@ def svdcache_forecast(shape: Shape, S, V, packed, R, Fhat):
     _check(rc, "svdcache_forecast")
 
 
+def svdcache_packed_state_bytes(shape: Shape) -> int:
+    return load_library().svdcache_packed_state_bytes(C.byref(shape))
+
+
+def _check_packed_state(shape: Shape, S_packed):
+    need = svdcache_packed_state_bytes(shape)
+    if need == 0 or not S_packed.is_contiguous() or S_packed.numel() * S_packed.element_size() < need:
+        raise ValueError(f"S_packed: {S_packed.numel() * S_packed.element_size()} bytes, this shape needs {need}")
+
+
+def svdcache_pack_state(shape: Shape, S, S_packed):
+    _dense_f32(shape.B * shape.N * shape.k, "[B, N, k]", S=S)
+    _check_packed_state(shape, S_packed)
+    _need_gpu(S, S_packed)
+    rc = load_library().svdcache_pack_state(C.byref(shape), _ptr(S), _ptr(S_packed),
+                                            S_packed.numel() * S_packed.element_size(), _stream())
+    _check(rc, "svdcache_pack_state")
+
+
+def svdcache_full_step_packed(shape: Shape, F, V, packed, R, S, Cout, S_packed, alpha: float, init: bool):
+    if packed is None:
+        raise ValueError("packed: the packed-state full step needs the packed basis")
+    _check_step_args(shape, V, packed, {"S": S, "C": Cout}, {"F": F, "R": R})
+    _check_packed_state(shape, S_packed)
+    _need_gpu(F, V, packed, R, S, Cout, S_packed)
+    rc = load_library().svdcache_full_step_packed(C.byref(shape), _ptr(F), _ptr(V), _ptr(packed), _ptr(R), _ptr(S),
+                                                  _ptr(Cout), _ptr(S_packed),
+                                                  S_packed.numel() * S_packed.element_size(), float(alpha),
+                                                  int(bool(init)), _stream())
+    _check(rc, "svdcache_full_step_packed")
+
+
+def svdcache_forecast_packed(shape: Shape, S_packed, packed, R, Fhat):
+    if packed is None:
+        raise ValueError("packed: the packed-state cached step needs the packed basis")
+    _like_features(shape, R=R, Fhat=Fhat)
+    _check_packed_state(shape, S_packed)
+    need = svdcache_packed_basis_bytes(shape)
+    if need == 0 or packed.numel() * packed.element_size() < need:
+        raise ValueError("packed: too small for this shape")
+    _need_gpu(S_packed, packed, R, Fhat)
+    rc = load_library().svdcache_forecast_packed(C.byref(shape), _ptr(S_packed), _ptr(packed), _ptr(R), _ptr(Fhat),
+                                                 _stream())
+    _check(rc, "svdcache_forecast_packed")
+
+
 def svdcache_select_rank(sigma, fro2, tau: float, k_star, reached=None):
     """k_star [B] int32 (and reached [B] int32, optional) from sigma [B,k] float32 and fro2 [B] float32."""
     _need_gpu(sigma, fro2, k_star, reached)
@@ -392,6 +445,12 @@ def load_basis(path: str, device="cuda:0"):
     if V.dim() != 3 or sigma.shape != (V.shape[0], V.shape[2]):
         raise ValueError("not a basis file: V must be [B, D, k] and sigma [B, k]")
     return V, sigma, fro2
+
+
+def alloc_packed_state(shape: Shape, device):
+    """Buffer for the packed coefficient state, or None when the shape has no matrix-core path."""
+    n = svdcache_packed_state_bytes(shape)
+    return torch.empty(n, device=device, dtype=torch.uint8) if n else None
 
 
 def pack_basis(shape: Shape, V: torch.Tensor):

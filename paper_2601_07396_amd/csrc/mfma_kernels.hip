@@ -109,6 +109,37 @@ __device__ __forceinline__ void split_operand(const float (&c)[8], u32x4* hi, u3
               pack_bf16(rem[6], rem[7])};
 }
 
+// ---------------------------------------------------------------------------
+// Packed coefficient state: S [B, N, k] float32 as the operand words of the cached step.  Per block, 16-row tile and
+// group kt of 32 coefficients two words of 64 lanes x 16 bytes (bf16 high part, then low part) of -S:
+//   lane (r, g), e  ->  -S[row = 16 tile + r][j = 32 kt + 16 (e / 4) + 4 g + e % 4]     (0 for row >= N, j >= k)
+// word index ((b ntile + tile) KT2 + kt) 2 + part.  The full step writes the same words next to S when asked.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_state_kernel(const float* __restrict__ S, u32x4* __restrict__ Sp, int N,
+                                                         int k, int KT2, int64_t words_per_block) {
+  const int b = blockIdx.y;
+  const int64_t w = (int64_t)blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);   // (tile, kt)
+  if (w >= words_per_block) return;
+  const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  const int kt = (int)(w % KT2);
+  const int64_t tile = w / KT2;
+  const int64_t row = tile * 16 + r;
+  float c8[8];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int j = 32 * kt + 16 * t + 4 * g;
+    f32x4 x = {0.f, 0.f, 0.f, 0.f};
+    if (row < N && j < k) x = *reinterpret_cast<const f32x4*>(S + ((int64_t)b * N + row) * k + j);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) c8[4 * t + i] = -x[i];
+  }
+  u32x4 hi, lo;
+  split_operand(c8, &hi, &lo);
+  u32x4* out = Sp + ((int64_t)b * words_per_block + w) * 2 * 64 + lane;
+  out[0] = hi;
+  out[64] = lo;
+}
+
 // Eight consecutive channels of one token as they sit in memory and in registers.  bf16: 16 bytes,
 // exact as an MFMA operand.  float32: 32 bytes; as an MFMA operand it is split into bf16 high + low parts.
 template <typename T>
@@ -154,11 +185,14 @@ struct RowPiece<float> {
 // in them, Sec. 5.3) and a tensor X may be added to the result (Out = C_hat V^T + R + X).
 // ---------------------------------------------------------------------------
 
-template <typename T, int NCW, int KT2, bool SPLIT, int PD, bool EXT>
+// PS: the coefficient state comes as packed operand words (packed_state_kernel / the full step's second state
+// output) instead of float32 rows: nothing is converted per tile.
+template <typename T, int NCW, int KT2, bool SPLIT, int PD, bool EXT, bool PS = false>
 __global__ __launch_bounds__(256) void forecast_mfma_kernel(const CoefStates cs, const uint16_t* __restrict__ P,
                                                             const T* R, const T* X, T* Fh, int N, int D, int k,
                                                             int64_t ldf, int64_t bstride, int NS,
                                                             int groups_per_block, int tiles_per_group) {
+  static_assert(!(PS && EXT), "the packed state serves the plain cached step");
   const int slab = blockIdx.x % NS;
   const int rgb = blockIdx.x / NS;
   const int b = rgb / groups_per_block, rg = rgb % groups_per_block;
@@ -173,23 +207,32 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const CoefStates cs,
   // EXT: the coefficient forecast is sum_m w_m S_m over up to kMaxStates stored states, and a tensor X
   // (nullable) is added to the result; otherwise the single state cs.s[0] with weight one.
   constexpr int MS = EXT ? kMaxStates : 1;
+  const int ntile_block = (N + 15) / 16;
   const bool has_x = EXT && X != nullptr;
   const T* xbase = has_x ? X + (int64_t)b * bstride + 32 * cg0 + 8 * g : nullptr;
   const int64_t soff = (int64_t)b * N * k;
   // Row tiles rg, rg + groups_per_block, ...: the workgroups of a block advance through its rows side by
   // side, which keeps the addresses in flight close together (measurably kinder to HBM than giving each
   // workgroup a contiguous range of tiles).
-  const int ntile_block = (N + 15) / 16;
   const int ntiles = min(tiles_per_group, (ntile_block - rg + groups_per_block - 1) / groups_per_block);
 
   RowPiece<T> rin[PD][NCW];
   RowPiece<T> xin[PD][EXT ? NCW : 1];
-  f32x4 sraw[PD][MS][KT2][2];
+  f32x4 sraw[PD][PS ? 1 : MS][PS ? 1 : KT2][2];
+  u32x4 spk[PD][PS ? KT2 : 1][2];   // packed state: high and low operand words
+  const u32x4* spbase = PS ? reinterpret_cast<const u32x4*>(cs.s[0]) + (int64_t)b * ntile_block * KT2 * 2 * 64 + lane : nullptr;
   // lane (r, g) needs S[row][j = 32 kt + 16 t + 4 g + i], i = 0..3 (zero beyond k)
   auto load_tile = [&](int tile, int u) {
     const int row = min(tile * 16 + r, N - 1);
+    if constexpr (PS) {
 #pragma unroll
-    for (int ms = 0; ms < MS; ++ms) {
+      for (int kt = 0; kt < KT2; ++kt)
+#pragma unroll
+        for (int part = 0; part < (SPLIT ? 2 : 1); ++part)
+          spk[u][kt][part] = spbase[(((int64_t)tile * KT2 + kt) * 2 + part) * 64];
+    }
+#pragma unroll
+    for (int ms = 0; ms < (PS ? 0 : MS); ++ms) {
       if (ms >= cs.m) break;
 #pragma unroll
       for (int kt = 0; kt < KT2; ++kt)
@@ -232,7 +275,12 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const CoefStates cs,
       const int tile = rg + (it + u) * groups_per_block;
       u32x4 shi[KT2], slo[KT2];
 #pragma unroll
-      for (int kt = 0; kt < KT2; ++kt) {
+      for (int kt = 0; kt < (PS ? KT2 : 0); ++kt) {
+        shi[kt] = spk[u][kt][0];
+        if (SPLIT) slo[kt] = spk[u][kt][1];
+      }
+#pragma unroll
+      for (int kt = 0; kt < (PS ? 0 : KT2); ++kt) {
         float c8[8];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
@@ -309,7 +357,7 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
                                                              T* R, const T* Rp, float alpha_r, float* S, float* C,
                                                              int N, int k, int64_t ldf, int64_t bstride,
                                                              float alpha, int init, int tiles_per_block,
-                                                             int total) {
+                                                             int total, u32x4* Sp) {
   constexpr int KP = KT2 * 32, KT = KT2 * 2, D = CH * 128;
   constexpr int M = CH * KT;   // basis operand items per wave and phase (a high + a low 16-byte word per lane each)
   constexpr int RA = RT + LT;  // row tiles per workgroup tile: RT in registers, LT in LDS
@@ -455,17 +503,22 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
       }
     __syncthreads();   // the next tile reuses `part`
 
-    // EMA update (Eq. 11, alpha = 1 - beta) and coefficient output, one wave per row tile
+    // EMA update (Eq. 11, alpha = 1 - beta) and coefficient output, one wave per row tile.  Sp (nullable): the new
+    // state also leaves as the cached step's operand words (negated, bf16 high + low parts; zeros beyond N and k).
+    const int ntile_block = (N + 15) / 16;
 #pragma unroll
     for (int rt = 0; rt < RA; ++rt) {
       if ((rt % kWavesPerGroup) != wave) continue;
       const int row = row0 + 16 * rt + r;
-      if (row >= N) continue;
-      const int64_t srow = ((int64_t)b * N + row) * k;
+      const int tile16 = tile * RA + rt;
+      if (tile16 >= ntile_block) continue;
+      const int64_t srow = ((int64_t)b * N + min(row, N - 1)) * k;
+      f32x4 snew[KT];
 #pragma unroll
       for (int jt = 0; jt < KT; ++jt) {
         const int j = 16 * jt + 4 * g;
-        if (j >= k) continue;   // k is a multiple of 4: a group of four is all inside or all outside
+        snew[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (j >= k || row >= N) continue;   // k is a multiple of 4: a group of four is all inside or all outside
         const f32x4 c4 = acc[jt][rt];
         f32x4 s4 = c4;
         if (!init) {
@@ -475,6 +528,22 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
         }
         *reinterpret_cast<f32x4*>(S + srow + j) = s4;
         if (C) *reinterpret_cast<f32x4*>(C + srow + j) = c4;
+        snew[jt] = s4;
+      }
+      if (Sp) {
+#pragma unroll
+        for (int kt = 0; kt < KT2; ++kt) {
+          float c8[8];
+#pragma unroll
+          for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) c8[4 * t + i] = -snew[2 * kt + t][i];
+          u32x4 hi, lo;
+          split_operand(c8, &hi, &lo);
+          u32x4* w = Sp + ((((int64_t)b * ntile_block + tile16) * KT2 + kt) * 2) * 64 + lane;
+          w[0] = hi;
+          w[64] = lo;
+        }
       }
     }
 
@@ -576,7 +645,7 @@ int32_t launch_pack_basis(const svdc_shape& s, const float* V, void* packed, hip
 
 namespace {
 
-template <typename T, int NCW, int KT2, bool SPLIT, int PD, bool EXT>
+template <typename T, int NCW, int KT2, bool SPLIT, int PD, bool EXT, bool PS = false>
 int32_t forecast_launch(const svdc_shape& s, const CoefStates& cs, const void* packed, const void* R, const void* X,
                         void* Fhat, hipStream_t st) {
   const int NS = s.D / (128 * NCW);
@@ -595,14 +664,14 @@ int32_t forecast_launch(const svdc_shape& s, const CoefStates& cs, const void* p
   const int gpb = (ntile + tpg - 1) / tpg;
   const int64_t grid = (int64_t)NS * gpb * s.B;
   if (grid > 0x7fffffff) return SVDC_E_SHAPE;
-  forecast_mfma_kernel<T, NCW, KT2, SPLIT, PD, EXT><<<(unsigned)grid, 256, 0, st>>>(
+  forecast_mfma_kernel<T, NCW, KT2, SPLIT, PD, EXT, PS><<<(unsigned)grid, 256, 0, st>>>(
       cs, (const uint16_t*)packed, (const T*)R, (const T*)X, (T*)Fhat, s.N, s.D, s.k, s.ldf, s.block_stride, NS, gpb,
       tpg);
   return launch_status();
 }
 
 // widest slab per wave (NCW chunks) that divides D / 128 and keeps the basis operands in registers
-template <typename T, int KT2, bool SPLIT, int PD, bool EXT>
+template <typename T, int KT2, bool SPLIT, int PD, bool EXT, bool PS = false>
 int32_t forecast_by_width(const svdc_shape& s, const CoefStates& cs, const void* packed, const void* R, const void* X,
                           void* Fhat, hipStream_t st) {
   // registers: basis operands 8 (16 with the low parts) per chunk and 32 coefficients, row pieces 4 (8 for f32)
@@ -612,21 +681,21 @@ int32_t forecast_by_width(const svdc_shape& s, const CoefStates& cs, const void*
       kBudget >= 12 ? 12 : (kBudget >= 6 ? 6 : (kBudget >= 4 ? 4 : (kBudget >= 3 ? 3 : ((kBudget >= 2 || !EXT) ? 2 : 1))));
   const int m = s.D / 128;
   if constexpr (kMax >= 12) {
-    if (m % 12 == 0) return forecast_launch<T, 12, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
+    if (m % 12 == 0) return forecast_launch<T, 12, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
   }
   if constexpr (kMax >= 6) {
-    if (m % 6 == 0) return forecast_launch<T, 6, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
+    if (m % 6 == 0) return forecast_launch<T, 6, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
   }
   if constexpr (kMax >= 4) {
-    if (m % 4 == 0) return forecast_launch<T, 4, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
+    if (m % 4 == 0) return forecast_launch<T, 4, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
   }
   if constexpr (kMax >= 3) {
-    if (m % 3 == 0) return forecast_launch<T, 3, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
+    if (m % 3 == 0) return forecast_launch<T, 3, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
   }
   if constexpr (kMax >= 2) {
-    if (m % 2 == 0) return forecast_launch<T, 2, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
+    if (m % 2 == 0) return forecast_launch<T, 2, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
   }
-  return forecast_launch<T, 1, KT2, SPLIT, PD, EXT>(s, cs, packed, R, X, Fhat, st);
+  return forecast_launch<T, 1, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
 }
 
 template <typename T, int CH, int RT, int KT2, bool SPLIT, int RD, bool REMA, int LT = 0>
@@ -638,7 +707,7 @@ int32_t full_step_launch(const svdc_shape& s, const void* F, const void* packed,
   const int grid = (int)std::min<int64_t>(total, num_compute_units());
   full_step_mfma_kernel<T, CH, RT, KT2, SPLIT, SPLIT, RD, REMA, LT><<<grid, 256, 0, st>>>(
       (const T*)F, (const uint16_t*)packed, (T*)R, (const T*)re.prev, re.alpha_r, S, C, s.N, s.k, s.ldf,
-      s.block_stride, alpha, init, tiles, (int)total);
+      s.block_stride, alpha, init, tiles, (int)total, (u32x4*)re.packed_state);
   return launch_status();
 }
 
@@ -732,25 +801,25 @@ int32_t launch_full_step_mfma(const svdc_shape& s, const void* F, const void* pa
 
 namespace {
 
-template <bool EXT>
+template <bool EXT, bool PS = false>
 int32_t forecast_dispatch(const svdc_shape& s, const CoefStates& cs, const void* packed, const void* R,
                           const void* X, void* Fhat, hipStream_t st) {
   const int kp = padded_rank(s.k);
   if (s.dtype == SVDC_F32) {
-    if (kp == 32) return forecast_by_width<float, 1, true, 1, EXT>(s, cs, packed, R, X, Fhat, st);
-    if (kp == 64) return forecast_by_width<float, 2, true, 2, EXT>(s, cs, packed, R, X, Fhat, st);
-    return forecast_by_width<float, 4, true, 2, EXT>(s, cs, packed, R, X, Fhat, st);
+    if (kp == 32) return forecast_by_width<float, 1, true, 1, EXT, PS>(s, cs, packed, R, X, Fhat, st);
+    if (kp == 64) return forecast_by_width<float, 2, true, 2, EXT, PS>(s, cs, packed, R, X, Fhat, st);
+    return forecast_by_width<float, 4, true, 2, EXT, PS>(s, cs, packed, R, X, Fhat, st);
   }
   if (s.precision == SVDC_PRECISE) {
-    if (kp == 32) return forecast_by_width<bf16_t, 1, true, 1, EXT>(s, cs, packed, R, X, Fhat, st);
+    if (kp == 32) return forecast_by_width<bf16_t, 1, true, 1, EXT, PS>(s, cs, packed, R, X, Fhat, st);
     // at rank 64 the matrix-core time per tile is no longer small next to its memory time: more tiles in flight
-    if (kp == 64) return forecast_by_width<bf16_t, 2, true, (EXT ? 2 : 4), EXT>(s, cs, packed, R, X, Fhat, st);
-    return forecast_by_width<bf16_t, 4, true, 2, EXT>(s, cs, packed, R, X, Fhat, st);
+    if (kp == 64) return forecast_by_width<bf16_t, 2, true, (EXT ? 2 : 4), EXT, PS>(s, cs, packed, R, X, Fhat, st);
+    return forecast_by_width<bf16_t, 4, true, 2, EXT, PS>(s, cs, packed, R, X, Fhat, st);
   }
   // at rank <= 32 the split-operand kernel is the faster one (its matrix-core work is hidden anyway)
-  if (kp == 32) return forecast_by_width<bf16_t, 1, true, 1, EXT>(s, cs, packed, R, X, Fhat, st);
-  if (kp == 64) return forecast_by_width<bf16_t, 2, false, 2, EXT>(s, cs, packed, R, X, Fhat, st);
-  return forecast_by_width<bf16_t, 4, false, 2, EXT>(s, cs, packed, R, X, Fhat, st);
+  if (kp == 32) return forecast_by_width<bf16_t, 1, true, 1, EXT, PS>(s, cs, packed, R, X, Fhat, st);
+  if (kp == 64) return forecast_by_width<bf16_t, 2, false, 2, EXT, PS>(s, cs, packed, R, X, Fhat, st);
+  return forecast_by_width<bf16_t, 4, false, 2, EXT, PS>(s, cs, packed, R, X, Fhat, st);
 }
 
 }  // namespace
@@ -767,6 +836,27 @@ int32_t launch_forecast_mfma(const svdc_shape& s, const float* S, const void* pa
 int32_t launch_forecast_combine_mfma(const svdc_shape& s, const CoefStates& cs, const void* packed, const void* R,
                                      const void* X, void* Out, hipStream_t st) {
   return forecast_dispatch<true>(s, cs, packed, R, X, Out, st);
+}
+
+size_t mfma_packed_state_bytes(const svdc_shape& s) {
+  return (size_t)s.B * ((size_t)(s.N + 15) / 16) * (padded_rank(s.k) / 32) * 2 * 1024;
+}
+
+int32_t launch_pack_state(const svdc_shape& s, const float* S, void* Sp, hipStream_t st) {
+  const int KT2 = padded_rank(s.k) / 32;
+  const int64_t words = (int64_t)((s.N + 15) / 16) * KT2;
+  dim3 grid((unsigned)((words + kWavesPerGroup - 1) / kWavesPerGroup), s.B);
+  pack_state_kernel<<<grid, 256, 0, st>>>(S, (u32x4*)Sp, s.N, s.k, KT2, words);
+  return launch_status();
+}
+
+int32_t launch_forecast_packed_mfma(const svdc_shape& s, const void* Sp, const void* packed, const void* R,
+                                    void* Fhat, hipStream_t st) {
+  CoefStates cs{};
+  cs.s[0] = static_cast<const float*>(Sp);   // the kernel reads it as operand words
+  cs.w[0] = 1.f;
+  cs.m = 1;
+  return forecast_dispatch<false, true>(s, cs, packed, R, nullptr, Fhat, st);
 }
 
 }  // namespace svdc

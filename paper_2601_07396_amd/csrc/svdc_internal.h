@@ -24,6 +24,7 @@ struct CoefStates {
 struct ResidualEma {
   const void* prev = nullptr;
   float alpha_r = 1.f;
+  void* packed_state = nullptr;   // matrix-core full step only: second output of the new state, as operand words
 };
 int32_t launch_full_step_general(const svdc_shape& s, const void* F, const float* V, void* R, float* S,
                                  float* C, float alpha, int init, ResidualEma re, hipStream_t st);
@@ -50,6 +51,11 @@ int32_t launch_full_step_mfma(const svdc_shape& s, const void* F, const void* pa
                               float* C, float alpha, int init, ResidualEma re, hipStream_t st);
 int32_t launch_forecast_mfma(const svdc_shape& s, const float* S, const void* packed, const void* R,
                              void* Fhat, hipStream_t st);
+// Coefficient state as the cached step's operand words (bf16 high + low parts of -S, tiled per 16 rows)
+size_t mfma_packed_state_bytes(const svdc_shape& s);
+int32_t launch_pack_state(const svdc_shape& s, const float* S, void* Sp, hipStream_t st);
+int32_t launch_forecast_packed_mfma(const svdc_shape& s, const void* Sp, const void* packed, const void* R,
+                                    void* Fhat, hipStream_t st);
 int32_t launch_forecast_combine_mfma(const svdc_shape& s, const CoefStates& cs, const void* packed, const void* R,
                                      const void* X, void* Out, hipStream_t st);
 

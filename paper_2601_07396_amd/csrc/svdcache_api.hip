@@ -204,6 +204,49 @@ int32_t svdcache_forecast(const svdc_shape* shape, const float* S, const float* 
   return launch_forecast_general(*shape, cs, V, R, nullptr, Fhat, (hipStream_t)stream);
 }
 
+size_t svdcache_packed_state_bytes(const svdc_shape* shape) {
+  if (check_shape(shape) != SVDC_OK || !mfma_shape_supported(*shape)) return 0;
+  return mfma_packed_state_bytes(*shape);
+}
+
+int32_t svdcache_pack_state(const svdc_shape* shape, const float* S, void* S_packed, size_t S_packed_bytes,
+                            void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!S || !S_packed) return SVDC_E_NULL;
+  if (!mfma_shape_supported(*shape)) return SVDC_E_SHAPE;
+  if (!aligned(S, 16) || !aligned(S_packed, 256)) return SVDC_E_ALIGN;
+  if (S_packed_bytes < mfma_packed_state_bytes(*shape)) return SVDC_E_WORKSPACE;
+  return launch_pack_state(*shape, S, S_packed, (hipStream_t)stream);
+}
+
+int32_t svdcache_full_step_packed(const svdc_shape* shape, const void* F, const float* V, const void* packed, void* R,
+                                  float* S, float* C, void* S_packed, size_t S_packed_bytes, float alpha,
+                                  int32_t init, void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!F || !V || !R || !S || !packed || !S_packed) return SVDC_E_NULL;
+  if (!(alpha > 0.f && alpha <= 1.f)) return SVDC_E_PARAM;
+  if (!mfma_shape_supported(*shape)) return SVDC_E_SHAPE;
+  if (!aligned(F, 16) || !aligned(R, 16) || !aligned(V, 16) || !aligned(S, 16) || (C && !aligned(C, 16)) ||
+      !aligned(packed, 256) || !aligned(S_packed, 256))
+    return SVDC_E_ALIGN;
+  if (S_packed_bytes < mfma_packed_state_bytes(*shape)) return SVDC_E_WORKSPACE;
+  ResidualEma re;
+  re.packed_state = S_packed;
+  return launch_full_step_mfma(*shape, F, packed, R, S, C, alpha, init != 0, re, (hipStream_t)stream);
+}
+
+int32_t svdcache_forecast_packed(const svdc_shape* shape, const void* S_packed, const void* packed, const void* R,
+                                 void* Fhat, void* stream) {
+  int32_t rc = check_shape(shape);
+  if (rc != SVDC_OK) return rc;
+  if (!S_packed || !packed || !R || !Fhat) return SVDC_E_NULL;
+  if (!mfma_shape_supported(*shape)) return SVDC_E_SHAPE;
+  if (!aligned(R, 16) || !aligned(Fhat, 16) || !aligned(packed, 256) || !aligned(S_packed, 256)) return SVDC_E_ALIGN;
+  return launch_forecast_packed_mfma(*shape, S_packed, packed, R, Fhat, (hipStream_t)stream);
+}
+
 int32_t svdcache_select_rank(int32_t B, int32_t k, const float* sigma, const float* fro2, float tau,
                              int32_t* k_star, int32_t* reached, void* stream) {
   if (!sigma || !fro2 || !k_star) return SVDC_E_NULL;

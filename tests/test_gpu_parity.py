@@ -303,6 +303,50 @@ def test_mfma_inplace_and_strided(k):
                      "bf16", "Fhat in place", scale_of=to_np(F[b]), ulp_of=state[b][0])
 
 
+@pytest.mark.parametrize("dtype,B,N,D,k,mode", [
+    (torch.bfloat16, 2, 200, 256, 32, 0), (torch.bfloat16, 1, 77, 512, 8, 0), (torch.bfloat16, 3, 130, 3072, 64, 0),
+    (torch.bfloat16, 1, 145, 3072, 128, 0), (torch.bfloat16, 2, 333, 3072, 20, 1), (torch.bfloat16, 1, 90, 1024, 64, 1),
+    (torch.float32, 1, 131, 512, 32, 0), (torch.float32, 1, 70, 3072, 64, 0)])
+def test_packed_state_full_step_and_cached_step(dtype, B, N, D, k, mode):
+    """The state handed over in the cached step's operand format: svdcache_full_step_packed writes it next to the
+    float32 state, svdcache_pack_state makes it from a float32 state, svdcache_forecast_packed reads it.  Against the
+    oracle at the usual bars, and bit for bit against the float32-state calls (same arithmetic, fewer conversions)."""
+    store = "f32" if dtype == torch.float32 else "bf16"
+    Fb, V, S0 = _lowrank_problem(B, N, D, k, seed=N + 3 * k)
+    F = Fb.to(dtype)
+    Fd, Vd = F.to(DEV), V.to(DEV)
+    shape = pkg.make_shape(Fd, k, precision=mode)
+    pk = pkg.pack_basis(shape, Vd)
+    fast = mode == pkg.SVDC_FAST
+    coef = "bf16" if fast else "f32"
+    for init in (True, False):
+        Sa, Sb = S0.clone().to(DEV), S0.clone().to(DEV)
+        Ra, Rb = torch.empty_like(Fd), torch.empty_like(Fd)
+        Ca, Cb = torch.empty_like(Sa), torch.empty_like(Sa)
+        Sp = pkg.alloc_packed_state(shape, DEV)
+        Sp.fill_(0xAB)
+        pkg.svdcache_full_step(shape, Fd, Vd, pk, Ra, Sa, Ca, 0.4, init)
+        pkg.svdcache_full_step_packed(shape, Fd, Vd, pk, Rb, Sb, Cb, Sp, 0.4, init)
+        Fa, Fb2, Fc = torch.empty_like(Fd), torch.empty_like(Fd), torch.empty_like(Fd)
+        pkg.svdcache_forecast(shape, Sa, Vd, pk, Ra, Fa)
+        pkg.svdcache_forecast_packed(shape, Sp, pk, Rb, Fb2)
+        Sp2 = torch.empty_like(Sp)
+        pkg.svdcache_pack_state(shape, Sa, Sp2)
+        pkg.svdcache_forecast_packed(shape, Sp2, pk, Ra, Fc)
+        torch.cuda.synchronize()
+        assert torch.equal(Ra, Rb) and torch.equal(Sa, Sb) and torch.equal(Ca, Cb)
+        assert torch.equal(Sp, Sp2), "the full step's packed state differs from the packed float32 state"
+        assert torch.equal(Fa, Fb2) and torch.equal(Fa, Fc)
+        for b in range(B):
+            Rr, Sr, _ = ref_full_step(to_np(F[b]), to_np(V[b]), to_np(S0[b]), 0.4, init, store)
+            assert_close(to_np(Sb[b]), Sr, coef, f"S[{b}]", fast=fast)
+            assert_close(to_np(Fb2[b]), ref_forecast(Sr, to_np(V[b]), Rr, store), store, f"Fhat[{b}] from packed state",
+                         fast=fast, scale_of=to_np(F[b]), ulp_of=Rr)
+    # a shape without a matrix-core path has no packed state
+    odd = pkg.make_shape(torch.zeros(1, 16, 72, device=DEV), 4)
+    assert pkg.svdcache_packed_state_bytes(odd) == 0
+
+
 # ---------------------------------------------------------------------------------------------
 # basis fit with the products on the matrix cores (bf16 features, D % 128 == 0, k + p <= 128)
 # ---------------------------------------------------------------------------------------------
@@ -568,7 +612,15 @@ def _sampled_row_parity(wl, B, blocks_to_check, n_rows, precision=0, fit_check_b
     S0 = S.clone()
     pkg.svdcache_full_step(shape, feats[1], Vgen, pk, R, S, Cc, wl.alpha, False)
     pkg.svdcache_forecast(shape, S, Vgen, pk, R, Fh)
+    # the same two calls with the state handed over in packed form: identical results at full size
+    Sp = pkg.alloc_packed_state(shape, DEV)
+    S2, R2, Fh2 = S0.clone(), torch.empty_like(R), torch.empty_like(R)
+    pkg.svdcache_full_step_packed(shape, feats[1], Vgen, pk, R2, S2, None, Sp, wl.alpha, False)
+    pkg.svdcache_forecast_packed(shape, Sp, pk, R2, Fh2)
     torch.cuda.synchronize()
+    for b in blocks_to_check:
+        assert torch.equal(S2[b], S[b]) and torch.equal(R2[b], R[b]) and torch.equal(Fh2[b], Fh[b])
+    del S2, R2, Fh2, Sp
     g = torch.Generator().manual_seed(wl.config_id)
     fast = precision != 0
     for b in blocks_to_check:
