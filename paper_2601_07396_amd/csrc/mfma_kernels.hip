@@ -187,7 +187,9 @@ struct RowPiece<float> {
 
 // PS: the coefficient state comes as packed operand words (packed_state_kernel / the full step's second state
 // output) instead of float32 rows: nothing is converted per tile.
-template <typename T, int NCW, int KT2, bool SPLIT, int PD, bool EXT, bool PS = false>
+// MSX, HX (EXT only): registers are held for MSX coefficient states per tile in flight, and for the added tensor only
+// with HX -- a forecaster of two states that adds nothing should not pay for four states and a second row tile.
+template <typename T, int NCW, int KT2, bool SPLIT, int PD, bool EXT, bool PS = false, int MSX = kMaxStates, bool HX = true>
 __global__ __launch_bounds__(256) void forecast_mfma_kernel(const CoefStates cs, const uint16_t* __restrict__ P,
                                                             const T* R, const T* X, T* Fh, int N, int D, int k,
                                                             int64_t ldf, int64_t bstride, int NS,
@@ -206,9 +208,9 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const CoefStates cs,
   T* obase = Fh + (int64_t)b * bstride + 32 * cg0 + 8 * g;
   // EXT: the coefficient forecast is sum_m w_m S_m over up to kMaxStates stored states, and a tensor X
   // (nullable) is added to the result; otherwise the single state cs.s[0] with weight one.
-  constexpr int MS = EXT ? kMaxStates : 1;
+  constexpr int MS = EXT ? MSX : 1;
   const int ntile_block = (N + 15) / 16;
-  const bool has_x = EXT && X != nullptr;
+  const bool has_x = EXT && HX && X != nullptr;
   const T* xbase = has_x ? X + (int64_t)b * bstride + 32 * cg0 + 8 * g : nullptr;
   const int64_t soff = (int64_t)b * N * k;
   // Row tiles rg, rg + groups_per_block, ...: the workgroups of a block advance through its rows side by
@@ -217,7 +219,7 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const CoefStates cs,
   const int ntiles = min(tiles_per_group, (ntile_block - rg + groups_per_block - 1) / groups_per_block);
 
   RowPiece<T> rin[PD][NCW];
-  RowPiece<T> xin[PD][EXT ? NCW : 1];
+  RowPiece<T> xin[PD][(EXT && HX) ? NCW : 1];
   f32x4 sraw[PD][PS ? 1 : MS][PS ? 1 : KT2][2];
   u32x4 spk[PD][PS ? KT2 : 1][2];   // packed state: high and low operand words
   const u32x4* spbase = PS ? reinterpret_cast<const u32x4*>(cs.s[0]) + (int64_t)b * ntile_block * KT2 * 2 * 64 + lane : nullptr;
@@ -245,7 +247,7 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const CoefStates cs,
     }
 #pragma unroll
     for (int c = 0; c < NCW; ++c) rin[u][c].load(rbase + (int64_t)row * ldf + 32 * c);
-    if constexpr (EXT) {
+    if constexpr (EXT && HX) {
       if (has_x) {
 #pragma unroll
         for (int c = 0; c < NCW; ++c) xin[u][c].load(xbase + (int64_t)row * ldf + 32 * c);
@@ -305,7 +307,7 @@ __global__ __launch_bounds__(256) void forecast_mfma_kernel(const CoefStates cs,
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           f32x4 acc = rin[u][c].half(t);
-          if constexpr (EXT) {
+          if constexpr (EXT && HX) {
             if (has_x) {
               const f32x4 xa = xin[u][c].half(t);
               acc[0] += xa[0]; acc[1] += xa[1]; acc[2] += xa[2]; acc[3] += xa[3];
@@ -664,9 +666,22 @@ int32_t forecast_launch(const svdc_shape& s, const CoefStates& cs, const void* p
   const int gpb = (ntile + tpg - 1) / tpg;
   const int64_t grid = (int64_t)NS * gpb * s.B;
   if (grid > 0x7fffffff) return SVDC_E_SHAPE;
-  forecast_mfma_kernel<T, NCW, KT2, SPLIT, PD, EXT, PS><<<(unsigned)grid, 256, 0, st>>>(
-      cs, (const uint16_t*)packed, (const T*)R, (const T*)X, (T*)Fhat, s.N, s.D, s.k, s.ldf, s.block_stride, NS, gpb,
-      tpg);
+  auto launch = [&](auto kernel) {
+    kernel<<<(unsigned)grid, 256, 0, st>>>(cs, (const uint16_t*)packed, (const T*)R, (const T*)X, (T*)Fhat, s.N, s.D,
+                                           s.k, s.ldf, s.block_stride, NS, gpb, tpg);
+  };
+  if constexpr (EXT) {
+    // registers for two or four states, with or without the added tensor
+    if (cs.m <= 2) {
+      if (X) launch(forecast_mfma_kernel<T, NCW, KT2, SPLIT, PD, true, false, 2, true>);
+      else launch(forecast_mfma_kernel<T, NCW, KT2, SPLIT, PD, true, false, 2, false>);
+    } else {
+      if (X) launch(forecast_mfma_kernel<T, NCW, KT2, SPLIT, PD, true, false, kMaxStates, true>);
+      else launch(forecast_mfma_kernel<T, NCW, KT2, SPLIT, PD, true, false, kMaxStates, false>);
+    }
+  } else {
+    launch(forecast_mfma_kernel<T, NCW, KT2, SPLIT, PD, false, PS>);
+  }
   return launch_status();
 }
 
