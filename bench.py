@@ -133,19 +133,13 @@ def run_probes():
     report("copy: 16 B per lane, one piece per thread, 1.6 GB in + 1.6 GB out", timed(lambda: probes.copy(b, a)), 2 * nbytes)
     report("read-only stream, 1.6 GB", timed(lambda: probes.read(a, sink)), nbytes)
     report("torch Tensor.copy_ (runtime's device-to-device copy), 1.6 GB in + 1.6 GB out", timed(lambda: b.copy_(a)), 2 * nbytes)
-    for tpg, inter in ((1, 0), (12, 0), (12, 1), (16, 1)):
-        report(f"tile copy, cached-step skeleton: {tpg} tile(s) per workgroup, {'interleaved' if inter else 'contiguous'}",
-               timed(lambda: probes.tile_copy(b, a, rows, tpg, inter)), 2 * nbytes)
+    for tpg, inter, gpc in ((1, 0, 0), (12, 0, 1), (12, 1, 1), (6, 1, 1), (12, 1, 2), (12, 1, 0)):
+        report(f"tile copy, cached-step skeleton: {tpg} tile(s) per workgroup, {'interleaved' if inter else 'contiguous'}, "
+               f"{str(gpc) + ' workgroup(s)' if gpc else 'any number of workgroups'} per compute unit",
+               timed(lambda: probes.tile_copy(b, a, rows, tpg, inter, gpc)), 2 * nbytes)
     for tr in (16, 32, 48):
         report(f"burst copy, full-step skeleton: persistent workgroups, {tr}-row tiles in registers",
                timed(lambda: probes.burst_copy(b, a, rows, tr)), 2 * nbytes)
-    cus = torch.cuda.get_device_properties(dev).multi_processor_count
-    for window, what in ((786432, "786 KB (packed basis of one block, rank 32)"), (1572864, "1.5 MB (rank 64)"),
-                         (196608, "192 KB")):
-        reps_in = max(1, int(4.4e9 / (window * cus)))
-        report(f"L2 -> compute units: {cus} workgroups each re-reading one {what} window {reps_in} times",
-               timed(lambda: probes.l2_stream(a, window, reps_in, cus, sink), reps=5), window * reps_in * cus,
-               note="bytes delivered to the compute units, not HBM traffic")
     # re-read of what the previous kernel just read: Infinity Cache (256 MB) and L2
     flush = a[nbytes // 2:]                  # another 0.8 GB, read in between to evict
     for mb in (64, 128, 192, 256, 512):

@@ -4,8 +4,7 @@
  * Not part of the SVD-Cache computation: these kernels move bytes and compute nothing.  The benchmark times them
  * (python bench.py --probes) to put measured ceilings next to the published 8 TB/s when it reports what fraction
  * of the memory roofline the step kernels reach: what a plain copy gets on this machine, what a copy with a step
- * kernel's access skeleton gets, how fast the L2 caches feed the compute units, and what a re-read out of the
- * Infinity Cache is worth.
+ * kernel's access skeleton gets, and what a re-read out of the Infinity Cache is worth.
  *
  * All pointers are DEVICE pointers, 16-byte aligned; sizes in bytes, multiples of 16.  Calls enqueue one kernel on
  * `stream` (hipStream_t as void*, NULL = default stream) and return 0, or -1 for bad arguments, -7 if the launch
@@ -33,20 +32,16 @@ int32_t svdc_probe_read(const void* src, size_t bytes, void* sink, void* stream)
  * channels: a load instruction of a wave covers 16 rows x 64 bytes (the matrix-core lane layout), a wave owns 12
  * such chunks of a row tile, a workgroup of four waves half a row, and a workgroup walks over `tiles_per_group`
  * 16-row tiles, one tile in flight ahead -- interleaved with the other workgroups of its 4608-row block
- * (interleave != 0, as the kernel does) or contiguous.  rows must be a multiple of 4608. */
+ * (interleave != 0, as the kernel does) or contiguous.  groups_per_cu (0..8; 0 = no limit) caps how many workgroups
+ * share a compute unit, by giving each that share of the LDS: the cached-step kernel, with its basis operands in
+ * registers, runs one workgroup per compute unit.  rows must be a multiple of 4608. */
 int32_t svdc_probe_tile_copy(void* dst, const void* src, int32_t rows, int32_t tiles_per_group, int32_t interleave,
-                             void* stream);
+                             int32_t groups_per_cu, void* stream);
 
 /* Copy of the same matrix with the skeleton of the full-step kernel: one persistent workgroup per compute unit
  * loads a whole tile of `tile_rows` (16, 32 or 48) rows x 6144 bytes into registers in one burst, stores it, and only
  * then requests its next tile. */
 int32_t svdc_probe_burst_copy(void* dst, const void* src, int32_t rows, int32_t tile_rows, void* stream);
-
-/* L2 -> compute unit streaming: `groups` workgroups of 256 threads each read the same `window_bytes` (a multiple of
- * 4096) `repeats` times with 16-byte loads, 12 loads in flight per wave.  With a window that fits the 4 MB L2 of
- * an XCD (e.g. the 786 KB packed basis of one block) this measures what the L2 caches deliver in aggregate. */
-int32_t svdc_probe_l2_stream(const void* window, size_t window_bytes, int32_t repeats, int32_t groups, void* sink,
-                             void* stream);
 
 #ifdef __cplusplus
 }

@@ -32,6 +32,8 @@ constexpr int kBlockRows = 4608;
 // The cached step's skeleton: NCW = 12 chunks of 64 bytes per wave and row tile, two slabs of 3072 bytes per row.
 __global__ __launch_bounds__(256) void tile_copy_kernel(const char* __restrict__ a, char* __restrict__ b,
                                                         int groups_per_block, int tiles_per_group, int interleave) {
+  extern __shared__ char occupancy_pad[];   // sized by the launcher so that only so many workgroups share a compute unit
+  if (threadIdx.x == 0 && groups_per_block < 0) occupancy_pad[0] = 0;   // never true: keeps the allocation
   constexpr int NCW = 12, NS = 2;
   const int slab = blockIdx.x % NS, rgb = blockIdx.x / NS;
   const int blk = rgb / groups_per_block, rg = rgb % groups_per_block;
@@ -89,33 +91,6 @@ __global__ __launch_bounds__(256) void burst_copy_kernel(const char* __restrict_
   }
 }
 
-// Every workgroup streams the same window `repeats` times: wave w reads the words w, w + 4, ... of 1 KB each,
-// RD loads in flight.
-__global__ __launch_bounds__(256) void l2_stream_kernel(const u32x4* __restrict__ win, int words, int repeats,
-                                                        uint32_t* sink) {
-  constexpr int RD = 12;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int mine = (words - wave + 3) / 4;              // 1 KB words of this wave
-  u32x4 acc = {0, 0, 0, 0};
-  for (int rep = 0; rep < repeats; ++rep) {
-    u32x4 ring[RD];
-#pragma unroll
-    for (int m = 0; m < RD; ++m)
-      if (m < mine) ring[m] = win[(size_t)(wave + 4 * m) * 64 + lane];
-    for (int m0 = 0; m0 < mine; m0 += RD) {
-#pragma unroll
-      for (int u = 0; u < RD; ++u) {
-        const int m = m0 + u;
-        if (m >= mine) break;
-        acc ^= ring[u];
-        if (m + RD < mine) ring[u] = win[(size_t)(wave + 4 * (m + RD)) * 64 + lane];
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u && acc[0] == 0x7f4a7c15u) *sink = 1;
-}
-
 }  // namespace
 
 extern "C" {
@@ -135,12 +110,18 @@ int32_t svdc_probe_read(const void* src, size_t bytes, void* sink, void* stream)
 }
 
 int32_t svdc_probe_tile_copy(void* dst, const void* src, int32_t rows, int32_t tiles_per_group, int32_t interleave,
-                             void* stream) {
-  if (!ok16(dst) || !ok16(src) || rows <= 0 || rows % kBlockRows || tiles_per_group < 1 || tiles_per_group > 288)
+                             int32_t groups_per_cu, void* stream) {
+  if (!ok16(dst) || !ok16(src) || rows <= 0 || rows % kBlockRows || tiles_per_group < 1 || tiles_per_group > 288 ||
+      groups_per_cu < 0 || groups_per_cu > 8)
     return -1;
   const int blocks = rows / kBlockRows;
   const int gpb = (kBlockRows / 16 + tiles_per_group - 1) / tiles_per_group;
-  tile_copy_kernel<<<(unsigned)(2 * gpb * blocks), 256, 0, (hipStream_t)stream>>>(
+  // LDS nobody uses, so that at most groups_per_cu workgroups fit a compute unit (160 KB of LDS); 0 = no limit
+  const size_t lds = groups_per_cu ? (size_t)(150 * 1024 / groups_per_cu) / 1024 * 1024 : 0;
+  if (lds > 48 * 1024 &&
+      hipFuncSetAttribute((const void*)tile_copy_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+    return -7;
+  tile_copy_kernel<<<(unsigned)(2 * gpb * blocks), 256, lds, (hipStream_t)stream>>>(
       (const char*)src, (char*)dst, gpb, tiles_per_group, interleave);
   return status();
 }
@@ -159,16 +140,6 @@ int32_t svdc_probe_burst_copy(void* dst, const void* src, int32_t rows, int32_t 
   if (tile_rows == 16) burst_copy_kernel<1><<<grid, 256, 0, st>>>(a, b, rows, total);
   else if (tile_rows == 32) burst_copy_kernel<2><<<grid, 256, 0, st>>>(a, b, rows, total);
   else burst_copy_kernel<3><<<grid, 256, 0, st>>>(a, b, rows, total);
-  return status();
-}
-
-int32_t svdc_probe_l2_stream(const void* window, size_t window_bytes, int32_t repeats, int32_t groups, void* sink,
-                             void* stream) {
-  if (!ok16(window) || !sink || window_bytes == 0 || window_bytes % 4096 || window_bytes > (size_t)1 << 30 ||
-      repeats < 1 || groups < 1 || groups > 65535)
-    return -1;
-  l2_stream_kernel<<<groups, 256, 0, (hipStream_t)stream>>>((const u32x4*)window, (int)(window_bytes / 1024), repeats,
-                                                           (uint32_t*)sink);
   return status();
 }
 

@@ -11,9 +11,9 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 EXPORTS = {
     "svdc_probe_copy": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "svdc_probe_read": (C.c_int32, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
-    "svdc_probe_tile_copy": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]),
+    "svdc_probe_tile_copy": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                         C.c_void_p]),
     "svdc_probe_burst_copy": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
-    "svdc_probe_l2_stream": (C.c_int32, [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
 }
 
 _lib = None
@@ -58,19 +58,13 @@ def read(src, sink, nbytes=None):
                                        _stream()), "svdc_probe_read")
 
 
-def tile_copy(dst, src, rows, tiles_per_group, interleave):
+def tile_copy(dst, src, rows, tiles_per_group, interleave, groups_per_cu=0):
     assert _bytes(src) >= rows * 6144 and _bytes(dst) >= rows * 6144
     _ok(load_library().svdc_probe_tile_copy(dst.data_ptr(), src.data_ptr(), rows, tiles_per_group, int(interleave),
-                                            _stream()), "svdc_probe_tile_copy")
+                                            int(groups_per_cu), _stream()), "svdc_probe_tile_copy")
 
 
 def burst_copy(dst, src, rows, tile_rows):
     assert _bytes(src) >= rows * 6144 and _bytes(dst) >= rows * 6144
     _ok(load_library().svdc_probe_burst_copy(dst.data_ptr(), src.data_ptr(), rows, tile_rows, _stream()),
         "svdc_probe_burst_copy")
-
-
-def l2_stream(window, window_bytes, repeats, groups, sink):
-    assert _bytes(window) >= window_bytes
-    _ok(load_library().svdc_probe_l2_stream(window.data_ptr(), window_bytes, repeats, groups, sink.data_ptr(),
-                                            _stream()), "svdc_probe_l2_stream")
