@@ -57,7 +57,8 @@ def algorithmic_bytes(wl, q_passes):
 def sweep(args):
     """Rank / precision sweep at the stacked-prompt shape (4 prompts x 4608 tokens, one shared basis):
     per-launch time and algorithmic GB/s of the full step and the cached step for k in {8..128},
-    bf16 (matrix-core kernels, both arithmetic modes) and float32 (general vector-ALU kernels).
+    bf16 (matrix-core kernels, both arithmetic modes) and float32 (the same matrix-core kernels, features split
+    into bf16 high + low parts on the fly).
     Prints one JSON line per case; not the headline benchmark."""
     import torch
     import paper_2601_07396_amd as pkg

@@ -1,7 +1,7 @@
 // General (any shape, any k <= 1024) kernels for the full-compute step and the
 // cached step.  Plain fp32 vector arithmetic, one wavefront per token row.
-// They are the fallback for shapes the matrix-core kernels do not cover and the
-// path used for float32 features.
+// They are the fallback for shapes the matrix-core kernels do not cover (hidden sizes that are not one of the
+// instantiated multiples of 128, ranks above 128 or not a multiple of 4), for either storage type.
 #include "svdc_device.h"
 #include "svdc_internal.h"
 
