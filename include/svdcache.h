@@ -157,8 +157,8 @@ int32_t svdcache_fit_basis(const svdc_shape* shape, const svdc_fit_params* param
  * (each GPU the library runs on holds its own copy until the process ends); the call allocates and frees nothing.
  *   status  out  [B] int32 device, the SVDC_FIT_* status words of the blocks; may be NULL
  * Problems whose workspace (svdcache_workspace_bytes) exceeds SVDC_STATIC_SCRATCH_BYTES are refused with
- * SVDC_E_WORKSPACE before anything is launched: at the default parameters 32 MiB hold 7 blocks of 4608 x 3072 at
- * rank 32, or one at rank 128.  The device that owns `stream` must be the current device.  All calls on one GPU
+ * SVDC_E_WORKSPACE before anything is launched: at the default parameters 32 MiB hold 8 blocks of 4608 x 3072 at
+ * rank 32, 3 at rank 64, or one at rank 128.  The device that owns `stream` must be the current device.  All calls on one GPU
  * share that GPU's array: calls that overlap in time on one GPU (different streams, different threads) race and must
  * be serialised by the caller; consecutive calls on one stream are fine (the fit overwrites or clears every part of
  * the array it reads).  The first call on a device looks up the array's address (no allocation). */
