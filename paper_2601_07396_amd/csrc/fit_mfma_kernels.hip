@@ -27,8 +27,10 @@ __device__ __forceinline__ f32x4 mfma16(const u32x4& a, const u32x4& b, const f3
 // Q [B, D, l] float32 -> bf16 high / low operand tiles (projection layout):
 //   tile (cg, jt), lane (r, g), e  ->  Q[d = 32 cg + 8 g + e][j = 16 jt + r]   (0 for j >= l)
 // Per block: hi array of D * LP elements followed by the lo array, LP = 16 KT.
+// Q points at the first of the l columns to pack; ldq is the row stride of the whole matrix (sketches wider than 128
+// are packed, and multiplied, as two column ranges).
 __global__ __launch_bounds__(256) void pack_q_kernel(const float* __restrict__ Q, uint16_t* __restrict__ P, int D,
-                                                     int l, int KT) {
+                                                     int l, int KT, int ldq) {
   const int b = blockIdx.y;
   const int64_t per = (int64_t)D * KT * 16;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -37,7 +39,7 @@ __global__ __launch_bounds__(256) void pack_q_kernel(const float* __restrict__ Q
   const int64_t tile = idx >> 9;
   const int jt = tile % KT, cg = tile / KT;
   const int d = 32 * cg + 8 * g + e, j = 16 * jt + r;
-  const float x = j < l ? Q[((int64_t)b * D + d) * l + j] : 0.f;
+  const float x = j < l ? Q[((int64_t)b * D + d) * ldq + j] : 0.f;
   const bf16_t hi = (bf16_t)x;
   const bf16_t lo = (bf16_t)(x - (float)hi);
   uint16_t* p = P + (int64_t)b * 2 * per;
@@ -79,7 +81,7 @@ __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __r
                                                                const uint16_t* __restrict__ Qp, float* Y,
                                                                u32x4* Yp, double* fro_acc, int N, int D, int l,
                                                                int64_t ldf, int64_t bstride, int NS,
-                                                               int groups_per_block) {
+                                                               int groups_per_block, int ldy) {
   constexpr int PD = 2;
   static_assert(TG % PD == 0, "prefetch ring must divide the tile group");
   __shared__ f32x4 part[kWaves][2][KT][64];
@@ -155,7 +157,7 @@ __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __r
   }
 
   // add the four waves' partial sums, two row tiles per round
-  float* ybase = Y + (int64_t)b * N * l;
+  float* ybase = Y + (int64_t)b * N * ldy;
   const int nsteps = (N + 31) / 32;
 #pragma unroll
   for (int rd = 0; rd < TG / 2; ++rd) {
@@ -200,7 +202,7 @@ __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __r
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int row = (tile0 + 2 * rd + tt) * 16 + 4 * g + i;
-        if (row < N && j < l) ybase[(int64_t)row * l + j] = s[i];
+        if (row < N && j < l) ybase[(int64_t)row * ldy + j] = s[i];
       }
     }
     __syncthreads();
@@ -223,7 +225,7 @@ __global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __r
                                                                const uint16_t* __restrict__ Qp, float* Y,
                                                                u32x4* Yp, double* fro_acc, int N, int D, int l,
                                                                int64_t ldf, int64_t bstride,
-                                                               int groups_per_block) {
+                                                               int groups_per_block, int ldy) {
   // Chunks of F in flight per wave.  With split operands they are requested two at a time (PD = 4): the two
   // 64-byte pieces of a 128-byte line belong to neighbouring chunks, and asked for a whole chunk's work apart the
   // line comes from L2 twice (4 % slower).  With plain operands at width 128 the extra registers cost more than
@@ -347,7 +349,7 @@ __global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __r
       return;
     }
   }
-  float* ybase = Y + (int64_t)b * N * l;
+  float* ybase = Y + (int64_t)b * N * ldy;
 #pragma unroll
   for (int t = 0; t < RTW; ++t)
 #pragma unroll
@@ -356,7 +358,7 @@ __global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __r
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int row = (tile0 + t) * 16 + 4 * g + i;
-        if (row < N && j < l) ybase[(int64_t)row * l + j] = acc[t][jt][i];
+        if (row < N && j < l) ybase[(int64_t)row * ldy + j] = acc[t][jt][i];
       }
     }
 }
@@ -381,7 +383,7 @@ __global__ __launch_bounds__(256) void fit_backproject_mfma_kernel(const bf16_t*
                                                                    const u32x4* __restrict__ Yp, float* Z, int N,
                                                                    int D, int l, int64_t ldf, int64_t bstride,
                                                                    int NS, int groups_per_block,
-                                                                   int rows_per_group) {
+                                                                   int rows_per_group, int ldy, int ldz) {
   const int slab = blockIdx.x % NS;
   const int rgb = blockIdx.x / NS;
   const int b = rgb / groups_per_block, rg = rgb % groups_per_block;
@@ -389,7 +391,7 @@ __global__ __launch_bounds__(256) void fit_backproject_mfma_kernel(const bf16_t*
   const int cg0 = (slab * kWaves + wave) * NCW;
   const uint32_t* fbase = reinterpret_cast<const uint32_t*>(F + (int64_t)b * bstride + 32 * cg0) + r;
   const int64_t ldw = ldf / 2;   // row stride in 32-bit words
-  const float* ybase = Y + (int64_t)b * N * l;
+  const float* ybase = Y + (int64_t)b * N * ldy;
   const int row_begin = rg * rows_per_group;
   const int row_end = min(N, row_begin + rows_per_group);
 
@@ -416,7 +418,7 @@ __global__ __launch_bounds__(256) void fit_backproject_mfma_kernel(const bf16_t*
 #pragma unroll
         for (int jt = 0; jt < KT; ++jt) {
           const int j = 16 * jt + r;
-          yv[jt][e] = (row < row_end && j < l) ? ybase[(int64_t)row * l + j] : 0.f;
+          yv[jt][e] = (row < row_end && j < l) ? ybase[(int64_t)row * ldy + j] : 0.f;
         }
       }
     }
@@ -453,7 +455,7 @@ __global__ __launch_bounds__(256) void fit_backproject_mfma_kernel(const bf16_t*
         for (int jt = 0; jt < KT; ++jt) acc[c][p][jt] = mfma16(fop[c][p], yop[jt], acc[c][p][jt]);
   }
 
-  float* zbase = Z + (int64_t)b * D * l;
+  float* zbase = Z + (int64_t)b * D * ldz;
 #pragma unroll
   for (int c = 0; c < NCW; ++c)
 #pragma unroll
@@ -466,8 +468,8 @@ __global__ __launch_bounds__(256) void fit_backproject_mfma_kernel(const bf16_t*
         for (int i = 0; i < 4; ++i) {
           const int d = 32 * (cg0 + c) + 2 * (4 * g + i) + p;
           // one row group per block: every element has a single writer
-          if (groups_per_block == 1) zbase[(int64_t)d * l + j] = acc[c][p][jt][i];
-          else atomicAdd(zbase + (int64_t)d * l + j, acc[c][p][jt][i]);
+          if (groups_per_block == 1) zbase[(int64_t)d * ldz + j] = acc[c][p][jt][i];
+          else atomicAdd(zbase + (int64_t)d * ldz + j, acc[c][p][jt][i]);
         }
       }
 }
@@ -475,9 +477,16 @@ __global__ __launch_bounds__(256) void fit_backproject_mfma_kernel(const bf16_t*
 template <int KT>
 constexpr int width_for() { return KT <= 2 ? 12 : (KT == 4 ? 6 : 3); }
 
+// Row strides of the whole Y / Z matrices when a call covers only a range of their columns (sketches wider than 128
+// are multiplied as two column ranges), and whether Z has been cleared for atomic accumulation already.
+struct Strides {
+  int ldy, ldz;
+  bool z_cleared;
+};
+
 template <int NCW, int KT>
 void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, u32x4* Yp,
-                    double* fro_acc, bool split, hipStream_t st) {
+                    double* fro_acc, bool split, Strides ld, hipStream_t st) {
   // 4 row tiles per workgroup from sketch width 64 on: with a 4-chunk slab that is about 250 registers, so two
   // workgroups share a compute unit and one streams F while the other loads its Q operands (measured 8 % / 13 %
   // faster than 8 tiles x 6 chunks at 3072 channels, plain / split operands)
@@ -498,16 +507,16 @@ void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, f
       const int g = rows_grid();
       if (fro_acc)
         fit_project_rows_kernel<KT, RTW, SC, true, true><<<(unsigned)((int64_t)g * s.B), 256, 0, st>>>(
-            f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g);
+            f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g, ld.ldy);
       else
         fit_project_rows_kernel<KT, RTW, SC, true, false><<<(unsigned)((int64_t)g * s.B), 256, 0, st>>>(
-            f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g);
+            f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g, ld.ldy);
       return;
     }
     if constexpr (KT == 8) {
       const int g = rows_grid();
       fit_project_rows_kernel<KT, RTW, 4, false, false><<<(unsigned)((int64_t)g * s.B), 256, 0, st>>>(
-          f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g);
+          f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g, ld.ldy);
       return;
     }
   }
@@ -515,28 +524,28 @@ void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, f
     const int NS = s.D / (128 * NCWS);
     if (fro_acc)
       fit_project_mfma_kernel<NCWS, KT, TG, true, true><<<grid, 256, 0, st>>>(f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf,
-                                                                            s.block_stride, NS, gpb);
+                                                                            s.block_stride, NS, gpb, ld.ldy);
     else
       fit_project_mfma_kernel<NCWS, KT, TG, true, false><<<grid, 256, 0, st>>>(f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf,
-                                                                             s.block_stride, NS, gpb);
+                                                                             s.block_stride, NS, gpb, ld.ldy);
   } else {
     const int NS = s.D / (128 * NCW);
     fit_project_mfma_kernel<NCW, KT, TG, false, false><<<grid, 256, 0, st>>>(f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf,
-                                                                           s.block_stride, NS, gpb);
+                                                                           s.block_stride, NS, gpb, ld.ldy);
   }
 }
 
 template <int NCW, int KT>
 void backproject_launch(const svdc_shape& s, int l, const void* F, const float* Y, const u32x4* Yp, float* Z, int gpb, int rows,
-                        hipStream_t st) {
+                        Strides ld, hipStream_t st) {
   const int NS = s.D / (128 * NCW);
   const unsigned grid = (unsigned)((int64_t)NS * gpb * s.B);
   if (Yp)
     fit_backproject_mfma_kernel<NCW, KT, true><<<grid, 256, 0, st>>>((const bf16_t*)F, Y, Yp, Z, s.N, s.D, l, s.ldf,
-                                                                    s.block_stride, NS, gpb, rows);
+                                                                    s.block_stride, NS, gpb, rows, ld.ldy, ld.ldz);
   else
     fit_backproject_mfma_kernel<NCW, KT, false><<<grid, 256, 0, st>>>((const bf16_t*)F, Y, Yp, Z, s.N, s.D, l, s.ldf,
-                                                                     s.block_stride, NS, gpb, rows);
+                                                                     s.block_stride, NS, gpb, rows, ld.ldy, ld.ldz);
 }
 
 __global__ void clear_f32_kernel(float* p, int64_t n) {
@@ -575,77 +584,130 @@ void by_width(int m, Fn12 f12, Fn6 f6, Fn4 f4, Fn3 f3, Fn2 f2, Fn1 f1) {
 
 template <int KT>
 void project_kt(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, u32x4* Yp, double* fro, bool split,
-                hipStream_t st) {
+                Strides ld, hipStream_t st) {
   constexpr int cap = KT == 4 ? 4 : width_for<KT>();
   by_width<KT, cap>(
-      s.D / 128, [&] { project_launch<(cap >= 12 ? 12 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, st); },
-      [&] { project_launch<(cap >= 6 ? 6 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, st); },
-      [&] { project_launch<(cap >= 4 ? 4 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, st); },
-      [&] { project_launch<3, KT>(s, l, F, Qp, Y, Yp, fro, split, st); },
-      [&] { project_launch<2, KT>(s, l, F, Qp, Y, Yp, fro, split, st); },
-      [&] { project_launch<1, KT>(s, l, F, Qp, Y, Yp, fro, split, st); });
+      s.D / 128, [&] { project_launch<(cap >= 12 ? 12 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
+      [&] { project_launch<(cap >= 6 ? 6 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
+      [&] { project_launch<(cap >= 4 ? 4 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
+      [&] { project_launch<3, KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
+      [&] { project_launch<2, KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
+      [&] { project_launch<1, KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); });
 }
 
 template <int NCW, int KT>
 void backproject_one(const svdc_shape& s, int l, const void* F, const float* Y, const u32x4* Yp, float* Z,
-                     hipStream_t st) {
+                     Strides ld, hipStream_t st) {
   int gpb, rows;
   backproject_groups<NCW>(s, &gpb, &rows);
-  if (gpb > 1) {   // atomics accumulate into Z
+  if (gpb > 1 && !ld.z_cleared) {   // atomics accumulate into Z (a single column range: Z is contiguous)
     const int64_t n = (int64_t)s.B * s.D * l;
     clear_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(Z, n);
   }
-  backproject_launch<NCW, KT>(s, l, F, Y, Yp, Z, gpb, rows, st);
+  backproject_launch<NCW, KT>(s, l, F, Y, Yp, Z, gpb, rows, ld, st);
 }
 
 template <int KT>
 void backproject_kt(const svdc_shape& s, int l, const void* F, const float* Y, const u32x4* Yp, float* Z,
-                    hipStream_t st) {
+                    Strides ld, hipStream_t st) {
   constexpr int cap = width_for<KT>();
   by_width<KT, cap>(
-      s.D / 128, [&] { backproject_one<(cap >= 12 ? 12 : 1), KT>(s, l, F, Y, Yp, Z, st); },
-      [&] { backproject_one<(cap >= 6 ? 6 : 1), KT>(s, l, F, Y, Yp, Z, st); },
-      [&] { backproject_one<(cap >= 4 ? 4 : 1), KT>(s, l, F, Y, Yp, Z, st); },
-      [&] { backproject_one<3, KT>(s, l, F, Y, Yp, Z, st); }, [&] { backproject_one<2, KT>(s, l, F, Y, Yp, Z, st); },
-      [&] { backproject_one<1, KT>(s, l, F, Y, Yp, Z, st); });
+      s.D / 128, [&] { backproject_one<(cap >= 12 ? 12 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
+      [&] { backproject_one<(cap >= 6 ? 6 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
+      [&] { backproject_one<(cap >= 4 ? 4 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
+      [&] { backproject_one<3, KT>(s, l, F, Y, Yp, Z, ld, st); }, [&] { backproject_one<2, KT>(s, l, F, Y, Yp, Z, ld, st); },
+      [&] { backproject_one<1, KT>(s, l, F, Y, Yp, Z, ld, st); });
+}
+
+// Sketches wider than 128 are handled as two column ranges (128 and the rest), each with the kernels of its own
+// width: F is then read twice per product.
+struct ColRange { int j0, l; };
+inline int col_ranges(int l, ColRange (&r)[2]) {
+  if (l <= 128) { r[0] = {0, l}; return 1; }
+  r[0] = {0, 128};
+  r[1] = {128, l - 128};
+  return 2;
+}
+inline int kt_for(int l) { return l <= 16 ? 1 : (l <= 32 ? 2 : (l <= 64 ? 4 : 8)); }
+inline size_t packed_q_bytes_one(const svdc_shape& s, int l) { return (size_t)s.B * 2 * s.D * kt_for(l) * 16 * sizeof(uint16_t); }
+inline size_t packed_y_bytes_one(const svdc_shape& s, int l) { return (size_t)s.B * (((size_t)s.N + 31) / 32) * kt_for(l) * 1024; }
+
+template <typename Fn>
+void by_kt(int l, Fn fn) {
+  if (l <= 16) fn(std::integral_constant<int, 1>{});
+  else if (l <= 32) fn(std::integral_constant<int, 2>{});
+  else if (l <= 64) fn(std::integral_constant<int, 4>{});
+  else fn(std::integral_constant<int, 8>{});
 }
 
 }  // namespace
 
 bool fit_mfma_supported(const svdc_shape& s, int l) {
-  return s.dtype == SVDC_BF16 && s.D % 128 == 0 && l <= 128;
+  return s.dtype == SVDC_BF16 && s.D % 128 == 0 && l <= 256;
 }
 
 size_t fit_mfma_packed_q_bytes(const svdc_shape& s, int l) {
-  const int KT = l <= 16 ? 1 : (l <= 32 ? 2 : (l <= 64 ? 4 : 8));
-  return (size_t)s.B * 2 * s.D * KT * 16 * sizeof(uint16_t);
+  ColRange r[2];
+  const int n = col_ranges(l, r);
+  size_t bytes = 0;
+  for (int h = 0; h < n; ++h) bytes += packed_q_bytes_one(s, r[h].l);
+  return bytes;
 }
 
 size_t fit_mfma_packed_y_bytes(const svdc_shape& s, int l) {
-  const int KT = l <= 16 ? 1 : (l <= 32 ? 2 : (l <= 64 ? 4 : 8));
-  return (size_t)s.B * (((size_t)s.N + 31) / 32) * KT * 1024;
+  ColRange r[2];
+  const int n = col_ranges(l, r);
+  size_t bytes = 0;
+  for (int h = 0; h < n; ++h) bytes += packed_y_bytes_one(s, r[h].l);
+  return bytes;
 }
 
 void fit_mfma_pack_q(const svdc_shape& s, int l, const float* Q, void* Qp, hipStream_t st) {
-  const int KT = l <= 16 ? 1 : (l <= 32 ? 2 : (l <= 64 ? 4 : 8));
-  const int64_t per = (int64_t)s.D * KT * 16;
-  pack_q_kernel<<<dim3((unsigned)((per + 255) / 256), s.B), 256, 0, st>>>(Q, (uint16_t*)Qp, s.D, l, KT);
+  ColRange r[2];
+  const int n = col_ranges(l, r);
+  char* out = static_cast<char*>(Qp);
+  for (int h = 0; h < n; ++h) {
+    const int KT = kt_for(r[h].l);
+    const int64_t per = (int64_t)s.D * KT * 16;
+    pack_q_kernel<<<dim3((unsigned)((per + 255) / 256), s.B), 256, 0, st>>>(Q + r[h].j0, (uint16_t*)out, s.D, r[h].l, KT, l);
+    out += packed_q_bytes_one(s, r[h].l);
+  }
 }
 
 void fit_mfma_project(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, void* Ypacked, double* fro_acc,
                       bool split, hipStream_t st) {
-  if (l <= 16) project_kt<1>(s, l, F, Qp, Y, (u32x4*)Ypacked, fro_acc, split, st);
-  else if (l <= 32) project_kt<2>(s, l, F, Qp, Y, (u32x4*)Ypacked, fro_acc, split, st);
-  else if (l <= 64) project_kt<4>(s, l, F, Qp, Y, (u32x4*)Ypacked, fro_acc, split, st);
-  else project_kt<8>(s, l, F, Qp, Y, (u32x4*)Ypacked, fro_acc, split, st);
+  ColRange r[2];
+  const int n = col_ranges(l, r);
+  const char* qp = static_cast<const char*>(Qp);
+  char* yp = static_cast<char*>(Ypacked);
+  for (int h = 0; h < n; ++h) {
+    const Strides ld{l, l, false};
+    by_kt(r[h].l, [&](auto kt) {
+      project_kt<decltype(kt)::value>(s, r[h].l, F, qp, Y + r[h].j0, (u32x4*)yp, h == 0 ? fro_acc : nullptr, split, ld, st);
+    });
+    qp += packed_q_bytes_one(s, r[h].l);
+    if (yp) yp += packed_y_bytes_one(s, r[h].l);
+  }
 }
 
 void fit_mfma_backproject(const svdc_shape& s, int l, const void* F, const float* Y, const void* Ypacked, float* Z,
                           hipStream_t st) {
-  if (l <= 16) backproject_kt<1>(s, l, F, Y, (const u32x4*)Ypacked, Z, st);
-  else if (l <= 32) backproject_kt<2>(s, l, F, Y, (const u32x4*)Ypacked, Z, st);
-  else if (l <= 64) backproject_kt<4>(s, l, F, Y, (const u32x4*)Ypacked, Z, st);
-  else backproject_kt<8>(s, l, F, Y, (const u32x4*)Ypacked, Z, st);
+  ColRange r[2];
+  const int n = col_ranges(l, r);
+  const char* yp = static_cast<const char*>(Ypacked);
+  bool cleared = false;
+  if (n > 1) {   // the column ranges interleave in memory: clear all of Z once, for whichever range accumulates
+    const int64_t cnt = (int64_t)s.B * s.D * l;
+    clear_f32_kernel<<<(unsigned)((cnt + 255) / 256), 256, 0, st>>>(Z, cnt);
+    cleared = true;
+  }
+  for (int h = 0; h < n; ++h) {
+    const Strides ld{l, l, cleared};
+    by_kt(r[h].l, [&](auto kt) {
+      backproject_kt<decltype(kt)::value>(s, r[h].l, F, Y ? Y + r[h].j0 : nullptr, (const u32x4*)yp, Z + r[h].j0, ld, st);
+    });
+    if (yp) yp += packed_y_bytes_one(s, r[h].l);
+  }
 }
 
 }  // namespace svdc
