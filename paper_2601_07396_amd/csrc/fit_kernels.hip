@@ -16,6 +16,8 @@
 #include <algorithm>
 #include <utility>
 
+#include <type_traits>
+
 #include "svdc_device.h"
 #include "svdc_internal.h"
 
@@ -907,10 +909,13 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   const bool want_fro = fro2 != nullptr;
   bool fro_done = false;
   // Y = F Q.  The last product feeds the Rayleigh-Ritz step and uses the full-precision operand split.
+  // float32 features: every product splits both operands, and Y stays float32 rows between the two products
+  constexpr bool kF32 = std::is_same<T, float>::value;
   auto project = [&](bool last) {
     if (pl.mfma) {
       fit_mfma_pack_q(s, l, Q, Qp, st);
-      fit_mfma_project(s, l, F, Qp, Y, last ? nullptr : (void*)Y, (last && want_fro) ? misc : nullptr, last, st);
+      fit_mfma_project(s, l, F, Qp, Y, (last || kF32) ? nullptr : (void*)Y, (last && want_fro) ? misc : nullptr,
+                       last || kF32, st);
       if (last && want_fro) fro_done = true;
     } else {
       gemm_fq<T>(s, l, F, Q, Y, st);
@@ -919,7 +924,7 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   for (int it = 0; it < pl.q; ++it) {
     project(false);
     if (pl.mfma) {
-      fit_mfma_backproject(s, l, F, Y, Y, Z, st);   // Y holds the packed form here
+      fit_mfma_backproject(s, l, F, Y, kF32 ? nullptr : Y, Z, st);   // bf16: Y holds the packed form here
     } else {
       gemm_fty<T>(s, l, F, Y, Z, st);
     }

@@ -24,6 +24,47 @@ __device__ __forceinline__ f32x4 mfma16(const u32x4& a, const u32x4& b, const f3
                                                  0, 0, 0);
 }
 
+// Eight consecutive channels of one token as they are loaded, and as matrix-core operands.  bf16 features are the
+// operand; float32 features are split into bf16 high + low parts when used (the products then take the high part
+// against both parts of the other operand and the low part against its high part: about 16 significant bits).
+template <typename T>
+struct FPiece;
+template <>
+struct FPiece<bf16_t> {
+  static constexpr bool kTwoParts = false;
+  u32x4 w;
+  __device__ __forceinline__ void load(const bf16_t* p) { w = *reinterpret_cast<const u32x4*>(p); }
+  __device__ __forceinline__ void operands(u32x4* hi, u32x4* lo) const { *hi = w; *lo = w; }
+  __device__ __forceinline__ float sumsq() const {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float x0 = bf16_lo(w[i]), x1 = bf16_hi(w[i]);
+      s += x0 * x0 + x1 * x1;
+    }
+    return s;
+  }
+};
+template <>
+struct FPiece<float> {
+  static constexpr bool kTwoParts = true;
+  f32x4 x[2];
+  __device__ __forceinline__ void load(const float* p) {
+    x[0] = *reinterpret_cast<const f32x4*>(p);
+    x[1] = *reinterpret_cast<const f32x4*>(p + 4);
+  }
+  __device__ __forceinline__ void operands(u32x4* hi, u32x4* lo) const {
+    const float c8[8] = {x[0][0], x[0][1], x[0][2], x[0][3], x[1][0], x[1][1], x[1][2], x[1][3]};
+    split_operand(c8, hi, lo);
+  }
+  __device__ __forceinline__ float sumsq() const {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s += x[0][i] * x[0][i] + x[1][i] * x[1][i];
+    return s;
+  }
+};
+
 // Q [B, D, l] float32 -> bf16 high / low operand tiles (projection layout):
 //   tile (cg, jt), lane (r, g), e  ->  Q[d = 32 cg + 8 g + e][j = 16 jt + r]   (0 for j >= l)
 // Per block: hi array of D * LP elements followed by the lo array, LP = 16 KT.
@@ -76,8 +117,8 @@ __device__ __forceinline__ u32x4 pack_y_word(const f32x4& t0, const f32x4& t1, i
 //   D[m = 4 g + i][n = r]  ->  Y[row 16 tile + 4 g + i][16 jt + r]
 // FRO: also accumulate sum F^2 (for ||F||_F^2).
 // ---------------------------------------------------------------------------
-template <int NCW, int KT, int TG, bool SPLIT, bool FRO>
-__global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __restrict__ F,
+template <typename T, int NCW, int KT, int TG, bool SPLIT, bool FRO>
+__global__ __launch_bounds__(256) void fit_project_mfma_kernel(const T* __restrict__ F,
                                                                const uint16_t* __restrict__ Qp, float* Y,
                                                                u32x4* Yp, double* fro_acc, int N, int D, int l,
                                                                int64_t ldf, int64_t bstride, int NS,
@@ -90,7 +131,7 @@ __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __r
   const int64_t per = (int64_t)D * KT * 16;
   const u32x4* Qhi = reinterpret_cast<const u32x4*>(Qp + (int64_t)b * 2 * per);
   const u32x4* Qlo = reinterpret_cast<const u32x4*>(Qp + (int64_t)b * 2 * per + per);
-  const bf16_t* fbase = F + (int64_t)b * bstride + 8 * g;
+  const T* fbase = F + (int64_t)b * bstride + 8 * g;
   const int tile0 = rg * TG;
   const int ntiles = min(TG, (N + 15) / 16 - tile0);
 
@@ -100,13 +141,12 @@ __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __r
 #pragma unroll
     for (int jt = 0; jt < KT; ++jt) acc[t][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  u32x4 fin[PD][NCW];
-  auto load_tile = [&](int slab, int t, u32x4(&fi)[NCW]) {
+  FPiece<T> fin[PD][NCW];
+  auto load_tile = [&](int slab, int t, FPiece<T>(&fi)[NCW]) {
     const int row = min((tile0 + t) * 16 + r, N - 1);
     const int cg0 = (slab * kWaves + wave) * NCW;
 #pragma unroll
-    for (int c = 0; c < NCW; ++c)
-      fi[c] = *reinterpret_cast<const u32x4*>(fbase + (int64_t)row * ldf + 32 * (cg0 + c));
+    for (int c = 0; c < NCW; ++c) fi[c].load(fbase + (int64_t)row * ldf + 32 * (cg0 + c));
   };
 #pragma unroll
   for (int u = 0; u < PD; ++u) load_tile(0, u, fin[u]);
@@ -129,18 +169,15 @@ __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __r
       if (t < ntiles) {
 #pragma unroll
         for (int c = 0; c < NCW; ++c) {
+          u32x4 fh, fl;
+          fin[u][c].operands(&fh, &fl);
 #pragma unroll
           for (int jt = 0; jt < KT; ++jt) {
-            acc[t][jt] = mfma16(fin[u][c], q_hi[c][jt], acc[t][jt]);
-            if (SPLIT) acc[t][jt] = mfma16(fin[u][c], q_lo[c][jt], acc[t][jt]);
+            acc[t][jt] = mfma16(fh, q_hi[c][jt], acc[t][jt]);
+            if (FPiece<T>::kTwoParts) acc[t][jt] = mfma16(fl, q_hi[c][jt], acc[t][jt]);
+            if (SPLIT) acc[t][jt] = mfma16(fh, q_lo[c][jt], acc[t][jt]);
           }
-          if (FRO && (tile0 + t) * 16 + r < N) {
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-              const float x0 = bf16_lo(fin[u][c][w]), x1 = bf16_hi(fin[u][c][w]);
-              ssq += x0 * x0 + x1 * x1;
-            }
-          }
+          if (FRO && (tile0 + t) * 16 + r < N) ssq += fin[u][c].sumsq();
         }
       }
       // refill this ring slot with the tile PD steps ahead (possibly in the next slab)
@@ -220,8 +257,8 @@ __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const bf16_t* __r
 // 128 (0.66 against 0.88 ms with split operands), 0.41 against 0.53 ms at width 64 with split operands; at width
 // 64 with plain operands the register-stationary kernel stays ahead (0.36 against 0.42 ms).
 // ---------------------------------------------------------------------------
-template <int KT, int RTW, int SC, bool SPLIT, bool FRO>
-__global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __restrict__ F,
+template <typename T, int KT, int RTW, int SC, bool SPLIT, bool FRO>
+__global__ __launch_bounds__(256) void fit_project_rows_kernel(const T* __restrict__ F,
                                                                const uint16_t* __restrict__ Qp, float* Y,
                                                                u32x4* Yp, double* fro_acc, int N, int D, int l,
                                                                int64_t ldf, int64_t bstride,
@@ -242,7 +279,7 @@ __global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __r
   const int64_t per = (int64_t)D * KT * 16;
   const u32x4* Qhi = reinterpret_cast<const u32x4*>(Qp + (int64_t)b * 2 * per);
   const u32x4* Qlo = reinterpret_cast<const u32x4*>(Qp + (int64_t)b * 2 * per + per);
-  const bf16_t* fbase = F + (int64_t)b * bstride + 8 * g;
+  const T* fbase = F + (int64_t)b * bstride + 8 * g;
   const int tile0 = (rg * kWaves + wave) * RTW;
   const int NS = D / (32 * SC), NC = D / 32;
 
@@ -255,10 +292,10 @@ __global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __r
   int64_t rowoff[RTW];
 #pragma unroll
   for (int t = 0; t < RTW; ++t) rowoff[t] = (int64_t)min((tile0 + t) * 16 + r, N - 1) * ldf;
-  u32x4 fin[PD][RTW];
-  auto load_chunk = [&](int chunk, u32x4(&fi)[RTW]) {
+  FPiece<T> fin[PD][RTW];
+  auto load_chunk = [&](int chunk, FPiece<T>(&fi)[RTW]) {
 #pragma unroll
-    for (int t = 0; t < RTW; ++t) fi[t] = *reinterpret_cast<const u32x4*>(fbase + rowoff[t] + 32 * chunk);
+    for (int t = 0; t < RTW; ++t) fi[t].load(fbase + rowoff[t] + 32 * chunk);
   };
   u32x4 stg[NP][WPW];
   auto load_stage = [&](int slab) {
@@ -292,6 +329,9 @@ __global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __r
       const int chunk = slab * SC + c;
       constexpr int kSlotBase = (PAR * SC) % PD;
       const int u = (kSlotBase + c) % PD;     // = chunk % PD
+      u32x4 fh[RTW], fl[RTW];
+#pragma unroll
+      for (int t = 0; t < RTW; ++t) fin[u][t].operands(&fh[t], &fl[t]);
 #pragma unroll
       for (int jt = 0; jt < KT; ++jt) {
         const u32x4 bh = qs[buf][0][c * KT + jt][lane];
@@ -299,20 +339,15 @@ __global__ __launch_bounds__(256) void fit_project_rows_kernel(const bf16_t* __r
         if (SPLIT) bl = qs[buf][NP - 1][c * KT + jt][lane];
 #pragma unroll
         for (int t = 0; t < RTW; ++t) {
-          acc[t][jt] = mfma16(fin[u][t], bh, acc[t][jt]);
-          if (SPLIT) acc[t][jt] = mfma16(fin[u][t], bl, acc[t][jt]);
+          acc[t][jt] = mfma16(fh[t], bh, acc[t][jt]);
+          if (FPiece<T>::kTwoParts) acc[t][jt] = mfma16(fl[t], bh, acc[t][jt]);
+          if (SPLIT) acc[t][jt] = mfma16(fh[t], bl, acc[t][jt]);
         }
       }
       if (FRO) {
 #pragma unroll
         for (int t = 0; t < RTW; ++t)
-          if ((tile0 + t) * 16 + r < N) {
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-              const float x0 = bf16_lo(fin[u][t][w]), x1 = bf16_hi(fin[u][t][w]);
-              ssq += x0 * x0 + x1 * x1;
-            }
-          }
+          if ((tile0 + t) * 16 + r < N) ssq += fin[u][t].sumsq();
       }
       if constexpr (PAIRED) {
         if (c % 2 == 1) {                     // chunks c - 1 and c are done: refill both slots together
@@ -474,6 +509,102 @@ __global__ __launch_bounds__(256) void fit_backproject_mfma_kernel(const bf16_t*
       }
 }
 
+// ---------------------------------------------------------------------------
+// backproject for float32 features: the same contraction, Z[d][j] += sum_rows F[row][d] Y[row][j], with both
+// operands split into bf16 high + low parts on the fly (F_hi Y_hi + F_lo Y_hi + F_hi Y_lo).  A lane loads, for each
+// of its 8 rows, the two float32 channels (2 r, 2 r + 1) of a chunk; Y comes as float32 rows.  Same output mapping
+// and row-group scheme as the bf16 kernel.
+// ---------------------------------------------------------------------------
+template <int NCW, int KT>
+__global__ __launch_bounds__(256) void fit_backproject_f32_kernel(const float* __restrict__ F,
+                                                                  const float* __restrict__ Y, float* Z, int N,
+                                                                  int D, int l, int64_t ldf, int64_t bstride,
+                                                                  int NS, int groups_per_block, int rows_per_group,
+                                                                  int ldy, int ldz) {
+  const int slab = blockIdx.x % NS;
+  const int rgb = blockIdx.x / NS;
+  const int b = rgb / groups_per_block, rg = rgb % groups_per_block;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  const int cg0 = (slab * kWaves + wave) * NCW;
+  const f32x2* fbase = reinterpret_cast<const f32x2*>(F + (int64_t)b * bstride + 32 * cg0) + r;
+  const int64_t ldw = ldf / 2;   // row stride in channel pairs
+  const float* ybase = Y + (int64_t)b * N * ldy;
+  const int row_begin = rg * rows_per_group;
+  const int row_end = min(N, row_begin + rows_per_group);
+
+  f32x4 acc[NCW][2][KT];
+#pragma unroll
+  for (int c = 0; c < NCW; ++c)
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+      for (int jt = 0; jt < KT; ++jt) acc[c][p][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  f32x2 fw[NCW][8];
+  float yv[KT][8];
+  auto load_step = [&](int row0) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int row = row0 + 8 * g + e;
+      const int rowc = min(row, N - 1);
+#pragma unroll
+      for (int c = 0; c < NCW; ++c) {
+        const f32x2 x = fbase[(int64_t)rowc * ldw + 16 * c];
+        fw[c][e] = row < row_end ? x : f32x2{0.f, 0.f};
+      }
+#pragma unroll
+      for (int jt = 0; jt < KT; ++jt) {
+        const int j = 16 * jt + r;
+        yv[jt][e] = (row < row_end && j < l) ? ybase[(int64_t)row * ldy + j] : 0.f;
+      }
+    }
+  };
+  if (row_begin < row_end) load_step(row_begin);
+  for (int row0 = row_begin; row0 < row_end; row0 += 32) {
+    u32x4 yhi[KT], ylo[KT];
+#pragma unroll
+    for (int jt = 0; jt < KT; ++jt) split_operand(yv[jt], &yhi[jt], &ylo[jt]);
+    u32x4 fhi[NCW][2], flo[NCW][2];
+#pragma unroll
+    for (int c = 0; c < NCW; ++c)
+#pragma unroll
+      for (int p = 0; p < 2; ++p) {
+        float c8[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) c8[e] = fw[c][e][p];
+        split_operand(c8, &fhi[c][p], &flo[c][p]);
+      }
+    if (row0 + 32 < row_end) load_step(row0 + 32);
+#pragma unroll
+    for (int c = 0; c < NCW; ++c)
+#pragma unroll
+      for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int jt = 0; jt < KT; ++jt) {
+          acc[c][p][jt] = mfma16(fhi[c][p], yhi[jt], acc[c][p][jt]);
+          acc[c][p][jt] = mfma16(flo[c][p], yhi[jt], acc[c][p][jt]);
+          acc[c][p][jt] = mfma16(fhi[c][p], ylo[jt], acc[c][p][jt]);
+        }
+  }
+
+  float* zbase = Z + (int64_t)b * D * ldz;
+#pragma unroll
+  for (int c = 0; c < NCW; ++c)
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+      for (int jt = 0; jt < KT; ++jt) {
+        const int j = 16 * jt + r;
+        if (j >= l) continue;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int d = 32 * (cg0 + c) + 2 * (4 * g + i) + p;
+          if (groups_per_block == 1) zbase[(int64_t)d * ldz + j] = acc[c][p][jt][i];
+          else atomicAdd(zbase + (int64_t)d * ldz + j, acc[c][p][jt][i]);
+        }
+      }
+}
+
 template <int KT>
 constexpr int width_for() { return KT <= 2 ? 12 : (KT == 4 ? 6 : 3); }
 
@@ -484,9 +615,10 @@ struct Strides {
   bool z_cleared;
 };
 
-template <int NCW, int KT>
+template <typename T, int NCW, int KT>
 void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, u32x4* Yp,
                     double* fro_acc, bool split, Strides ld, hipStream_t st) {
+  constexpr bool kF32 = std::is_same<T, float>::value;   // float32 features always take the split sketch
   // 4 row tiles per workgroup from sketch width 64 on: with a 4-chunk slab that is about 250 registers, so two
   // workgroups share a compute unit and one streams F while the other loads its Q operands (measured 8 % / 13 %
   // faster than 8 tiles x 6 chunks at 3072 channels, plain / split operands)
@@ -496,8 +628,9 @@ void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, f
   const int ntile = (s.N + 15) / 16;
   const int gpb = (ntile + TG - 1) / TG;
   const unsigned grid = (unsigned)((int64_t)gpb * s.B);
-  const bf16_t* f = (const bf16_t*)F;
+  const T* f = (const T*)F;
   const uint16_t* q = (const uint16_t*)Qp;
+  if (kF32) split = true;
   // wide sketches: rows split over the waves, Q shared through LDS
   if constexpr (KT >= 4) {
     constexpr int RTW = (KT == 8) ? 2 : 3;
@@ -506,16 +639,16 @@ void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, f
       constexpr int SC = (KT == 8) ? 2 : 4;
       const int g = rows_grid();
       if (fro_acc)
-        fit_project_rows_kernel<KT, RTW, SC, true, true><<<(unsigned)((int64_t)g * s.B), 256, 0, st>>>(
+        fit_project_rows_kernel<T, KT, RTW, SC, true, true><<<(unsigned)((int64_t)g * s.B), 256, 0, st>>>(
             f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g, ld.ldy);
       else
-        fit_project_rows_kernel<KT, RTW, SC, true, false><<<(unsigned)((int64_t)g * s.B), 256, 0, st>>>(
+        fit_project_rows_kernel<T, KT, RTW, SC, true, false><<<(unsigned)((int64_t)g * s.B), 256, 0, st>>>(
             f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g, ld.ldy);
       return;
     }
-    if constexpr (KT == 8) {
+    if constexpr (KT == 8 && !kF32) {
       const int g = rows_grid();
-      fit_project_rows_kernel<KT, RTW, 4, false, false><<<(unsigned)((int64_t)g * s.B), 256, 0, st>>>(
+      fit_project_rows_kernel<T, KT, RTW, 4, false, false><<<(unsigned)((int64_t)g * s.B), 256, 0, st>>>(
           f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, g, ld.ldy);
       return;
     }
@@ -523,29 +656,34 @@ void project_launch(const svdc_shape& s, int l, const void* F, const void* Qp, f
   if (split) {
     const int NS = s.D / (128 * NCWS);
     if (fro_acc)
-      fit_project_mfma_kernel<NCWS, KT, TG, true, true><<<grid, 256, 0, st>>>(f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf,
-                                                                            s.block_stride, NS, gpb, ld.ldy);
+      fit_project_mfma_kernel<T, NCWS, KT, TG, true, true><<<grid, 256, 0, st>>>(
+          f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, NS, gpb, ld.ldy);
     else
-      fit_project_mfma_kernel<NCWS, KT, TG, true, false><<<grid, 256, 0, st>>>(f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf,
-                                                                             s.block_stride, NS, gpb, ld.ldy);
-  } else {
+      fit_project_mfma_kernel<T, NCWS, KT, TG, true, false><<<grid, 256, 0, st>>>(
+          f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, NS, gpb, ld.ldy);
+  } else if constexpr (!kF32) {
     const int NS = s.D / (128 * NCW);
-    fit_project_mfma_kernel<NCW, KT, TG, false, false><<<grid, 256, 0, st>>>(f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf,
-                                                                           s.block_stride, NS, gpb, ld.ldy);
+    fit_project_mfma_kernel<T, NCW, KT, TG, false, false><<<grid, 256, 0, st>>>(
+        f, q, Y, Yp, fro_acc, s.N, s.D, l, s.ldf, s.block_stride, NS, gpb, ld.ldy);
   }
 }
 
-template <int NCW, int KT>
+template <typename T, int NCW, int KT>
 void backproject_launch(const svdc_shape& s, int l, const void* F, const float* Y, const u32x4* Yp, float* Z, int gpb, int rows,
                         Strides ld, hipStream_t st) {
   const int NS = s.D / (128 * NCW);
   const unsigned grid = (unsigned)((int64_t)NS * gpb * s.B);
-  if (Yp)
-    fit_backproject_mfma_kernel<NCW, KT, true><<<grid, 256, 0, st>>>((const bf16_t*)F, Y, Yp, Z, s.N, s.D, l, s.ldf,
-                                                                    s.block_stride, NS, gpb, rows, ld.ldy, ld.ldz);
-  else
-    fit_backproject_mfma_kernel<NCW, KT, false><<<grid, 256, 0, st>>>((const bf16_t*)F, Y, Yp, Z, s.N, s.D, l, s.ldf,
-                                                                     s.block_stride, NS, gpb, rows, ld.ldy, ld.ldz);
+  if constexpr (std::is_same<T, float>::value) {
+    fit_backproject_f32_kernel<NCW, KT><<<grid, 256, 0, st>>>((const float*)F, Y, Z, s.N, s.D, l, s.ldf,
+                                                              s.block_stride, NS, gpb, rows, ld.ldy, ld.ldz);
+  } else {
+    if (Yp)
+      fit_backproject_mfma_kernel<NCW, KT, true><<<grid, 256, 0, st>>>((const bf16_t*)F, Y, Yp, Z, s.N, s.D, l, s.ldf,
+                                                                      s.block_stride, NS, gpb, rows, ld.ldy, ld.ldz);
+    else
+      fit_backproject_mfma_kernel<NCW, KT, false><<<grid, 256, 0, st>>>((const bf16_t*)F, Y, Yp, Z, s.N, s.D, l, s.ldf,
+                                                                       s.block_stride, NS, gpb, rows, ld.ldy, ld.ldz);
+  }
 }
 
 __global__ void clear_f32_kernel(float* p, int64_t n) {
@@ -572,30 +710,31 @@ void backproject_groups(const svdc_shape& s, int* gpb, int* rows) {
 }
 
 // largest instantiated slab width (chunks per wave) that divides D / 128 and is at most `cap`
-template <int KT, int cap, typename Fn12, typename Fn6, typename Fn4, typename Fn3, typename Fn2, typename Fn1>
+template <int cap, typename Fn12, typename Fn6, typename Fn4, typename Fn3, typename Fn2, typename Fn1>
 void by_width(int m, Fn12 f12, Fn6 f6, Fn4 f4, Fn3 f3, Fn2 f2, Fn1 f1) {
   if constexpr (cap >= 12) { if (m % 12 == 0) return f12(); }
   if constexpr (cap >= 6) { if (m % 6 == 0) return f6(); }
   if constexpr (cap >= 4) { if (m % 4 == 0) return f4(); }
-  if (m % 3 == 0) return f3();
+  if constexpr (cap >= 3) { if (m % 3 == 0) return f3(); }
   if (m % 2 == 0) return f2();
   return f1();
 }
 
-template <int KT>
+template <typename T, int KT>
 void project_kt(const svdc_shape& s, int l, const void* F, const void* Qp, float* Y, u32x4* Yp, double* fro, bool split,
                 Strides ld, hipStream_t st) {
-  constexpr int cap = KT == 4 ? 4 : width_for<KT>();
-  by_width<KT, cap>(
-      s.D / 128, [&] { project_launch<(cap >= 12 ? 12 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
-      [&] { project_launch<(cap >= 6 ? 6 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
-      [&] { project_launch<(cap >= 4 ? 4 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
-      [&] { project_launch<3, KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
-      [&] { project_launch<2, KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
-      [&] { project_launch<1, KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); });
+  // float32 features hold 8 registers per piece in flight and always carry both sketch parts: narrower slabs
+  constexpr int cap = std::is_same<T, float>::value ? 3 : (KT == 4 ? 4 : width_for<KT>());
+  by_width<cap>(
+      s.D / 128, [&] { project_launch<T, (cap >= 12 ? 12 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
+      [&] { project_launch<T, (cap >= 6 ? 6 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
+      [&] { project_launch<T, (cap >= 4 ? 4 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
+      [&] { project_launch<T, (cap >= 3 ? 3 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
+      [&] { project_launch<T, 2, KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
+      [&] { project_launch<T, 1, KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); });
 }
 
-template <int NCW, int KT>
+template <typename T, int NCW, int KT>
 void backproject_one(const svdc_shape& s, int l, const void* F, const float* Y, const u32x4* Yp, float* Z,
                      Strides ld, hipStream_t st) {
   int gpb, rows;
@@ -604,19 +743,24 @@ void backproject_one(const svdc_shape& s, int l, const void* F, const float* Y, 
     const int64_t n = (int64_t)s.B * s.D * l;
     clear_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(Z, n);
   }
-  backproject_launch<NCW, KT>(s, l, F, Y, Yp, Z, gpb, rows, ld, st);
+  backproject_launch<T, NCW, KT>(s, l, F, Y, Yp, Z, gpb, rows, ld, st);
 }
 
+// slab widths of the float32 back-projection (twice the registers per loaded row, two operand parts on each side)
 template <int KT>
+constexpr int width_for_f32() { return KT <= 2 ? 6 : (KT == 4 ? 3 : 2); }
+
+template <typename T, int KT>
 void backproject_kt(const svdc_shape& s, int l, const void* F, const float* Y, const u32x4* Yp, float* Z,
                     Strides ld, hipStream_t st) {
-  constexpr int cap = width_for<KT>();
-  by_width<KT, cap>(
-      s.D / 128, [&] { backproject_one<(cap >= 12 ? 12 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
-      [&] { backproject_one<(cap >= 6 ? 6 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
-      [&] { backproject_one<(cap >= 4 ? 4 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
-      [&] { backproject_one<3, KT>(s, l, F, Y, Yp, Z, ld, st); }, [&] { backproject_one<2, KT>(s, l, F, Y, Yp, Z, ld, st); },
-      [&] { backproject_one<1, KT>(s, l, F, Y, Yp, Z, ld, st); });
+  constexpr int cap = std::is_same<T, float>::value ? width_for_f32<KT>() : width_for<KT>();
+  by_width<cap>(
+      s.D / 128, [&] { backproject_one<T, (cap >= 12 ? 12 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
+      [&] { backproject_one<T, (cap >= 6 ? 6 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
+      [&] { backproject_one<T, (cap >= 4 ? 4 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
+      [&] { backproject_one<T, (cap >= 3 ? 3 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
+      [&] { backproject_one<T, 2, KT>(s, l, F, Y, Yp, Z, ld, st); },
+      [&] { backproject_one<T, 1, KT>(s, l, F, Y, Yp, Z, ld, st); });
 }
 
 // Sketches wider than 128 are handled as two column ranges (128 and the rest), each with the kernels of its own
@@ -643,7 +787,7 @@ void by_kt(int l, Fn fn) {
 }  // namespace
 
 bool fit_mfma_supported(const svdc_shape& s, int l) {
-  return s.dtype == SVDC_BF16 && s.D % 128 == 0 && l <= 256;
+  return (s.dtype == SVDC_BF16 || s.dtype == SVDC_F32) && s.D % 128 == 0 && l <= 256;
 }
 
 size_t fit_mfma_packed_q_bytes(const svdc_shape& s, int l) {
@@ -683,7 +827,11 @@ void fit_mfma_project(const svdc_shape& s, int l, const void* F, const void* Qp,
   for (int h = 0; h < n; ++h) {
     const Strides ld{l, l, false};
     by_kt(r[h].l, [&](auto kt) {
-      project_kt<decltype(kt)::value>(s, r[h].l, F, qp, Y + r[h].j0, (u32x4*)yp, h == 0 ? fro_acc : nullptr, split, ld, st);
+      constexpr int KT = decltype(kt)::value;
+      if (s.dtype == SVDC_F32)
+        project_kt<float, KT>(s, r[h].l, F, qp, Y + r[h].j0, nullptr, h == 0 ? fro_acc : nullptr, true, ld, st);
+      else
+        project_kt<bf16_t, KT>(s, r[h].l, F, qp, Y + r[h].j0, (u32x4*)yp, h == 0 ? fro_acc : nullptr, split, ld, st);
     });
     qp += packed_q_bytes_one(s, r[h].l);
     if (yp) yp += packed_y_bytes_one(s, r[h].l);
@@ -704,7 +852,11 @@ void fit_mfma_backproject(const svdc_shape& s, int l, const void* F, const float
   for (int h = 0; h < n; ++h) {
     const Strides ld{l, l, cleared};
     by_kt(r[h].l, [&](auto kt) {
-      backproject_kt<decltype(kt)::value>(s, r[h].l, F, Y ? Y + r[h].j0 : nullptr, (const u32x4*)yp, Z + r[h].j0, ld, st);
+      constexpr int KT = decltype(kt)::value;
+      if (s.dtype == SVDC_F32)
+        backproject_kt<float, KT>(s, r[h].l, F, Y + r[h].j0, nullptr, Z + r[h].j0, ld, st);
+      else
+        backproject_kt<bf16_t, KT>(s, r[h].l, F, Y ? Y + r[h].j0 : nullptr, (const u32x4*)yp, Z + r[h].j0, ld, st);
     });
     if (yp) yp += packed_y_bytes_one(s, r[h].l);
   }

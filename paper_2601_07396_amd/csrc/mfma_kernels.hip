@@ -94,21 +94,6 @@ __global__ __launch_bounds__(256) void pack_basis_kernel(const float* __restrict
   }
 }
 
-// split 8 fp32 coefficients into bf16 high and low operand words
-__device__ __forceinline__ void split_operand(const float (&c)[8], u32x4* hi, u32x4* lo) {
-  float rem[8];
-  uint32_t h[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    h[i] = pack_bf16(c[2 * i], c[2 * i + 1]);
-    rem[2 * i] = c[2 * i] - bf16_lo(h[i]);
-    rem[2 * i + 1] = c[2 * i + 1] - bf16_hi(h[i]);
-  }
-  *hi = u32x4{h[0], h[1], h[2], h[3]};
-  *lo = u32x4{pack_bf16(rem[0], rem[1]), pack_bf16(rem[2], rem[3]), pack_bf16(rem[4], rem[5]),
-              pack_bf16(rem[6], rem[7])};
-}
-
 // ---------------------------------------------------------------------------
 // Packed coefficient state: S [B, N, k] float32 as the operand words of the cached step.  Per block, 16-row tile and
 // group kt of 32 coefficients two words of 64 lanes x 16 bytes (bf16 high part, then low part) of -S:

@@ -30,6 +30,21 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, b);
 }
 
+// split 8 float32 values into bf16 high and low operand words
+__device__ __forceinline__ void split_operand(const float (&c)[8], u32x4* hi, u32x4* lo) {
+  float rem[8];
+  uint32_t h[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    h[i] = pack_bf16(c[2 * i], c[2 * i + 1]);
+    rem[2 * i] = c[2 * i] - bf16_lo(h[i]);
+    rem[2 * i + 1] = c[2 * i + 1] - bf16_hi(h[i]);
+  }
+  *hi = u32x4{h[0], h[1], h[2], h[3]};
+  *lo = u32x4{pack_bf16(rem[0], rem[1]), pack_bf16(rem[2], rem[3]), pack_bf16(rem[4], rem[5]),
+              pack_bf16(rem[6], rem[7])};
+}
+
 // ---- wavefront reductions -----------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
