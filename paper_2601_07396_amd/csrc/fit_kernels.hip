@@ -224,72 +224,6 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restri
 constexpr double kRankTol = 1e-12;
 
 // ---------------------------------------------------------------------------
-// Cholesky factor of a (shifted) Gram matrix and the transposed inverse factor.
-//   in : G [l x l] symmetric positive semi-definite, float64
-//   out: G lower triangle = L with G + shift I = L L^T, upper triangle zeroed
-//        Minv [l x l] = L^-T (upper triangular), so that Z * Minv has orthonormal columns
-// One workgroup per block.  The matrix lives in LDS when it fits.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void chol_inv_kernel(double* G, double* Minv, int l, int use_lds,
-                                                       double rel_shift, int32_t* info) {
-  extern __shared__ double dyn_lds[];
-  __shared__ double s_shift;
-  const int b = blockIdx.x, t = threadIdx.x;
-  double* g = G + (int64_t)b * l * l;
-  double* A = use_lds ? dyn_lds : g;
-  if (t < kWave) {
-    double mx = 0.0;
-    for (int i = t; i < l; i += kWave) mx = fmax(mx, g[(int64_t)i * l + i]);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o, kWave));
-    if (t == 0) s_shift = mx * rel_shift;
-  }
-  if (use_lds)
-    for (int idx = t; idx < l * l; idx += 256) A[idx] = g[idx];
-  __syncthreads();
-  for (int i = t; i < l; i += 256) A[i * l + i] += s_shift;
-  __syncthreads();
-
-  bool dependent = false;   // a pivot at the level of the sketch's float32 round-off (see kRankTol)
-  for (int c = 0; c < l; ++c) {
-    const double piv = sqrt(fmax(A[c * l + c], 1e-300));
-    dependent |= A[c * l + c] < s_shift * (kRankTol / rel_shift);
-    __syncthreads();
-    if (t == 0) A[c * l + c] = piv;
-    for (int i = c + 1 + t; i < l; i += 256) A[i * l + c] /= piv;
-    __syncthreads();
-    const int n = l - c - 1;
-    for (int idx = t; idx < n * n; idx += 256) {
-      const int i = c + 1 + idx / n, j = c + 1 + idx % n;
-      if (j <= i) A[i * l + j] -= A[i * l + c] * A[j * l + c];
-    }
-    __syncthreads();
-  }
-
-  if (t == 0 && dependent && info) atomicOr(info + b, SVDC_FIT_RANK_DEFICIENT);
-  if (Minv) {
-    // column j of L^-1 by forward substitution, stored as row j of Minv = L^-T
-    double* m = Minv + (int64_t)b * l * l;
-    for (int j = t; j < l; j += 256) {
-      double* mj = m + (int64_t)j * l;
-      for (int i = 0; i < j; ++i) mj[i] = 0.0;
-      mj[j] = 1.0 / A[j * l + j];
-      for (int i = j + 1; i < l; ++i) {
-        double s = 0.0;
-        for (int mm = j; mm < i; ++mm) s += A[i * l + mm] * mj[mm];
-        mj[i] = -s / A[i * l + i];
-      }
-    }
-  }
-  __syncthreads();
-  for (int idx = t; idx < l * l; idx += 256) {
-    const int i = idx / l, j = idx % l;
-    if (j > i) g[idx] = 0.0;
-    else if (use_lds) g[idx] = A[idx];
-  }
-}
-
-// ---------------------------------------------------------------------------
 // Out[rows x m] (float32) = In[rows x l] (float32) * M[l x m] (float64, row stride ldm)
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void rows_times_small_kernel(const float* __restrict__ In,
@@ -324,23 +258,47 @@ __global__ __launch_bounds__(256) void rows_times_small_kernel(const float* __re
 // through LDS (double buffered, one barrier per column) and every thread at or
 // below the diagonal and right of c applies the rank-1 update to its block; only
 // the block column that contains c needs per-element conditions.
-//   G      in/out  lower triangle = L with G + shift I = L L^T, upper triangle zeroed
-//   rdiag  out     (nullable) 1 / L[i][i]
+//   G      in/out  [l x l] at row stride ld, block b at G + b * bstride: lower triangle = L with
+//                  G + shift I = L L^T, upper triangle zeroed
+//   rdiag  out     (nullable) 1 / L[i][i], block b at rdiag + b * rd_bstride
+// The matrix may be a diagonal block of a larger one that is factored in two steps (ChoShift tells both steps
+// which shift to use: the first computes it from the whole diagonal, diag_n >= l entries, and stores it; the
+// second, diag_n = 0, reads it), the second block then being A22 - L21 L21^T with L21^T = Ut [ku x l] at row
+// stride ldut.
 // ---------------------------------------------------------------------------
+struct ChoShift {
+  double* slot;        // per block (stride slot_bstride): the shift, written when diag_n > 0, read otherwise
+  int64_t slot_bstride;
+  int diag_n;          // diagonal entries of G (same ld) that define the shift
+};
+struct ChoUpdate {
+  const double* Ut;    // nullable
+  int64_t bstride;
+  int ldut, ku;
+};
+
 template <int BS>
-__global__ __launch_bounds__(256) void chol_reg_kernel(double* G, double* rdiag, int l, double rel_shift,
-                                                       int32_t* info) {
+__global__ __launch_bounds__(256) void chol_reg_kernel(double* G, int64_t bstride, int ld, double* rdiag,
+                                                       int64_t rd_bstride, int l, double rel_shift, int32_t* info,
+                                                       ChoShift sh, ChoUpdate up) {
   constexpr int LM = 16 * BS;          // padded matrix size
   __shared__ double colbuf[2][LM];
   __shared__ double s_shift;
   const int b = blockIdx.x, t = threadIdx.x, tj = t >> 4, ti = t & 15;
-  double* g = G + (int64_t)b * l * l;
+  double* g = G + (int64_t)b * bstride;
   if (t < kWave) {
-    double mx = 0.0;
-    for (int i = t; i < l; i += kWave) mx = fmax(mx, g[(int64_t)i * l + i]);
+    if (sh.diag_n > 0) {
+      double mx = 0.0;
+      for (int i = t; i < sh.diag_n; i += kWave) mx = fmax(mx, g[(int64_t)i * ld + i]);
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o, kWave));
-    if (t == 0) s_shift = mx * rel_shift;
+      for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o, kWave));
+      if (t == 0) {
+        s_shift = mx * rel_shift;
+        if (sh.slot) sh.slot[(int64_t)b * sh.slot_bstride] = mx * rel_shift;
+      }
+    } else if (t == 0) {
+      s_shift = sh.slot[(int64_t)b * sh.slot_bstride];
+    }
   }
   __syncthreads();
   double a[BS][BS];
@@ -349,10 +307,24 @@ __global__ __launch_bounds__(256) void chol_reg_kernel(double* G, double* rdiag,
 #pragma unroll
     for (int jj = 0; jj < BS; ++jj) {
       const int i = BS * ti + ii, j = BS * tj + jj;
-      double v = (i < l && j < l) ? g[(int64_t)i * l + j] : (i == j ? 1.0 : 0.0);   // identity padding
+      double v = (i < l && j < l) ? g[(int64_t)i * ld + j] : (i == j ? 1.0 : 0.0);   // identity padding
       if (i == j && i < l) v += s_shift;
       a[ii][jj] = v;
     }
+  if (up.Ut && ti >= tj) {   // a -= L21 L21^T, from the transposed factor (rows of Ut are contiguous over i)
+    const double* ut = up.Ut + (int64_t)b * up.bstride;
+    for (int kk = 0; kk < up.ku; ++kk) {
+      double ui[BS], uj[BS];
+#pragma unroll
+      for (int ii = 0; ii < BS; ++ii) ui[ii] = (BS * ti + ii < l) ? ut[(int64_t)kk * up.ldut + BS * ti + ii] : 0.0;
+#pragma unroll
+      for (int jj = 0; jj < BS; ++jj) uj[jj] = (BS * tj + jj < l) ? ut[(int64_t)kk * up.ldut + BS * tj + jj] : 0.0;
+#pragma unroll
+      for (int ii = 0; ii < BS; ++ii)
+#pragma unroll
+        for (int jj = 0; jj < BS; ++jj) a[ii][jj] -= ui[ii] * uj[jj];
+    }
+  }
   const bool below = ti > tj;          // every element of the block is below the diagonal
   bool dependent = false;
   for (int c = 0; c < l; ++c) {
@@ -410,8 +382,8 @@ __global__ __launch_bounds__(256) void chol_reg_kernel(double* G, double* rdiag,
     for (int jj = 0; jj < BS; ++jj) {
       const int i = BS * ti + ii, j = BS * tj + jj;
       const double v = (j <= i) ? a[ii][jj] : 0.0;
-      if (i < l && j < l) g[(int64_t)i * l + j] = v;
-      if (rdiag && i == j && i < l) rdiag[(int64_t)b * l + i] = 1.0 / v;
+      if (i < l && j < l) g[(int64_t)i * ld + j] = v;
+      if (rdiag && i == j && i < l) rdiag[(int64_t)b * rd_bstride + i] = 1.0 / v;
     }
   // the thread that owns the last diagonal block has seen every pivot
   if (info && dependent && ti == tj && ti == (l - 1) / BS) atomicOr(info + b, SVDC_FIT_RANK_DEFICIENT);
@@ -479,11 +451,14 @@ __global__ __launch_bounds__(256) void rows_times_small_tiled_kernel(const float
 // at wave-uniform addresses (scalar loads); the row lives in registers.  Replaces the
 // explicit inverse factor plus a product for l <= LMAX.
 // ---------------------------------------------------------------------------
+// The l columns may be a column range of wider rows (row stride ld_io, In and Out already offset to the range's
+// first column) and L a diagonal block of a larger factor (row stride ldl, block b at Lfac + b * l_bstride).  In may
+// be the same buffer as Out: a thread reads its whole row before it writes.
 template <int LMAX>
-__global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* __restrict__ In,
-                                                             const double* __restrict__ Lfac,
+__global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* In, const double* __restrict__ Lfac,
                                                              const double* __restrict__ rdiag, float* Out,
-                                                             int rows, int l) {
+                                                             int rows, int l, int ld_io, int ldl,
+                                                             int64_t l_bstride, int64_t rd_bstride) {
   const int b = blockIdx.y, t = threadIdx.x;
   // every thread reads the same element of L at the same time: the factor is staged in LDS and read as
   // broadcasts (as scalar loads its 32 KB at l = 64 overflow the scalar cache)
@@ -491,15 +466,15 @@ __global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* __rest
   __shared__ double rd[LMAX];
   // rows of L at a compile-time stride: every LDS offset below is then a constant and neighbouring elements of a
   // row are fetched by one wide read
-  for (int e = t; e < l * l; e += 256) Lf[(e / l) * LMAX + e % l] = Lfac[(int64_t)b * l * l + e];
-  if (t < l) rd[t] = rdiag[(int64_t)b * l + t];
+  for (int e = t; e < l * l; e += 256) Lf[(e / l) * LMAX + e % l] = Lfac[(int64_t)b * l_bstride + (int64_t)(e / l) * ldl + e % l];
+  if (t < l) rd[t] = rdiag[(int64_t)b * rd_bstride + t];
   __syncthreads();
   const int64_t row = (int64_t)blockIdx.x * 256 + t;
   if (row >= rows) return;
-  const float* in = In + ((int64_t)b * rows + row) * l;
-  float* out = Out + ((int64_t)b * rows + row) * l;
+  const float* in = In + ((int64_t)b * rows + row) * ld_io;
+  float* out = Out + ((int64_t)b * rows + row) * ld_io;
   double q[LMAX];
-  const bool vec = (l & 3) == 0;   // rows are then 16-byte aligned
+  const bool vec = ((l | ld_io) & 3) == 0;   // rows (and column ranges that start at a multiple of 4) are then 16-byte aligned
   if (vec) {
 #pragma unroll
     for (int j = 0; j < LMAX; j += 4) {
@@ -528,6 +503,101 @@ __global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* __rest
 #pragma unroll
     for (int j = 0; j < LMAX; ++j)
       if (j < l) out[j] = (float)q[j];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Two-step Cholesky factorisation for 128 < l <= 256, G = [A11 . ; A21 A22] with A11 128 x 128:
+//   L11 = chol(A11)  (chol_reg_kernel),  L21 = A21 L11^-T  (this kernel),  L22 = chol(A22 - L21 L21^T)  (chol_reg_kernel)
+// One workgroup per block, thread t solves row 128 + t of A21 in registers against L11 staged in LDS, in float64;
+// L21 goes back in place and, transposed ([128 x m], m = l - 128), to Ut for the update of A22 and for the
+// products with L21^T.
+// ---------------------------------------------------------------------------
+constexpr int kCholHead = 128;
+
+__global__ __launch_bounds__(128) void tri_solve_block_kernel(double* G, const double* __restrict__ rdiag,
+                                                              int64_t rd_bstride, double* Ut, int64_t ut_bstride,
+                                                              int l) {
+  constexpr int H = kCholHead;
+  __shared__ double Lf[H * H];
+  __shared__ double rd[H];
+  const int b = blockIdx.x, t = threadIdx.x, m = l - H;
+  double* g = G + (int64_t)b * l * l;
+  for (int e = t; e < H * H; e += 128) Lf[e] = g[(int64_t)(e / H) * l + e % H];
+  rd[t] = rdiag[(int64_t)b * rd_bstride + t];
+  __syncthreads();
+  if (t >= m) return;
+  double* row = g + (int64_t)(H + t) * l;
+  double q[H];
+#pragma unroll
+  for (int j = 0; j < H; ++j) q[j] = row[j];
+#pragma unroll
+  for (int j = 0; j < H; ++j) {
+    double s = q[j];
+#pragma unroll
+    for (int i = 0; i < j; ++i) s -= q[i] * Lf[j * H + i];
+    q[j] = s * rd[j];
+  }
+  double* ut = Ut + (int64_t)b * ut_bstride;
+#pragma unroll
+  for (int j = 0; j < H; ++j) {
+    row[j] = q[j];
+    ut[(int64_t)j * m + t] = q[j];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Out[:, c0 + j] = In[:, c0 + j] - sum_{i < 128} Out[:, i] * Ut[i][j],  j < m: the middle step of Out = In L^-T for
+// the two-step factor, between the triangular solves with L11 (columns 0..127, already in Out) and with L22.
+// A workgroup takes 64 rows x 64 columns; Ut (float64) and the 128 leading columns of its rows are staged in LDS;
+// every thread accumulates a 4 x 4 block in float64.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rows_minus_product_kernel(const float* __restrict__ In, float* Out,
+                                                                 const double* __restrict__ Ut,
+                                                                 int64_t ut_bstride, int rows, int l) {
+  constexpr int H = kCholHead, LT = H + 1;
+  __shared__ double Ms[H * 64];      // [i][j]
+  __shared__ float tile[64 * LT];    // [row][i]
+  const int b = blockIdx.z, t = threadIdx.x, m = l - H;
+  const float* in = In + (int64_t)b * rows * l;
+  float* out = Out + (int64_t)b * rows * l;
+  const double* ut = Ut + (int64_t)b * ut_bstride;
+  const int r0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
+  for (int idx = t; idx < H * 64; idx += 256) {
+    const int i = idx >> 6, j = idx & 63;
+    Ms[idx] = (j0 + j < m) ? ut[(int64_t)i * m + j0 + j] : 0.0;
+  }
+  for (int idx = t; idx < 64 * H; idx += 256) {
+    const int rr = idx / H, c = idx % H;
+    tile[rr * LT + c] = (r0 + rr < rows) ? out[(int64_t)(r0 + rr) * l + c] : 0.f;
+  }
+  __syncthreads();
+  const int ty = t >> 4, tx = t & 15;
+  double acc[4][4];
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) acc[ii][jj] = 0.0;
+  for (int i = 0; i < H; ++i) {
+    double av[4], bv[4];
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii) av[ii] = (double)tile[(4 * ty + ii) * LT + i];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) bv[jj] = Ms[i * 64 + tx + 16 * jj];
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) acc[ii][jj] += av[ii] * bv[jj];
+  }
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii) {
+    const int row = r0 + 4 * ty + ii;
+    if (row >= rows) continue;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const int j = j0 + tx + 16 * jj;
+      if (j < m) out[(int64_t)row * l + H + j] = (float)((double)in[(int64_t)row * l + H + j] - acc[ii][jj]);
+    }
   }
 }
 
@@ -565,12 +635,77 @@ __device__ __forceinline__ double row_sum(double x, int width) {
 
 constexpr int kJacobiThreads = 512;
 
-// NE > 0 (matrix in LDS): a lane handles exactly NE elements of a column, NE >= ceil(l / lanes per pair), so the
-// element loops unroll with a fixed trip count, their LDS loads are issued together, and the elements stay in
-// registers between the dot products and the rotation.  NE = 0: loops of run-time length (matrix in global memory).
-template <bool a_in_lds, int NE>   // compile-time so that LDS accesses are ds_* instructions, not flat ones
+// One plane rotation of the one-sided Jacobi: the tp lanes of a pair (lane gl of tp) make columns ap and aq (length
+// l, in LDS) orthogonal.  A lane handles exactly NE elements of a column, NE >= ceil(l / tp), so the element loops
+// unroll with a fixed trip count, their LDS loads are issued together, and the elements stay in registers between
+// the dot products and the rotation.  Lane 0 of the pair counts the rotation in *rot, and in *big when the cosine of
+// the angle between the columns was above 3.2e-5.
+template <int NE>
+__device__ __forceinline__ void jacobi_rotate(double* ap, double* aq, int l, int gl, int tp, int* rot, int* big) {
+  double al = 0.0, be = 0.0, ga = 0.0;
+  double xs[NE], ys[NE];
+#pragma unroll
+  for (int e = 0; e < NE; ++e) {
+    const int r = gl + e * tp;
+    xs[e] = r < l ? ap[r] : 0.0;
+    ys[e] = r < l ? aq[r] : 0.0;
+  }
+#pragma unroll
+  for (int e = 0; e < NE; ++e) {
+    al += xs[e] * xs[e]; be += ys[e] * ys[e]; ga += xs[e] * ys[e];
+  }
+  // sums over the tp lanes of the pair: inside a row of 16 lanes with data-parallel-primitive moves (no LDS
+  // round trip as in a shuffle), across rows with shuffles
+  al = row_sum(al, tp); be = row_sum(be, tp); ga = row_sum(ga, tp);
+  for (int o = tp >> 1; o >= 16; o >>= 1) {
+    al += __shfl_xor(al, o, kWave);
+    be += __shfl_xor(be, o, kWave);
+    ga += __shfl_xor(ga, o, kWave);
+  }
+  // rotate when the columns are not yet orthogonal to 1e-7 (compared in squares, no sqrt): the outputs are
+  // float32, and a sweep that finds nothing above the threshold ends the iteration
+  if (ga * ga > 1e-14 * al * be) {
+    // The rotation ANGLE only steers convergence, so tan(theta) is computed in float32; cos and sin
+    // are then formed in float64 so that the rotation is orthogonal to double round-off.
+    const double zd = (be - al) * 0.5 * __builtin_amdgcn_rcp(ga);     // approximate reciprocal is enough
+    double tt;
+    if (fabs(zd) < 1e15) {
+      const float zeta = (float)zd;
+      tt = (double)((zeta >= 0.f ? 1.f : -1.f) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta)));
+    } else {
+      tt = 0.5 * __builtin_amdgcn_rcp(zd);
+    }
+    const double n2 = 1.0 + tt * tt;
+    double cs = __builtin_amdgcn_rsq(n2);
+    cs = cs * (1.5 - 0.5 * n2 * cs * cs);
+    cs = cs * (1.5 - 0.5 * n2 * cs * cs);
+    const double sn = cs * tt;
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      const int r = gl + e * tp;
+      if (r < l) {
+        ap[r] = cs * xs[e] - sn * ys[e];
+        aq[r] = sn * xs[e] + cs * ys[e];
+      }
+    }
+    if (gl == 0) {
+      atomicAdd(rot, 1);
+      if (ga * ga > 1e-9 * al * be) atomicAdd(big, 1);
+    }
+  }
+}
+
+// players p, q of pair `group` in step `step` of a round-robin over `le` players (le even): le - 1 steps pair
+// everybody with everybody once
+__device__ __forceinline__ void round_robin_pair(int le, int step, int group, int* p, int* q) {
+  if (group == 0) { *p = le - 1; *q = step % (le - 1); }
+  else { *p = (step + group) % (le - 1); *q = (step + (le - 1) - group) % (le - 1); }
+}
+
+// Whole matrix in LDS (l <= 138), one workgroup per block.
+template <int NE>
 __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __restrict__ Lfac, double* Wout, float* sigma,
-                                                     double* gA, int l, int k, const double* fro_acc, float* fro2,
+                                                     int l, int k, const double* fro_acc, float* fro2,
                                                      int max_sweeps, int32_t* info) {
   extern __shared__ double dyn_lds[];
   __shared__ double nrm[256];
@@ -579,7 +714,7 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
   const int b = blockIdx.x, t = threadIdx.x;
   const double* Lf = Lfac + (int64_t)b * l * l;
   const int la = l + 1;   // column stride, padded so that concurrently rotated columns spread over the LDS banks
-  double* A = a_in_lds ? dyn_lds : gA + (int64_t)b * l * la;                        // column-major
+  double* A = dyn_lds;    // column-major
   for (int idx = t; idx < l * l; idx += NT) {
     const int r = idx / l, c = idx % l;
     A[c * la + r] = (c <= r) ? Lf[idx] : 0.0;   // A = L
@@ -588,7 +723,7 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
   __syncthreads();
 
   const int le = (l + 1) & ~1;         // players in the round-robin (one dummy if l is odd)
-  const int npairs = le / 2;           // <= 128
+  const int npairs = le / 2;           // <= 69
   int tp = 64;
   while (tp > 1 && tp * npairs > NT) tp >>= 1;
   const int group = t / tp, gl = t % tp;
@@ -600,80 +735,8 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
     __syncthreads();
     for (int step = 0; step < le - 1; ++step) {
       int p = 0, q = 0;
-      if (active) {
-        if (group == 0) { p = le - 1; q = step % (le - 1); }
-        else { p = (step + group) % (le - 1); q = (step + (le - 1) - group) % (le - 1); }
-      }
-      if (active && p < l && q < l) {
-        double* ap = A + (int64_t)p * la;
-        double* aq = A + (int64_t)q * la;
-        double al = 0.0, be = 0.0, ga = 0.0;
-        double xs[NE > 0 ? NE : 1], ys[NE > 0 ? NE : 1];
-        if constexpr (NE > 0) {
-#pragma unroll
-          for (int e = 0; e < NE; ++e) {
-            const int r = gl + e * tp;
-            xs[e] = r < l ? ap[r] : 0.0;
-            ys[e] = r < l ? aq[r] : 0.0;
-          }
-#pragma unroll
-          for (int e = 0; e < NE; ++e) {
-            al += xs[e] * xs[e]; be += ys[e] * ys[e]; ga += xs[e] * ys[e];
-          }
-        } else {
-          for (int r = gl; r < l; r += tp) {
-            const double x = ap[r], y = aq[r];
-            al += x * x; be += y * y; ga += x * y;
-          }
-        }
-        // sums over the tp lanes of the pair: inside a row of 16 lanes with data-parallel-primitive moves (no LDS
-        // round trip as in a shuffle), across rows with shuffles
-        al = row_sum(al, tp); be = row_sum(be, tp); ga = row_sum(ga, tp);
-        for (int o = tp >> 1; o >= 16; o >>= 1) {
-          al += __shfl_xor(al, o, kWave);
-          be += __shfl_xor(be, o, kWave);
-          ga += __shfl_xor(ga, o, kWave);
-        }
-        // rotate when the columns are not yet orthogonal to 1e-7 (compared in squares, no sqrt): the outputs are
-        // float32, and a sweep that finds nothing above the threshold ends the iteration
-        if (ga * ga > 1e-14 * al * be) {
-          // The rotation ANGLE only steers convergence, so tan(theta) is computed in float32; cos and sin
-          // are then formed in float64 so that the rotation is orthogonal to double round-off.
-          const double zd = (be - al) * 0.5 * __builtin_amdgcn_rcp(ga);     // approximate reciprocal is enough
-          double tt;
-          if (fabs(zd) < 1e15) {
-            const float zeta = (float)zd;
-            tt = (double)((zeta >= 0.f ? 1.f : -1.f) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta)));
-          } else {
-            tt = 0.5 * __builtin_amdgcn_rcp(zd);
-          }
-          const double n2 = 1.0 + tt * tt;
-          double cs = __builtin_amdgcn_rsq(n2);
-          cs = cs * (1.5 - 0.5 * n2 * cs * cs);
-          cs = cs * (1.5 - 0.5 * n2 * cs * cs);
-          const double sn = cs * tt;
-          if constexpr (NE > 0) {
-#pragma unroll
-            for (int e = 0; e < NE; ++e) {
-              const int r = gl + e * tp;
-              if (r < l) {
-                ap[r] = cs * xs[e] - sn * ys[e];
-                aq[r] = sn * xs[e] + cs * ys[e];
-              }
-            }
-          } else {
-            for (int r = gl; r < l; r += tp) {
-              const double x = ap[r], y = aq[r];
-              ap[r] = cs * x - sn * y;
-              aq[r] = sn * x + cs * y;
-            }
-          }
-          if (gl == 0) {
-            atomicAdd(&s_rot, 1);
-            if (ga * ga > 1e-9 * al * be) atomicAdd(&s_big, 1);
-          }
-        }
-      }
+      if (active) round_robin_pair(le, step, group, &p, &q);
+      if (active && p < l && q < l) jacobi_rotate<NE>(A + (int64_t)p * la, A + (int64_t)q * la, l, gl, tp, &s_rot, &s_big);
       __syncthreads();
     }
     const int rot = s_rot, big = s_big;
@@ -699,6 +762,100 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __
     if (rank < k) sigma[(int64_t)b * k + rank] = (float)sqrt(nj);
     const double inv = nj > 0.0 ? 1.0 / sqrt(nj) : 0.0;
     for (int i = 0; i < l; ++i) wo[(int64_t)i * l + rank] = A[(int64_t)j * la + i] * inv;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// The same Jacobi for 138 < l <= 256, where the matrix (l x l float64) no longer fits the LDS of one workgroup: by
+// column blocks.  The columns form nb = ceil(l / 32) blocks; a round-robin over the blocks pairs every block with
+// every other once per sweep, and the pairs of one round-robin step are disjoint, so one launch handles a step with
+// one workgroup per block pair: it brings the pair's 64 columns into LDS, runs one full round-robin of rotations over
+// them (63 steps of 32 concurrent pairs, 16 lanes per pair) and writes them back.  The working matrix A lives in
+// global memory column by column (A[c * l + r]); the very first launch reads its columns from the Cholesky factor
+// instead.  Convergence is tracked per block in three rotating counters cnt[b][0..2]: the launches of sweep s count
+// the rotations with a cosine above 3.2e-5 in cnt[s % 3], return at once when cnt[(s - 1) % 3] is zero (the previous
+// sweep found nothing: converged, and it stays so because nothing is counted any more), and the first launch of the
+// sweep clears cnt[(s + 1) % 3] for the next one.  jacobi_finish_kernel then sorts and normalises.
+// ---------------------------------------------------------------------------
+constexpr int kJbCols = 32;
+
+template <int NE>
+__global__ __launch_bounds__(kJacobiThreads) void jacobi_block_kernel(const double* __restrict__ Lfac, double* gA, int l,
+                                                                      int step, int sweep, int first, int* cnt) {
+  extern __shared__ double dyn_lds[];
+  __shared__ int s_rot, s_big;
+  constexpr int NT = kJacobiThreads, NC = 2 * kJbCols, TP = NT / kJbCols;   // 64 local columns, 16 lanes per pair
+  static_assert(TP == 16, "lanes per pair");
+  const int b = blockIdx.y, t = threadIdx.x;
+  int* c3 = cnt + 4 * b;
+  if (blockIdx.x == 0 && step == 0 && t == 0) c3[(sweep + 1) % 3] = 0;
+  if (sweep > 0 && c3[(sweep + 2) % 3] == 0) return;   // uniform over the workgroup
+  const int nb = (l + kJbCols - 1) / kJbCols, nbe = (nb + 1) & ~1;
+  int bi, bj;
+  round_robin_pair(nbe, step, blockIdx.x, &bi, &bj);
+  const int la = l + 1;
+  double* A = dyn_lds;                                  // [NC][la]
+  double* ga = gA + (int64_t)b * l * l;
+  // global column of local column c (>= l: none)
+  auto gcol = [&](int c) { const int blk = c < kJbCols ? bi : bj; return blk < nb ? blk * kJbCols + (c & (kJbCols - 1)) : l; };
+  if (first) {
+    const double* Lf = Lfac + (int64_t)b * l * l;
+    for (int idx = t; idx < l * NC; idx += NT) {
+      const int r = idx / NC, c = idx % NC, gc = gcol(c);
+      if (gc < l) A[c * la + r] = (gc <= r) ? Lf[(int64_t)r * l + gc] : 0.0;
+    }
+  } else {
+    for (int idx = t; idx < NC * l; idx += NT) {
+      const int c = idx / l, r = idx % l, gc = gcol(c);
+      if (gc < l) A[c * la + r] = ga[(int64_t)gc * l + r];
+    }
+  }
+  if (t == 0) { s_rot = 0; s_big = 0; }
+  __syncthreads();
+  const int group = t / TP, gl = t % TP;
+  for (int st = 0; st < NC - 1; ++st) {
+    int p, q;
+    round_robin_pair(NC, st, group, &p, &q);
+    if (gcol(p) < l && gcol(q) < l) jacobi_rotate<NE>(A + p * la, A + q * la, l, gl, TP, &s_rot, &s_big);
+    __syncthreads();
+  }
+  for (int idx = t; idx < NC * l; idx += NT) {
+    const int c = idx / l, r = idx % l, gc = gcol(c);
+    if (gc < l) ga[(int64_t)gc * l + r] = A[c * la + r];
+  }
+  if (t == 0 && s_big > 0) atomicAdd(&c3[sweep % 3], s_big);
+}
+
+// Column norms -> singular values, rank order, normalised eigenvectors (same outputs as jacobi_kernel), one
+// workgroup per block, one wave per column at a time.
+__global__ __launch_bounds__(256) void jacobi_finish_kernel(const double* __restrict__ gA, double* Wout, float* sigma,
+                                                            int l, int k, const double* fro_acc, float* fro2,
+                                                            int max_sweeps, const int* cnt, int32_t* info) {
+  __shared__ double nrm[256];
+  const int b = blockIdx.x, t = threadIdx.x, wave = t >> 6, lane = t & 63;
+  const double* A = gA + (int64_t)b * l * l;
+  if (t == 0) {
+    if (fro2) fro2[b] = (float)fro_acc[b];
+    // the last sweep still found rotations to do
+    if (info && cnt[4 * b + (max_sweeps - 1) % 3] != 0) atomicOr(info + b, SVDC_FIT_JACOBI_CAPPED);
+  }
+  for (int j = wave; j < l; j += 4) {
+    double s = 0.0;
+    for (int r = lane; r < l; r += kWave) s += A[(int64_t)j * l + r] * A[(int64_t)j * l + r];
+    s = wave_sum(s);
+    if (lane == 0) nrm[j] = s;
+  }
+  __syncthreads();
+  double* wo = Wout + (int64_t)b * l * l;
+  for (int j = wave; j < l; j += 4) {
+    const double nj = nrm[j];
+    int rank = 0;
+    for (int i = lane; i < l; i += kWave) rank += (nrm[i] > nj || (nrm[i] == nj && i < j)) ? 1 : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) rank += __shfl_xor(rank, o, kWave);
+    if (lane == 0 && rank < k) sigma[(int64_t)b * k + rank] = (float)sqrt(nj);
+    const double inv = nj > 0.0 ? 1.0 / sqrt(nj) : 0.0;
+    for (int i = lane; i < l; i += kWave) wo[(int64_t)i * l + rank] = A[(int64_t)j * l + i] * inv;
   }
 }
 
@@ -761,10 +918,12 @@ bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan)
   plan->off_G = off; off = align_up(off + B * l * l * sizeof(double), 256);
   plan->off_Gp = off; off = align_up(off + B * kGramSlices * (size_t)l * l * sizeof(double), 256);
   plan->off_M = off; off = align_up(off + B * l * l * sizeof(double), 256);
-  plan->off_W = off; off = align_up(off + B * l * (l + 1) * sizeof(double), 256);   // Jacobi matrix when l > 138
+  plan->off_W = off; off = align_up(off + B * l * l * sizeof(double), 256);   // Jacobi matrix when l > 138
   // ||F||_F^2 accumulators (B doubles) followed by the status words (B int32, see svdcache_fit_status_offset)
   plan->off_misc = off; off = align_up(off + B * sizeof(double), 256);
   plan->off_info = off; off = align_up(off + B * sizeof(int32_t), 256);
+  // convergence counters of the Jacobi by column blocks (4 int32 per block); cleared together with the two above
+  plan->off_jcnt = off; off = align_up(off + B * 4 * sizeof(int32_t), 256);
   plan->mfma = fit_mfma_supported(s, l);
   plan->off_Qp = off;
   if (plan->mfma) off = align_up(off + fit_mfma_packed_q_bytes(s, l), 256);
@@ -814,16 +973,34 @@ void gram(const float* A, double* G, double* Gpart, int B, int rows, int l, hipS
   gram_reduce_kernel<<<dim3((unsigned)((ll + 255) / 256), B), 256, 0, st>>>(Gpart, G, nslice, ll);
 }
 
-int32_t chol_inv(double* G, double* Minv, int B, int l, int32_t* info, hipStream_t st, double* rdiag = nullptr) {
-  if (!Minv && l <= 128) {   // factor only: register blocked
-    if (l <= 64) chol_reg_kernel<4><<<B, 256, 0, st>>>(G, rdiag, l, 1e-14, info);
-    else chol_reg_kernel<8><<<B, 256, 0, st>>>(G, rdiag, l, 1e-14, info);
+// Scratch layout of the two-step factor inside the l x l float64 matrix M of a block (128 < l <= 256):
+// [0, l) reciprocal diagonal of L, [l] the diagonal shift, from 2 l on L21^T as [128][l - 128].
+inline int64_t chol2_ut_offset(int l) { return 2 * (int64_t)l; }
+
+// Cholesky factor of G + shift I in place (lower triangle; the upper triangle of each diagonal block is zeroed),
+// l <= 256.  scratch (block stride l * l doubles): receives the reciprocal diagonal in its first l entries per block
+// when not null; REQUIRED for l > 128, where it also holds the shift and L21^T (see above).
+int32_t chol_factor(double* G, int B, int l, int32_t* info, hipStream_t st, double* scratch) {
+  const int64_t ll = (int64_t)l * l;
+  if (l <= 128) {
+    const ChoShift sh{nullptr, 0, l};
+    const ChoUpdate up{nullptr, 0, 0, 0};
+    if (l <= 64) chol_reg_kernel<4><<<B, 256, 0, st>>>(G, ll, l, scratch, ll, l, 1e-14, info, sh, up);
+    else chol_reg_kernel<8><<<B, 256, 0, st>>>(G, ll, l, scratch, ll, l, 1e-14, info, sh, up);
     return SVDC_OK;
   }
-  const size_t bytes = (size_t)l * l * sizeof(double);
-  const int use_lds = bytes <= kLdsBudget;
-  if (use_lds && set_dyn_lds((const void*)chol_inv_kernel, bytes) != SVDC_OK) return SVDC_E_HIP;
-  chol_inv_kernel<<<B, 256, use_lds ? bytes : 0, st>>>(G, Minv, l, use_lds, 1e-14, info);
+  if (!scratch || l > 2 * kCholHead) return SVDC_E_SHAPE;
+  constexpr int H = kCholHead;   // two steps of 128 and l - 128 columns
+  const int m = l - H;
+  double* ut = scratch + chol2_ut_offset(l);
+  chol_reg_kernel<8><<<B, 256, 0, st>>>(G, ll, l, scratch, ll, H, 1e-14, info, ChoShift{scratch + l, ll, l},
+                                        ChoUpdate{nullptr, 0, 0, 0});
+  tri_solve_block_kernel<<<B, 128, 0, st>>>(G, scratch, ll, ut, ll, l);
+  const ChoShift sh2{scratch + l, ll, 0};
+  const ChoUpdate up2{ut, ll, m, H};
+  double* g22 = G + (int64_t)H * l + H;
+  if (m <= 64) chol_reg_kernel<4><<<B, 256, 0, st>>>(g22, ll, l, scratch + H, ll, m, 1e-14, info, sh2, up2);
+  else chol_reg_kernel<8><<<B, 256, 0, st>>>(g22, ll, l, scratch + H, ll, m, 1e-14, info, sh2, up2);
   return SVDC_OK;
 }
 
@@ -845,21 +1022,32 @@ int32_t rows_times_small(const float* In, const double* M, float* Out, int B, in
 // One pass leaves the result in Qout and is accurate to about eps32 * cond(Zin): enough to keep the
 // power iteration well conditioned.  two_pass repeats the step on the result (CholeskyQR2), giving
 // orthonormality at float32 round-off; the result is then back in Zin.
-// Out = In * L^-T with L the Cholesky factor of In^T In (left in G by chol_inv)
+// Out = In * L^-T with L the Cholesky factor of In^T In (left in G by chol_factor)
 int32_t cholqr_apply(const float* In, float* Out, double* G, double* M, int B, int rows, int l, int32_t* info,
                      hipStream_t st) {
+  const int64_t ll = (int64_t)l * l;
+  // M receives the reciprocal diagonal of L (its first l entries per block)
+  if (chol_factor(G, B, l, info, st, M) != SVDC_OK) return SVDC_E_HIP;
+  dim3 grid((rows + 255) / 256, B);
   if (l <= 128) {
-    // M receives the reciprocal diagonal of L (its first l entries per block)
-    if (chol_inv(G, nullptr, B, l, info, st, M) != SVDC_OK) return SVDC_E_HIP;
-    dim3 grid((rows + 255) / 256, B);
-    if (l <= 16) tri_solve_rows_kernel<16><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
-    else if (l <= 32) tri_solve_rows_kernel<32><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
-    else if (l <= 64) tri_solve_rows_kernel<64><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
-    else tri_solve_rows_kernel<128><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l);
+    if (l <= 16) tri_solve_rows_kernel<16><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l, l, l, ll, ll);
+    else if (l <= 32) tri_solve_rows_kernel<32><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l, l, l, ll, ll);
+    else if (l <= 64) tri_solve_rows_kernel<64><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l, l, l, ll, ll);
+    else tri_solve_rows_kernel<128><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l, l, l, ll, ll);
     return SVDC_OK;
   }
-  if (chol_inv(G, M, B, l, info, st) != SVDC_OK) return SVDC_E_HIP;
-  return rows_times_small(In, M, Out, B, rows, l, l, l, st);
+  // two-step factor: Out1 = In1 L11^-T;  Out2 = (In2 - Out1 L21^T) L22^-T
+  constexpr int H = kCholHead;
+  const int m = l - H;
+  tri_solve_rows_kernel<128><<<grid, 256, 0, st>>>(In, G, M, Out, rows, H, l, l, ll, ll);
+  rows_minus_product_kernel<<<dim3((rows + 63) / 64, (m + 63) / 64, B), 256, 0, st>>>(
+      In, Out, M + chol2_ut_offset(l), ll, rows, l);
+  const double* l22 = G + (int64_t)H * l + H;
+  if (m <= 16) tri_solve_rows_kernel<16><<<grid, 256, 0, st>>>(Out + H, l22, M + H, Out + H, rows, m, l, l, ll, ll);
+  else if (m <= 32) tri_solve_rows_kernel<32><<<grid, 256, 0, st>>>(Out + H, l22, M + H, Out + H, rows, m, l, l, ll, ll);
+  else if (m <= 64) tri_solve_rows_kernel<64><<<grid, 256, 0, st>>>(Out + H, l22, M + H, Out + H, rows, m, l, l, ll, ll);
+  else tri_solve_rows_kernel<128><<<grid, 256, 0, st>>>(Out + H, l22, M + H, Out + H, rows, m, l, l, ll, ll);
+  return SVDC_OK;
 }
 
 int32_t orth(float* Zin, float* Qout, double* G, double* Gpart, double* M, int B, int rows, int l, bool two_pass,
@@ -888,8 +1076,8 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   int32_t* info = (int32_t*)(ws + pl.off_info);
 
   const int64_t nq = (int64_t)B * s.D * l;
-  // fro accumulators and status words are adjacent 256-byte aligned areas: one fill clears both
-  zero_f64(misc, (int64_t)((pl.off_info - pl.off_misc) + align_up((size_t)B * sizeof(int32_t), 8)) / 8, st);
+  // fro accumulators, status words and Jacobi counters are adjacent 256-byte aligned areas: one fill clears them all
+  zero_f64(misc, (int64_t)((pl.off_jcnt - pl.off_misc) + align_up((size_t)B * 4 * sizeof(int32_t), 8)) / 8, st);
   // With power iterations the Gaussian test matrix (D x l) is used as it is: its columns are well conditioned
   // and every product F^T F Q is re-orthonormalised afterwards.  With none, the sketch is Z = F^T Omega with a
   // Gaussian Omega (N x l) -- the plain randomized range finder, exact when rank(F) <= l -- and Q <- orth(Z), two
@@ -936,35 +1124,44 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   // Rayleigh-Ritz on span(Q)
   project(true);
   gram(Y, G, Gp, B, s.N, l, st);
-  if (chol_inv(G, nullptr, B, l, info, st) != SVDC_OK) return SVDC_E_HIP;
+  if (chol_factor(G, B, l, info, st, l > 128 ? M : nullptr) != SVDC_OK) return SVDC_E_HIP;   // M: scratch until the Jacobi writes it
   if (want_fro && !fro_done) {
     const int rpg = 64;
     sumsq_kernel<T><<<dim3((s.N + rpg - 1) / rpg, B), 256, 0, st>>>(F, misc, s.N, s.D, s.ldf, s.block_stride, rpg);
   }
   const size_t mat = (size_t)l * (l + 1) * sizeof(double);
-  const bool a_in_lds = mat <= kLdsBudget;          // l <= 138
-  const size_t lds = a_in_lds ? mat : 0;
-  // elements of a column per lane, as the kernel derives them: lanes per pair = largest power of two <= 64 with
-  // pairs x lanes <= threads
-  const int npairs = ((l + 1) & ~1) / 2;
-  int tp = 64;
-  while (tp > 1 && tp * npairs > kJacobiThreads) tp >>= 1;
-  const int ne = (l + tp - 1) / tp;
-  auto launch = [&](auto kernel) -> int32_t {
-    if (set_dyn_lds((const void*)kernel, lds) != SVDC_OK) return SVDC_E_HIP;
-    kernel<<<B, kJacobiThreads, lds, st>>>(G, M, sigma, Wg, l, s.k, misc, fro2, pl.max_sweeps, info);
-    return SVDC_OK;
-  };
   int32_t jrc = SVDC_OK;
-  if (a_in_lds) {
-    if (ne <= 1) jrc = launch(jacobi_kernel<true, 1>);
-    else if (ne <= 2) jrc = launch(jacobi_kernel<true, 2>);
-    else if (ne <= 4) jrc = launch(jacobi_kernel<true, 4>);
-    else if (ne <= 8) jrc = launch(jacobi_kernel<true, 8>);
-    else if (ne <= 16) jrc = launch(jacobi_kernel<true, 16>);
-    else jrc = launch(jacobi_kernel<true, 0>);    // l = 129..138: 65 or more pairs leave 4 lanes per pair
-  } else {
-    jacobi_kernel<false, 0><<<B, kJacobiThreads, 0, st>>>(G, M, sigma, Wg, l, s.k, misc, fro2, pl.max_sweeps, info);
+  if (mat <= kLdsBudget) {                          // l <= 138: the whole matrix in the LDS of one workgroup
+    // elements of a column per lane, as the kernel derives them: lanes per pair = largest power of two <= 64 with
+    // pairs x lanes <= threads
+    const int npairs = ((l + 1) & ~1) / 2;
+    int tp = 64;
+    while (tp > 1 && tp * npairs > kJacobiThreads) tp >>= 1;
+    const int ne = (l + tp - 1) / tp;
+    auto launch = [&](auto kernel) -> int32_t {
+      if (set_dyn_lds((const void*)kernel, mat) != SVDC_OK) return SVDC_E_HIP;
+      kernel<<<B, kJacobiThreads, mat, st>>>(G, M, sigma, l, s.k, misc, fro2, pl.max_sweeps, info);
+      return SVDC_OK;
+    };
+    if (ne <= 1) jrc = launch(jacobi_kernel<1>);
+    else if (ne <= 2) jrc = launch(jacobi_kernel<2>);
+    else if (ne <= 4) jrc = launch(jacobi_kernel<4>);
+    else if (ne <= 8) jrc = launch(jacobi_kernel<8>);
+    else if (ne <= 16) jrc = launch(jacobi_kernel<16>);
+    else jrc = launch(jacobi_kernel<35>);           // l = 129..138: 65 or more pairs leave 4 lanes per pair
+  } else {                                          // by column blocks, one launch per round-robin step
+    const int nb = (l + kJbCols - 1) / kJbCols, nbe = (nb + 1) & ~1;
+    const size_t lds = (size_t)2 * kJbCols * (l + 1) * sizeof(double);
+    int* cnt = (int*)(ws + pl.off_jcnt);
+    auto sweeps = [&](auto kernel) -> int32_t {
+      if (set_dyn_lds((const void*)kernel, lds) != SVDC_OK) return SVDC_E_HIP;
+      for (int sweep = 0; sweep < pl.max_sweeps; ++sweep)
+        for (int step = 0; step < nbe - 1; ++step)
+          kernel<<<dim3(nbe / 2, B), kJacobiThreads, lds, st>>>(G, Wg, l, step, sweep, sweep == 0 && step == 0, cnt);
+      return SVDC_OK;
+    };
+    jrc = l <= 192 ? sweeps(jacobi_block_kernel<12>) : sweeps(jacobi_block_kernel<16>);
+    jacobi_finish_kernel<<<B, 256, 0, st>>>(Wg, M, sigma, l, s.k, misc, fro2, pl.max_sweeps, cnt, info);
   }
   if (jrc != SVDC_OK) return jrc;
   if (rows_times_small(Q, M, V, B, s.D, l, s.k, l, st) != SVDC_OK) return SVDC_E_HIP;

@@ -65,7 +65,7 @@ struct FitPlan {
   int q;          // power iterations
   uint64_t seed;
   int max_sweeps; // cap on the Jacobi sweeps
-  size_t off_Q, off_Z, off_Y, off_G, off_Gp, off_M, off_W, off_misc, off_info, off_Qp, total;
+  size_t off_Q, off_Z, off_Y, off_G, off_Gp, off_M, off_W, off_misc, off_info, off_jcnt, off_Qp, total;
   bool mfma;      // products with F on the matrix cores
 };
 bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan);
