@@ -250,7 +250,7 @@ __global__ __launch_bounds__(256) void rows_times_small_kernel(const float* __re
 }
 
 // ---------------------------------------------------------------------------
-// Register-blocked Cholesky factor for l <= 16 * BS (BS = 4 or 8), factor only:
+// Register-blocked Cholesky factor for l <= 16 * BS (BS = 4: l <= 64), factor only:
 // thread (ti, tj) of a 16 x 16 grid owns the BS x BS block (ti, tj) of the matrix
 // in registers; a wave owns four block columns, so the 16 threads that hold the
 // current column sit in one wave and the waves whose columns are finished only
@@ -261,10 +261,10 @@ __global__ __launch_bounds__(256) void rows_times_small_kernel(const float* __re
 //   G      in/out  [l x l] at row stride ld, block b at G + b * bstride: lower triangle = L with
 //                  G + shift I = L L^T, upper triangle zeroed
 //   rdiag  out     (nullable) 1 / L[i][i], block b at rdiag + b * rd_bstride
-// The matrix may be a diagonal block of a larger one that is factored in two steps (ChoShift tells both steps
-// which shift to use: the first computes it from the whole diagonal, diag_n >= l entries, and stores it; the
-// second, diag_n = 0, reads it), the second block then being A22 - L21 L21^T with L21^T = Ut [ku x l] at row
-// stride ldut.
+// The matrix may be a diagonal block of a larger one that is factored block by block (see chol_panel_kernel).
+// ChoShift tells every step which shift to use: the first computes it from the whole diagonal, diag_n >= l
+// entries, and stores it; the later ones, diag_n = 0, read it.  A later block is A_kk - L_k L_k^T with L_k the ku
+// finished columns of its rows, given transposed: Ut [ku x l] at row stride ldut.
 // ---------------------------------------------------------------------------
 struct ChoShift {
   double* slot;        // per block (stride slot_bstride): the shift, written when diag_n > 0, read otherwise
@@ -507,87 +507,117 @@ __global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* In, co
 }
 
 // ---------------------------------------------------------------------------
-// Two-step Cholesky factorisation for 128 < l <= 256, G = [A11 . ; A21 A22] with A11 128 x 128:
-//   L11 = chol(A11)  (chol_reg_kernel),  L21 = A21 L11^-T  (this kernel),  L22 = chol(A22 - L21 L21^T)  (chol_reg_kernel)
-// One workgroup per block, thread t solves row 128 + t of A21 in registers against L11 staged in LDS, in float64;
-// L21 goes back in place and, transposed ([128 x m], m = l - 128), to Ut for the update of A22 and for the
-// products with L21^T.
+// Blocked Cholesky factorisation for l > 64, left-looking over column blocks of 64: for block k at columns c0..c0+63
+//   L_kk = chol(A_kk - sum_{c < c0} L[k, c] L[k, c]^T)                     (chol_reg_kernel with its update)
+//   L_ik = (A_ik - sum_{c < c0} L[i, c] L[k, c]^T) L_kk^-T  for rows i below  (this kernel)
+// The finished columns are kept twice, as L in the lower triangle and as L^T in the upper one (G[c][r] = L[r][c]):
+// every product above then reads rows of the upper triangle, contiguous over the output index.
+// A workgroup takes 64 rows of the panel: all 256 threads form the 64 x 64 update (4 x 4 per thread, float64), then
+// 64 threads solve one row each against L_kk staged in LDS.
 // ---------------------------------------------------------------------------
-constexpr int kCholHead = 128;
+constexpr int kCholBlock = 64;
 
-__global__ __launch_bounds__(128) void tri_solve_block_kernel(double* G, const double* __restrict__ rdiag,
-                                                              int64_t rd_bstride, double* Ut, int64_t ut_bstride,
-                                                              int l) {
-  constexpr int H = kCholHead;
-  __shared__ double Lf[H * H];
+__global__ __launch_bounds__(256) void chol_panel_kernel(double* G, const double* __restrict__ rdiag,
+                                                         int64_t rd_bstride, int l, int c0) {
+  constexpr int H = kCholBlock, LT = H + 1;
+  __shared__ double T[H * LT];     // [row][j]
+  __shared__ double Lk[H * H];     // [j][i]
   __shared__ double rd[H];
-  const int b = blockIdx.x, t = threadIdx.x, m = l - H;
+  const int b = blockIdx.y, t = threadIdx.x;
   double* g = G + (int64_t)b * l * l;
-  for (int e = t; e < H * H; e += 128) Lf[e] = g[(int64_t)(e / H) * l + e % H];
-  rd[t] = rdiag[(int64_t)b * rd_bstride + t];
-  __syncthreads();
-  if (t >= m) return;
-  double* row = g + (int64_t)(H + t) * l;
-  double q[H];
-#pragma unroll
-  for (int j = 0; j < H; ++j) q[j] = row[j];
-#pragma unroll
-  for (int j = 0; j < H; ++j) {
-    double s = q[j];
-#pragma unroll
-    for (int i = 0; i < j; ++i) s -= q[i] * Lf[j * H + i];
-    q[j] = s * rd[j];
-  }
-  double* ut = Ut + (int64_t)b * ut_bstride;
-#pragma unroll
-  for (int j = 0; j < H; ++j) {
-    row[j] = q[j];
-    ut[(int64_t)j * m + t] = q[j];
-  }
-}
-
-// ---------------------------------------------------------------------------
-// Out[:, c0 + j] = In[:, c0 + j] - sum_{i < 128} Out[:, i] * Ut[i][j],  j < m: the middle step of Out = In L^-T for
-// the two-step factor, between the triangular solves with L11 (columns 0..127, already in Out) and with L22.
-// A workgroup takes 64 rows x 64 columns; Ut (float64) and the 128 leading columns of its rows are staged in LDS;
-// every thread accumulates a 4 x 4 block in float64.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void rows_minus_product_kernel(const float* __restrict__ In, float* Out,
-                                                                 const double* __restrict__ Ut,
-                                                                 int64_t ut_bstride, int rows, int l) {
-  constexpr int H = kCholHead, LT = H + 1;
-  __shared__ double Ms[H * 64];      // [i][j]
-  __shared__ float tile[64 * LT];    // [row][i]
-  const int b = blockIdx.z, t = threadIdx.x, m = l - H;
-  const float* in = In + (int64_t)b * rows * l;
-  float* out = Out + (int64_t)b * rows * l;
-  const double* ut = Ut + (int64_t)b * ut_bstride;
-  const int r0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
-  for (int idx = t; idx < H * 64; idx += 256) {
-    const int i = idx >> 6, j = idx & 63;
-    Ms[idx] = (j0 + j < m) ? ut[(int64_t)i * m + j0 + j] : 0.0;
-  }
-  for (int idx = t; idx < 64 * H; idx += 256) {
-    const int rr = idx / H, c = idx % H;
-    tile[rr * LT + c] = (r0 + rr < rows) ? out[(int64_t)(r0 + rr) * l + c] : 0.f;
-  }
-  __syncthreads();
+  const int r0 = c0 + H + blockIdx.x * H;          // first row of this workgroup
+  for (int e = t; e < H * H; e += 256) Lk[e] = g[(int64_t)(c0 + e / H) * l + c0 + e % H];
+  if (t < H) rd[t] = rdiag[(int64_t)b * rd_bstride + c0 + t];
   const int ty = t >> 4, tx = t & 15;
   double acc[4][4];
 #pragma unroll
   for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) acc[ii][jj] = 0.0;
-  for (int i = 0; i < H; ++i) {
+  int ri[4];
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii) ri[ii] = min(r0 + 4 * ty + ii, l - 1);
+#pragma unroll 4
+  for (int c = 0; c < c0; ++c) {
+    const double* gc = g + (int64_t)c * l;
     double av[4], bv[4];
 #pragma unroll
-    for (int ii = 0; ii < 4; ++ii) av[ii] = (double)tile[(4 * ty + ii) * LT + i];
+    for (int ii = 0; ii < 4; ++ii) av[ii] = gc[ri[ii]];
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) bv[jj] = Ms[i * 64 + tx + 16 * jj];
+    for (int jj = 0; jj < 4; ++jj) bv[jj] = gc[c0 + tx + 16 * jj];
 #pragma unroll
     for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) acc[ii][jj] += av[ii] * bv[jj];
+  }
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj)
+      T[(4 * ty + ii) * LT + tx + 16 * jj] = g[(int64_t)ri[ii] * l + c0 + tx + 16 * jj] - acc[ii][jj];
+  __syncthreads();
+  const int row = r0 + t;
+  if (t >= H || row >= l) return;
+  double q[H];
+#pragma unroll
+  for (int j = 0; j < H; ++j) q[j] = T[t * LT + j];
+#pragma unroll
+  for (int j = 0; j < H; ++j) {
+    double s = q[j];
+#pragma unroll
+    for (int i = 0; i < j; ++i) s -= q[i] * Lk[j * H + i];
+    q[j] = s * rd[j];
+  }
+#pragma unroll
+  for (int j = 0; j < H; ++j) {
+    g[(int64_t)row * l + c0 + j] = q[j];
+    g[(int64_t)(c0 + j) * l + row] = q[j];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Out[:, c0 + j] = In[:, c0 + j] - sum_{c < c0} Out[:, c] * L[c0 + j][c],  j < w: the update step of Out = In L^-T by
+// column blocks, between the triangular solves of the blocks (tri_solve_rows_kernel).  L^T is read from the upper
+// triangle of G.  A workgroup takes 64 rows x the block's columns and walks over c in chunks of 64, each staged in
+// LDS (the factor in float64, the rows of Out in float32); every thread accumulates a 4 x 4 block in float64.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rows_minus_product_kernel(const float* __restrict__ In, float* Out,
+                                                                 const double* __restrict__ G, int rows, int l,
+                                                                 int c0, int w) {
+  constexpr int H = kCholBlock, LT = H + 1;
+  __shared__ double Ms[H * H];      // [c][j]
+  __shared__ float tile[H * LT];    // [row][c]
+  const int b = blockIdx.y, t = threadIdx.x;
+  const float* in = In + (int64_t)b * rows * l;
+  float* out = Out + (int64_t)b * rows * l;
+  const double* g = G + (int64_t)b * l * l;
+  const int r0 = blockIdx.x * H;
+  const int ty = t >> 4, tx = t & 15;
+  double acc[4][4];
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) acc[ii][jj] = 0.0;
+  for (int cc = 0; cc < c0; cc += H) {
+    for (int idx = t; idx < H * H; idx += 256) {
+      const int i = idx >> 6, j = idx & 63;
+      Ms[idx] = j < w ? g[(int64_t)(cc + i) * l + c0 + j] : 0.0;
+      tile[i * LT + j] = (r0 + i < rows) ? out[(int64_t)(r0 + i) * l + cc + j] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int i = 0; i < H; ++i) {
+      double av[4], bv[4];
+#pragma unroll
+      for (int ii = 0; ii < 4; ++ii) av[ii] = (double)tile[(4 * ty + ii) * LT + i];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) bv[jj] = Ms[i * H + tx + 16 * jj];
+#pragma unroll
+      for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) acc[ii][jj] += av[ii] * bv[jj];
+    }
+    __syncthreads();
   }
 #pragma unroll
   for (int ii = 0; ii < 4; ++ii) {
@@ -595,8 +625,8 @@ __global__ __launch_bounds__(256) void rows_minus_product_kernel(const float* __
     if (row >= rows) continue;
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
-      const int j = j0 + tx + 16 * jj;
-      if (j < m) out[(int64_t)row * l + H + j] = (float)((double)in[(int64_t)row * l + H + j] - acc[ii][jj]);
+      const int j = tx + 16 * jj;
+      if (j < w) out[(int64_t)row * l + c0 + j] = (float)((double)in[(int64_t)row * l + c0 + j] - acc[ii][jj]);
     }
   }
 }
@@ -973,34 +1003,26 @@ void gram(const float* A, double* G, double* Gpart, int B, int rows, int l, hipS
   gram_reduce_kernel<<<dim3((unsigned)((ll + 255) / 256), B), 256, 0, st>>>(Gpart, G, nslice, ll);
 }
 
-// Scratch layout of the two-step factor inside the l x l float64 matrix M of a block (128 < l <= 256):
-// [0, l) reciprocal diagonal of L, [l] the diagonal shift, from 2 l on L21^T as [128][l - 128].
-inline int64_t chol2_ut_offset(int l) { return 2 * (int64_t)l; }
-
-// Cholesky factor of G + shift I in place (lower triangle; the upper triangle of each diagonal block is zeroed),
-// l <= 256.  scratch (block stride l * l doubles): receives the reciprocal diagonal in its first l entries per block
-// when not null; REQUIRED for l > 128, where it also holds the shift and L21^T (see above).
+// Cholesky factor of G + shift I in place, l <= 256: L in the lower triangle; for l > 64 the strict upper triangle
+// holds L^T outside the 64 x 64 diagonal blocks (whose upper halves are zeroed).  scratch (block stride l * l
+// doubles): receives the reciprocal diagonal in its first l entries per block when not null; REQUIRED for l > 64,
+// where entry [l] carries the diagonal shift from the first block's factorisation to the later ones.
 int32_t chol_factor(double* G, int B, int l, int32_t* info, hipStream_t st, double* scratch) {
   const int64_t ll = (int64_t)l * l;
-  if (l <= 128) {
-    const ChoShift sh{nullptr, 0, l};
-    const ChoUpdate up{nullptr, 0, 0, 0};
-    if (l <= 64) chol_reg_kernel<4><<<B, 256, 0, st>>>(G, ll, l, scratch, ll, l, 1e-14, info, sh, up);
-    else chol_reg_kernel<8><<<B, 256, 0, st>>>(G, ll, l, scratch, ll, l, 1e-14, info, sh, up);
+  constexpr int H = kCholBlock;
+  if (l <= H) {
+    chol_reg_kernel<4><<<B, 256, 0, st>>>(G, ll, l, scratch, ll, l, 1e-14, info, ChoShift{nullptr, 0, l},
+                                          ChoUpdate{nullptr, 0, 0, 0});
     return SVDC_OK;
   }
-  if (!scratch || l > 2 * kCholHead) return SVDC_E_SHAPE;
-  constexpr int H = kCholHead;   // two steps of 128 and l - 128 columns
-  const int m = l - H;
-  double* ut = scratch + chol2_ut_offset(l);
-  chol_reg_kernel<8><<<B, 256, 0, st>>>(G, ll, l, scratch, ll, H, 1e-14, info, ChoShift{scratch + l, ll, l},
-                                        ChoUpdate{nullptr, 0, 0, 0});
-  tri_solve_block_kernel<<<B, 128, 0, st>>>(G, scratch, ll, ut, ll, l);
-  const ChoShift sh2{scratch + l, ll, 0};
-  const ChoUpdate up2{ut, ll, m, H};
-  double* g22 = G + (int64_t)H * l + H;
-  if (m <= 64) chol_reg_kernel<4><<<B, 256, 0, st>>>(g22, ll, l, scratch + H, ll, m, 1e-14, info, sh2, up2);
-  else chol_reg_kernel<8><<<B, 256, 0, st>>>(g22, ll, l, scratch + H, ll, m, 1e-14, info, sh2, up2);
+  if (!scratch) return SVDC_E_NULL;
+  for (int c0 = 0; c0 < l; c0 += H) {
+    const int w = std::min(H, l - c0);
+    chol_reg_kernel<4><<<B, 256, 0, st>>>(G + (int64_t)c0 * l + c0, ll, l, scratch + c0, ll, w, 1e-14, info,
+                                          ChoShift{scratch + l, ll, c0 == 0 ? l : 0},
+                                          ChoUpdate{c0 ? G + c0 : nullptr, ll, l, c0});
+    if (c0 + w < l) chol_panel_kernel<<<dim3((l - c0 - w + H - 1) / H, B), 256, 0, st>>>(G, scratch, ll, l, c0);
+  }
   return SVDC_OK;
 }
 
@@ -1028,25 +1050,21 @@ int32_t cholqr_apply(const float* In, float* Out, double* G, double* M, int B, i
   const int64_t ll = (int64_t)l * l;
   // M receives the reciprocal diagonal of L (its first l entries per block)
   if (chol_factor(G, B, l, info, st, M) != SVDC_OK) return SVDC_E_HIP;
-  dim3 grid((rows + 255) / 256, B);
-  if (l <= 128) {
-    if (l <= 16) tri_solve_rows_kernel<16><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l, l, l, ll, ll);
-    else if (l <= 32) tri_solve_rows_kernel<32><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l, l, l, ll, ll);
-    else if (l <= 64) tri_solve_rows_kernel<64><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l, l, l, ll, ll);
-    else tri_solve_rows_kernel<128><<<grid, 256, 0, st>>>(In, G, M, Out, rows, l, l, l, ll, ll);
-    return SVDC_OK;
+  // by column blocks of 64: Out_j = (In_j - sum_{i < j} Out_i L_ji^T) L_jj^-T
+  constexpr int H = kCholBlock;
+  const dim3 grid((rows + 255) / 256, B);
+  for (int c0 = 0; c0 < l; c0 += H) {
+    const int w = std::min(H, l - c0);
+    const float* src = In;
+    if (c0 > 0) {
+      rows_minus_product_kernel<<<dim3((rows + H - 1) / H, B), 256, 0, st>>>(In, Out, G, rows, l, c0, w);
+      src = Out;
+    }
+    const double* lkk = G + (int64_t)c0 * l + c0;
+    if (w <= 16) tri_solve_rows_kernel<16><<<grid, 256, 0, st>>>(src + c0, lkk, M + c0, Out + c0, rows, w, l, l, ll, ll);
+    else if (w <= 32) tri_solve_rows_kernel<32><<<grid, 256, 0, st>>>(src + c0, lkk, M + c0, Out + c0, rows, w, l, l, ll, ll);
+    else tri_solve_rows_kernel<64><<<grid, 256, 0, st>>>(src + c0, lkk, M + c0, Out + c0, rows, w, l, l, ll, ll);
   }
-  // two-step factor: Out1 = In1 L11^-T;  Out2 = (In2 - Out1 L21^T) L22^-T
-  constexpr int H = kCholHead;
-  const int m = l - H;
-  tri_solve_rows_kernel<128><<<grid, 256, 0, st>>>(In, G, M, Out, rows, H, l, l, ll, ll);
-  rows_minus_product_kernel<<<dim3((rows + 63) / 64, (m + 63) / 64, B), 256, 0, st>>>(
-      In, Out, M + chol2_ut_offset(l), ll, rows, l);
-  const double* l22 = G + (int64_t)H * l + H;
-  if (m <= 16) tri_solve_rows_kernel<16><<<grid, 256, 0, st>>>(Out + H, l22, M + H, Out + H, rows, m, l, l, ll, ll);
-  else if (m <= 32) tri_solve_rows_kernel<32><<<grid, 256, 0, st>>>(Out + H, l22, M + H, Out + H, rows, m, l, l, ll, ll);
-  else if (m <= 64) tri_solve_rows_kernel<64><<<grid, 256, 0, st>>>(Out + H, l22, M + H, Out + H, rows, m, l, l, ll, ll);
-  else tri_solve_rows_kernel<128><<<grid, 256, 0, st>>>(Out + H, l22, M + H, Out + H, rows, m, l, l, ll, ll);
   return SVDC_OK;
 }
 
@@ -1124,7 +1142,7 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
   // Rayleigh-Ritz on span(Q)
   project(true);
   gram(Y, G, Gp, B, s.N, l, st);
-  if (chol_factor(G, B, l, info, st, l > 128 ? M : nullptr) != SVDC_OK) return SVDC_E_HIP;   // M: scratch until the Jacobi writes it
+  if (chol_factor(G, B, l, info, st, M) != SVDC_OK) return SVDC_E_HIP;   // M: scratch until the Jacobi writes it
   if (want_fro && !fro_done) {
     const int rpg = 64;
     sumsq_kernel<T><<<dim3((s.N + rpg - 1) / rpg, B), 256, 0, st>>>(F, misc, s.N, s.D, s.ldf, s.block_stride, rpg);
