@@ -137,15 +137,18 @@ __global__ __launch_bounds__(256) void fit_gemm_kernel(const T* __restrict__ F, 
 }
 
 // ---------------------------------------------------------------------------
-// G[l x l] += A^T A in float64, A float32 [rows x l]; rows split over grid.x
+// Partial Gram matrices A^T A in float64, A float32 [rows x l]; rows split over grid.x, 64 x 64 tiles of the lower
+// block triangle (tile row >= tile column) over grid.y: the factorisation that follows never reads the rest.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void gram_f64_kernel(const float* __restrict__ A, double* G, int rows, int l,
-                                                       int rows_per_slice, int ntile) {
+                                                       int rows_per_slice) {
   // staged as float64 so that each value is converted once, not once per use
   __shared__ double Ai[16][64];
   __shared__ double Aj[16][64];
   const int b = blockIdx.z;
-  const int ti = blockIdx.y / ntile, tj = blockIdx.y % ntile;
+  int ti = 0;
+  while ((ti + 1) * (ti + 2) / 2 <= (int)blockIdx.y) ++ti;
+  const int tj = blockIdx.y - ti * (ti + 1) / 2;
   const float* a = A + (int64_t)b * rows * l;
   double* g = G + ((int64_t)b * gridDim.x + blockIdx.x) * l * l;   // partial Gram matrix of this row slice
   const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
@@ -205,12 +208,14 @@ __global__ __launch_bounds__(256) void gram_f64_kernel(const float* __restrict__
   }
 }
 
-// G[b] = sum over the row slices of the partial Gram matrices, in slice order (no atomics: the same bits every run)
+// G[b] = sum over the row slices of the partial Gram matrices, in slice order (no atomics: the same bits every run);
+// lower block triangle only, like the partial matrices
 __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restrict__ part, double* G, int nslice,
-                                                          int64_t ll) {
+                                                          int l) {
   const int b = blockIdx.y;
+  const int64_t ll = (int64_t)l * l;
   const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (e >= ll) return;
+  if (e >= ll || (e % l) / 64 > (e / l) / 64) return;
   const double* p = part + (int64_t)b * nslice * ll + e;
   double s = 0.0;
   for (int i = 0; i < nslice; ++i) s += p[(int64_t)i * ll];
@@ -222,32 +227,6 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restri
 // matrix has numerical rank < l.  The shift keeps the factorisation going (the result stays orthonormal, directions
 // beyond the numerical rank are arbitrary) and the block's status word reports it.
 constexpr double kRankTol = 1e-12;
-
-// ---------------------------------------------------------------------------
-// Out[rows x m] (float32) = In[rows x l] (float32) * M[l x m] (float64, row stride ldm)
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void rows_times_small_kernel(const float* __restrict__ In,
-                                                               const double* __restrict__ M, float* Out,
-                                                               int rows, int l, int m, int ldm) {
-  __shared__ float tile[16][256];
-  const int b = blockIdx.y, t = threadIdx.x;
-  const float* in = In + (int64_t)b * rows * l;
-  const double* mm = M + (int64_t)b * l * ldm;
-  float* out = Out + (int64_t)b * rows * m;
-  const int r0 = blockIdx.x * 16;
-  for (int idx = t; idx < 16 * l; idx += 256) {
-    const int rr = idx / l, c = idx % l;
-    tile[rr][c] = (r0 + rr < rows) ? in[(int64_t)(r0 + rr) * l + c] : 0.f;
-  }
-  __syncthreads();
-  const int rr = t >> 4, jj = t & 15;
-  if (r0 + rr >= rows) return;
-  for (int j = jj; j < m; j += 16) {
-    double acc = 0.0;
-    for (int i = 0; i < l; ++i) acc += (double)tile[rr][i] * mm[(int64_t)i * ldm + j];
-    out[(int64_t)(r0 + rr) * m + j] = (float)acc;
-  }
-}
 
 // ---------------------------------------------------------------------------
 // Register-blocked Cholesky factor for l <= 16 * BS (BS = 4: l <= 64), factor only:
@@ -390,48 +369,81 @@ __global__ __launch_bounds__(256) void chol_reg_kernel(double* G, int64_t bstrid
 }
 
 // ---------------------------------------------------------------------------
-// Tiled version of rows_times_small_kernel for l <= 128: a workgroup computes a
-// 64-row x 64-column tile of Out = In * M with M (float64) and the rows of In
-// staged in LDS; every thread accumulates a 4 x 4 block in float64.
+// 64 x 64 tile of a product A[64 x K] (float32 rows) * Bm[K x 64] (float64), accumulated in float64, by one workgroup
+// of 256 threads (thread (ty, tx) of 16 x 16 owns rows 4 ty .. 4 ty + 3, columns tx + 16 jj).  The inner dimension is
+// walked in chunks of 32 staged in LDS; the next chunk's elements are fetched into registers before the current
+// one is multiplied, so their latency is hidden behind the arithmetic.
+//   load_a(r, k)  element (r, k) of A, 0 outside        load_b(k, j)  element (k, j) of Bm, 0 outside
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void rows_times_small_tiled_kernel(const float* __restrict__ In,
-                                                                     const double* __restrict__ M, float* Out,
-                                                                     int rows, int l, int m, int ldm) {
-  extern __shared__ double dyn_lds[];
-  double* Ms = dyn_lds;                                        // [l][64]
-  float* tile = reinterpret_cast<float*>(dyn_lds + l * 64);    // [64][l + 1]
-  const int lt = l + 1;
+constexpr int kTileK = 32;
+struct TileGemmLds {
+  double Bs[kTileK * 64];          // [k][j]
+  float As[64 * (kTileK + 1)];     // [r][k]
+};
+
+template <typename LoadA, typename LoadB>
+__device__ __forceinline__ void tile_gemm_64x64(int K, LoadA load_a, LoadB load_b, TileGemmLds& lds,
+                                                double (&acc)[4][4]) {
+  constexpr int LT = kTileK + 1;
+  const int t = threadIdx.x, ty = t >> 4, tx = t & 15;
+  // staging role of this thread: 8 elements of each operand per chunk
+  const int ar = t >> 5, ak = t & 31;          // A: rows ar + 8 e, column ak
+  const int bk = t >> 6, bj = t & 63;          // B: rows bk + 4 e, column bj
+  float ra[8];
+  double rb[8];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      ra[e] = load_a(ar + 8 * e, k0 + ak);
+      rb[e] = load_b(k0 + bk + 4 * e, bj);
+    }
+  };
+  fetch(0);
+  for (int k0 = 0; k0 < K; k0 += kTileK) {
+    if (k0 > 0) __syncthreads();               // the previous chunk has been read by everybody
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      lds.As[(ar + 8 * e) * LT + ak] = ra[e];
+      lds.Bs[(bk + 4 * e) * 64 + bj] = rb[e];
+    }
+    __syncthreads();
+    if (k0 + kTileK < K) fetch(k0 + kTileK);
+#pragma unroll 8
+    for (int i = 0; i < kTileK; ++i) {
+      double av[4], bv[4];
+#pragma unroll
+      for (int ii = 0; ii < 4; ++ii) av[ii] = (double)lds.As[(4 * ty + ii) * LT + i];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) bv[jj] = lds.Bs[i * 64 + tx + 16 * jj];
+#pragma unroll
+      for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) acc[ii][jj] += av[ii] * bv[jj];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Out[rows x m] (float32) = In[rows x l] (float32) * M[l x m] (float64, row stride ldm), 64 x 64 tiles.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rows_times_small_kernel(const float* __restrict__ In,
+                                                               const double* __restrict__ M, float* Out,
+                                                               int rows, int l, int m, int ldm) {
+  __shared__ TileGemmLds lds;
   const int b = blockIdx.z, t = threadIdx.x;
   const float* in = In + (int64_t)b * rows * l;
   const double* mm = M + (int64_t)b * l * ldm;
   float* out = Out + (int64_t)b * rows * m;
   const int r0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
-  for (int idx = t; idx < l * 64; idx += 256) {
-    const int i = idx >> 6, j = idx & 63;
-    Ms[idx] = (j0 + j < m) ? mm[(int64_t)i * ldm + j0 + j] : 0.0;
-  }
-  for (int idx = t; idx < 64 * l; idx += 256) {
-    const int rr = idx / l, c = idx % l;
-    tile[rr * lt + c] = (r0 + rr < rows) ? in[(int64_t)(r0 + rr) * l + c] : 0.f;
-  }
-  __syncthreads();
-  const int ty = t >> 4, tx = t & 15;
   double acc[4][4];
 #pragma unroll
   for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) acc[ii][jj] = 0.0;
-  for (int i = 0; i < l; ++i) {
-    double av[4], bv[4];
-#pragma unroll
-    for (int ii = 0; ii < 4; ++ii) av[ii] = (double)tile[(4 * ty + ii) * lt + i];
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) bv[jj] = Ms[i * 64 + tx + 16 * jj];
-#pragma unroll
-    for (int ii = 0; ii < 4; ++ii)
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) acc[ii][jj] += av[ii] * bv[jj];
-  }
+  tile_gemm_64x64(
+      l, [&](int r, int k) { return (r0 + r < rows && k < l) ? in[(int64_t)(r0 + r) * l + k] : 0.f; },
+      [&](int k, int j) { return (k < l && j0 + j < m) ? mm[(int64_t)k * ldm + j0 + j] : 0.0; }, lds, acc);
+  const int ty = t >> 4, tx = t & 15;
 #pragma unroll
   for (int ii = 0; ii < 4; ++ii) {
     const int row = r0 + 4 * ty + ii;
@@ -578,47 +590,26 @@ __global__ __launch_bounds__(256) void chol_panel_kernel(double* G, const double
 // ---------------------------------------------------------------------------
 // Out[:, c0 + j] = In[:, c0 + j] - sum_{c < c0} Out[:, c] * L[c0 + j][c],  j < w: the update step of Out = In L^-T by
 // column blocks, between the triangular solves of the blocks (tri_solve_rows_kernel).  L^T is read from the upper
-// triangle of G.  A workgroup takes 64 rows x the block's columns and walks over c in chunks of 64, each staged in
-// LDS (the factor in float64, the rows of Out in float32); every thread accumulates a 4 x 4 block in float64.
+// triangle of G.  A workgroup takes 64 rows x the block's columns (tile_gemm_64x64).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void rows_minus_product_kernel(const float* __restrict__ In, float* Out,
                                                                  const double* __restrict__ G, int rows, int l,
                                                                  int c0, int w) {
-  constexpr int H = kCholBlock, LT = H + 1;
-  __shared__ double Ms[H * H];      // [c][j]
-  __shared__ float tile[H * LT];    // [row][c]
+  __shared__ TileGemmLds lds;
   const int b = blockIdx.y, t = threadIdx.x;
   const float* in = In + (int64_t)b * rows * l;
   float* out = Out + (int64_t)b * rows * l;
   const double* g = G + (int64_t)b * l * l;
-  const int r0 = blockIdx.x * H;
-  const int ty = t >> 4, tx = t & 15;
+  const int r0 = blockIdx.x * 64;
   double acc[4][4];
 #pragma unroll
   for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) acc[ii][jj] = 0.0;
-  for (int cc = 0; cc < c0; cc += H) {
-    for (int idx = t; idx < H * H; idx += 256) {
-      const int i = idx >> 6, j = idx & 63;
-      Ms[idx] = j < w ? g[(int64_t)(cc + i) * l + c0 + j] : 0.0;
-      tile[i * LT + j] = (r0 + i < rows) ? out[(int64_t)(r0 + i) * l + cc + j] : 0.f;
-    }
-    __syncthreads();
-#pragma unroll 8
-    for (int i = 0; i < H; ++i) {
-      double av[4], bv[4];
-#pragma unroll
-      for (int ii = 0; ii < 4; ++ii) av[ii] = (double)tile[(4 * ty + ii) * LT + i];
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) bv[jj] = Ms[i * H + tx + 16 * jj];
-#pragma unroll
-      for (int ii = 0; ii < 4; ++ii)
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) acc[ii][jj] += av[ii] * bv[jj];
-    }
-    __syncthreads();
-  }
+  tile_gemm_64x64(
+      c0, [&](int r, int k) { return (r0 + r < rows && k < c0) ? out[(int64_t)(r0 + r) * l + k] : 0.f; },
+      [&](int k, int j) { return (k < c0 && j < w) ? g[(int64_t)k * l + c0 + j] : 0.0; }, lds, acc);
+  const int ty = t >> 4, tx = t & 15;
 #pragma unroll
   for (int ii = 0; ii < 4; ++ii) {
     const int row = r0 + 4 * ty + ii;
@@ -997,10 +988,10 @@ void gram(const float* A, double* G, double* Gpart, int B, int rows, int l, hipS
   int rows_per_slice = ((rows + kGramSlices - 1) / kGramSlices + 15) / 16 * 16;
   if (rows_per_slice < 64) rows_per_slice = 64;
   const int nslice = (rows + rows_per_slice - 1) / rows_per_slice;
-  dim3 grid(nslice, ntile * ntile, B);
-  gram_f64_kernel<<<grid, 256, 0, st>>>(A, Gpart, rows, l, rows_per_slice, ntile);
+  dim3 grid(nslice, ntile * (ntile + 1) / 2, B);
+  gram_f64_kernel<<<grid, 256, 0, st>>>(A, Gpart, rows, l, rows_per_slice);
   const int64_t ll = (int64_t)l * l;
-  gram_reduce_kernel<<<dim3((unsigned)((ll + 255) / 256), B), 256, 0, st>>>(Gpart, G, nslice, ll);
+  gram_reduce_kernel<<<dim3((unsigned)((ll + 255) / 256), B), 256, 0, st>>>(Gpart, G, nslice, l);
 }
 
 // Cholesky factor of G + shift I in place, l <= 256: L in the lower triangle; for l > 64 the strict upper triangle
@@ -1029,14 +1020,8 @@ int32_t chol_factor(double* G, int B, int l, int32_t* info, hipStream_t st, doub
 // Out[rows x m] = In[rows x l] * M[l x m]
 int32_t rows_times_small(const float* In, const double* M, float* Out, int B, int rows, int l, int m, int ldm,
                          hipStream_t st) {
-  if (l <= 128) {
-    const size_t bytes = (size_t)l * 64 * sizeof(double) + (size_t)64 * (l + 1) * sizeof(float);
-    if (set_dyn_lds((const void*)rows_times_small_tiled_kernel, bytes) != SVDC_OK) return SVDC_E_HIP;
-    dim3 grid((rows + 63) / 64, (m + 63) / 64, B);
-    rows_times_small_tiled_kernel<<<grid, 256, bytes, st>>>(In, M, Out, rows, l, m, ldm);
-  } else {
-    rows_times_small_kernel<<<dim3((rows + 15) / 16, B), 256, 0, st>>>(In, M, Out, rows, l, m, ldm);
-  }
+  dim3 grid((rows + 63) / 64, (m + 63) / 64, B);
+  rows_times_small_kernel<<<grid, 256, 0, st>>>(In, M, Out, rows, l, m, ldm);
   return SVDC_OK;
 }
 
