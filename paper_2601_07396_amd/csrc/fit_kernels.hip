@@ -724,13 +724,12 @@ __device__ __forceinline__ void round_robin_pair(int le, int step, int group, in
 }
 
 // Whole matrix in LDS (l <= 138), one workgroup per block.
-template <int NE>
-__global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const double* __restrict__ Lfac, double* Wout, float* sigma,
+template <int NE, int NT>
+__global__ __launch_bounds__(NT) void jacobi_kernel(const double* __restrict__ Lfac, double* Wout, float* sigma,
                                                      int l, int k, const double* fro_acc, float* fro2,
                                                      int max_sweeps, int32_t* info) {
   extern __shared__ double dyn_lds[];
   __shared__ double nrm[256];
-  constexpr int NT = kJacobiThreads;
   __shared__ int s_rot, s_big;
   const int b = blockIdx.x, t = threadIdx.x;
   const double* Lf = Lfac + (int64_t)b * l * l;
@@ -1138,20 +1137,21 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
     // elements of a column per lane, as the kernel derives them: lanes per pair = largest power of two <= 64 with
     // pairs x lanes <= threads
     const int npairs = ((l + 1) & ~1) / 2;
+    const int nt = npairs > 32 ? 1024 : kJacobiThreads;
     int tp = 64;
-    while (tp > 1 && tp * npairs > kJacobiThreads) tp >>= 1;
+    while (tp > 1 && tp * npairs > nt) tp >>= 1;
     const int ne = (l + tp - 1) / tp;
     auto launch = [&](auto kernel) -> int32_t {
       if (set_dyn_lds((const void*)kernel, mat) != SVDC_OK) return SVDC_E_HIP;
-      kernel<<<B, kJacobiThreads, mat, st>>>(G, M, sigma, l, s.k, misc, fro2, pl.max_sweeps, info);
+      kernel<<<B, nt, mat, st>>>(G, M, sigma, l, s.k, misc, fro2, pl.max_sweeps, info);
       return SVDC_OK;
     };
-    if (ne <= 1) jrc = launch(jacobi_kernel<1>);
-    else if (ne <= 2) jrc = launch(jacobi_kernel<2>);
-    else if (ne <= 4) jrc = launch(jacobi_kernel<4>);
-    else if (ne <= 8) jrc = launch(jacobi_kernel<8>);
-    else if (ne <= 16) jrc = launch(jacobi_kernel<16>);
-    else jrc = launch(jacobi_kernel<35>);           // l = 129..138: 65 or more pairs leave 4 lanes per pair
+    if (nt == 1024) {
+      if (ne <= 8) jrc = launch(jacobi_kernel<8, 1024>);       // l <= 128: 16 lanes per pair
+      else jrc = launch(jacobi_kernel<18, 1024>);              // l = 129..138: 8 lanes per pair
+    } else if (ne <= 1) jrc = launch(jacobi_kernel<1, kJacobiThreads>);
+    else if (ne <= 2) jrc = launch(jacobi_kernel<2, kJacobiThreads>);
+    else jrc = launch(jacobi_kernel<4, kJacobiThreads>);
   } else {                                          // by column blocks, one launch per round-robin step
     const int nb = (l + kJbCols - 1) / kJbCols, nbe = (nb + 1) & ~1;
     const size_t lds = (size_t)2 * kJbCols * (l + 1) * sizeof(double);
