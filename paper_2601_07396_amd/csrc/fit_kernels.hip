@@ -659,8 +659,8 @@ constexpr int kJacobiThreads = 512;
 // One plane rotation of the one-sided Jacobi: the tp lanes of a pair (lane gl of tp) make columns ap and aq (length
 // l, in LDS) orthogonal.  A lane handles exactly NE elements of a column, NE >= ceil(l / tp), so the element loops
 // unroll with a fixed trip count, their LDS loads are issued together, and the elements stay in registers between
-// the dot products and the rotation.  Lane 0 of the pair counts the rotation in *rot, and in *big when the cosine of
-// the angle between the columns was above 3.2e-5.
+// the dot products and the rotation.  A rotation sets *rot, and *big when the cosine of the angle between the
+// columns was above 3.2e-5 (flags in registers: the caller publishes them once per sweep).
 template <int NE>
 __device__ __forceinline__ void jacobi_rotate(double* ap, double* aq, int l, int gl, int tp, int* rot, int* big) {
   double al = 0.0, be = 0.0, ga = 0.0;
@@ -709,10 +709,8 @@ __device__ __forceinline__ void jacobi_rotate(double* ap, double* aq, int l, int
         aq[r] = sn * xs[e] + cs * ys[e];
       }
     }
-    if (gl == 0) {
-      atomicAdd(rot, 1);
-      if (ga * ga > 1e-9 * al * be) atomicAdd(big, 1);
-    }
+    *rot = 1;
+    if (ga * ga > 1e-9 * al * be) *big = 1;
   }
 }
 
@@ -722,6 +720,23 @@ __device__ __forceinline__ void round_robin_pair(int le, int step, int group, in
   if (group == 0) { *p = le - 1; *q = step % (le - 1); }
   else { *p = (step + group) % (le - 1); *q = (step + (le - 1) - group) % (le - 1); }
 }
+
+// The same pairing followed step by step without divisions (a remainder by a run-time divisor costs about as many
+// instructions as the rest of a rotation): start(le, group) gives the pair of step 0, next() that of the step after.
+struct RoundRobin {
+  int p, q, m;
+  bool fixed;   // group 0 keeps player le - 1
+  __device__ __forceinline__ void start(int le, int group) {
+    m = le - 1;
+    fixed = group == 0;
+    p = fixed ? le - 1 : group;      // group <= le / 2 - 1 < m
+    q = fixed ? 0 : m - group;
+  }
+  __device__ __forceinline__ void next() {
+    if (!fixed) p = p + 1 == m ? 0 : p + 1;
+    q = q + 1 == m ? 0 : q + 1;
+  }
+};
 
 // Whole matrix in LDS (l <= 138), one workgroup per block.
 template <int NE, int NT>
@@ -753,12 +768,17 @@ __global__ __launch_bounds__(NT) void jacobi_kernel(const double* __restrict__ L
   for (int sweep = 0; sweep < max_sweeps; ++sweep) {
     if (t == 0) { s_rot = 0; s_big = 0; }
     __syncthreads();
+    int my_rot = 0, my_big = 0;
+    RoundRobin rr;
+    rr.start(le, active ? group : 0);
     for (int step = 0; step < le - 1; ++step) {
-      int p = 0, q = 0;
-      if (active) round_robin_pair(le, step, group, &p, &q);
-      if (active && p < l && q < l) jacobi_rotate<NE>(A + (int64_t)p * la, A + (int64_t)q * la, l, gl, tp, &s_rot, &s_big);
+      if (active && rr.p < l && rr.q < l) jacobi_rotate<NE>(A + rr.p * la, A + rr.q * la, l, gl, tp, &my_rot, &my_big);
+      rr.next();
       __syncthreads();
     }
+    if (my_rot && gl == 0) atomicOr(&s_rot, 1);
+    if (my_big && gl == 0) atomicOr(&s_big, 1);
+    __syncthreads();
     const int rot = s_rot, big = s_big;
     __syncthreads();
     // Done when a sweep rotates nothing -- or only pairs whose cosine was below 3.2e-5: cyclic Jacobi converges
@@ -833,12 +853,16 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_block_kernel(const doub
   if (t == 0) { s_rot = 0; s_big = 0; }
   __syncthreads();
   const int group = t / TP, gl = t % TP;
+  int my_rot = 0, my_big = 0;
+  RoundRobin rr;
+  rr.start(NC, group);
   for (int st = 0; st < NC - 1; ++st) {
-    int p, q;
-    round_robin_pair(NC, st, group, &p, &q);
-    if (gcol(p) < l && gcol(q) < l) jacobi_rotate<NE>(A + p * la, A + q * la, l, gl, TP, &s_rot, &s_big);
+    if (gcol(rr.p) < l && gcol(rr.q) < l) jacobi_rotate<NE>(A + rr.p * la, A + rr.q * la, l, gl, TP, &my_rot, &my_big);
+    rr.next();
     __syncthreads();
   }
+  if (my_big && gl == 0) atomicAdd(&s_big, 1);
+  __syncthreads();
   for (int idx = t; idx < NC * l; idx += NT) {
     const int c = idx / l, r = idx % l, gc = gcol(c);
     if (gc < l) ga[(int64_t)gc * l + r] = A[c * la + r];
