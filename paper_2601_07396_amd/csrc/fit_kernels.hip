@@ -646,30 +646,35 @@ __device__ __forceinline__ double dpp_move(double x) {
 // Sum over aligned groups of min(width, 16) lanes (width a power of two); every lane of a group gets the sum.
 // Lane i adds lane i^1, then i^2 (quad permutations); once the quads are uniform, mirroring a half row (i <-> 7-i)
 // and then a row (i <-> 15-i) brings in the other quads.
-__device__ __forceinline__ double row_sum(double x, int width) {
-  if (width >= 2) x += dpp_move<0xB1>(x);    // quad_perm [1,0,3,2]
-  if (width >= 4) x += dpp_move<0x4E>(x);    // quad_perm [2,3,0,1]
-  if (width >= 8) x += dpp_move<0x141>(x);   // row_half_mirror
-  if (width >= 16) x += dpp_move<0x140>(x);  // row_mirror
+template <int WIDTH>
+__device__ __forceinline__ double row_sum(double x) {
+  if constexpr (WIDTH >= 2) x += dpp_move<0xB1>(x);    // quad_perm [1,0,3,2]
+  if constexpr (WIDTH >= 4) x += dpp_move<0x4E>(x);    // quad_perm [2,3,0,1]
+  if constexpr (WIDTH >= 8) x += dpp_move<0x141>(x);   // row_half_mirror
+  if constexpr (WIDTH >= 16) x += dpp_move<0x140>(x);  // row_mirror
   return x;
 }
 
 constexpr int kJacobiThreads = 512;
 
-// One plane rotation of the one-sided Jacobi: the tp lanes of a pair (lane gl of tp) make columns ap and aq (length
-// l, in LDS) orthogonal.  A lane handles exactly NE elements of a column, NE >= ceil(l / tp), so the element loops
+// One plane rotation of the one-sided Jacobi: the TP lanes of a pair (lane gl of TP, a compile-time power of two:
+// with a run-time width every level of the sums below is a branch) make columns ap and aq (length l, in LDS)
+// orthogonal.  A lane handles exactly NE elements of a column, NE >= ceil(l / tp), so the element loops
 // unroll with a fixed trip count, their LDS loads are issued together, and the elements stay in registers between
 // the dot products and the rotation.  A rotation sets *rot, and *big when the cosine of the angle between the
 // columns was above 3.2e-5 (flags in registers: the caller publishes them once per sweep).
-template <int NE>
-__device__ __forceinline__ void jacobi_rotate(double* ap, double* aq, int l, int gl, int tp, int* rot, int* big) {
+// PAD: the columns are stored with TP * NE elements, zero beyond l (zeros stay zero under a rotation), so that no
+// load or store needs a bounds check (each conditional store is a branch).
+template <int NE, int TP, bool PAD>
+__device__ __forceinline__ void jacobi_rotate(double* ap, double* aq, int l, int gl, int* rot, int* big) {
+  constexpr int tp = TP;
   double al = 0.0, be = 0.0, ga = 0.0;
   double xs[NE], ys[NE];
 #pragma unroll
   for (int e = 0; e < NE; ++e) {
     const int r = gl + e * tp;
-    xs[e] = r < l ? ap[r] : 0.0;
-    ys[e] = r < l ? aq[r] : 0.0;
+    xs[e] = (PAD || r < l) ? ap[r] : 0.0;
+    ys[e] = (PAD || r < l) ? aq[r] : 0.0;
   }
 #pragma unroll
   for (int e = 0; e < NE; ++e) {
@@ -677,7 +682,8 @@ __device__ __forceinline__ void jacobi_rotate(double* ap, double* aq, int l, int
   }
   // sums over the tp lanes of the pair: inside a row of 16 lanes with data-parallel-primitive moves (no LDS
   // round trip as in a shuffle), across rows with shuffles
-  al = row_sum(al, tp); be = row_sum(be, tp); ga = row_sum(ga, tp);
+  al = row_sum<TP>(al); be = row_sum<TP>(be); ga = row_sum<TP>(ga);
+#pragma unroll
   for (int o = tp >> 1; o >= 16; o >>= 1) {
     al += __shfl_xor(al, o, kWave);
     be += __shfl_xor(be, o, kWave);
@@ -704,7 +710,7 @@ __device__ __forceinline__ void jacobi_rotate(double* ap, double* aq, int l, int
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
       const int r = gl + e * tp;
-      if (r < l) {
+      if (PAD || r < l) {
         ap[r] = cs * xs[e] - sn * ys[e];
         aq[r] = sn * xs[e] + cs * ys[e];
       }
@@ -739,7 +745,7 @@ struct RoundRobin {
 };
 
 // Whole matrix in LDS (l <= 138), one workgroup per block.
-template <int NE, int NT>
+template <int NE, int NT, int TP, bool PAD>
 __global__ __launch_bounds__(NT) void jacobi_kernel(const double* __restrict__ Lfac, double* Wout, float* sigma,
                                                      int l, int k, const double* fro_acc, float* fro2,
                                                      int max_sweeps, int32_t* info) {
@@ -748,20 +754,23 @@ __global__ __launch_bounds__(NT) void jacobi_kernel(const double* __restrict__ L
   __shared__ int s_rot, s_big;
   const int b = blockIdx.x, t = threadIdx.x;
   const double* Lf = Lfac + (int64_t)b * l * l;
-  const int la = l + 1;   // column stride, padded so that concurrently rotated columns spread over the LDS banks
+  // column stride: odd, so that concurrently rotated columns spread over the LDS banks
+  const int la = PAD ? TP * NE + 1 : l + 1;
   double* A = dyn_lds;    // column-major
   for (int idx = t; idx < l * l; idx += NT) {
     const int r = idx / l, c = idx % l;
     A[c * la + r] = (c <= r) ? Lf[idx] : 0.0;   // A = L
   }
+  if (PAD) {
+    const int np = la - l;
+    for (int idx = t; idx < l * np; idx += NT) A[(idx / np) * la + l + idx % np] = 0.0;
+  }
   if (t == 0 && fro2) fro2[b] = (float)fro_acc[b];
   __syncthreads();
 
   const int le = (l + 1) & ~1;         // players in the round-robin (one dummy if l is odd)
-  const int npairs = le / 2;           // <= 69
-  int tp = 64;
-  while (tp > 1 && tp * npairs > NT) tp >>= 1;
-  const int group = t / tp, gl = t % tp;
+  const int npairs = le / 2;           // <= 69; the host picks TP with TP * npairs <= NT
+  const int group = t / TP, gl = t % TP;
   const bool active = group < npairs;
 
   bool converged = false;
@@ -772,7 +781,7 @@ __global__ __launch_bounds__(NT) void jacobi_kernel(const double* __restrict__ L
     RoundRobin rr;
     rr.start(le, active ? group : 0);
     for (int step = 0; step < le - 1; ++step) {
-      if (active && rr.p < l && rr.q < l) jacobi_rotate<NE>(A + rr.p * la, A + rr.q * la, l, gl, tp, &my_rot, &my_big);
+      if (active && rr.p < l && rr.q < l) jacobi_rotate<NE, TP, PAD>(A + rr.p * la, A + rr.q * la, l, gl, &my_rot, &my_big);
       rr.next();
       __syncthreads();
     }
@@ -833,7 +842,7 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_block_kernel(const doub
   const int nb = (l + kJbCols - 1) / kJbCols, nbe = (nb + 1) & ~1;
   int bi, bj;
   round_robin_pair(nbe, step, blockIdx.x, &bi, &bj);
-  const int la = l + 1;
+  constexpr int la = TP * NE + 1;                       // columns padded with zeros to TP * NE elements
   double* A = dyn_lds;                                  // [NC][la]
   double* ga = gA + (int64_t)b * l * l;
   // global column of local column c (>= l: none)
@@ -850,6 +859,7 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_block_kernel(const doub
       if (gc < l) A[c * la + r] = ga[(int64_t)gc * l + r];
     }
   }
+  for (int idx = t; idx < NC * (la - l); idx += NT) A[(idx / (la - l)) * la + l + idx % (la - l)] = 0.0;
   if (t == 0) { s_rot = 0; s_big = 0; }
   __syncthreads();
   const int group = t / TP, gl = t % TP;
@@ -857,7 +867,7 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_block_kernel(const doub
   RoundRobin rr;
   rr.start(NC, group);
   for (int st = 0; st < NC - 1; ++st) {
-    if (gcol(rr.p) < l && gcol(rr.q) < l) jacobi_rotate<NE>(A + rr.p * la, A + rr.q * la, l, gl, TP, &my_rot, &my_big);
+    if (gcol(rr.p) < l && gcol(rr.q) < l) jacobi_rotate<NE, TP, true>(A + rr.p * la, A + rr.q * la, l, gl, &my_rot, &my_big);
     rr.next();
     __syncthreads();
   }
@@ -1155,30 +1165,26 @@ int32_t run_fit_typed(const svdc_shape& s, const FitPlan& pl, const T* F, float*
     const int rpg = 64;
     sumsq_kernel<T><<<dim3((s.N + rpg - 1) / rpg, B), 256, 0, st>>>(F, misc, s.N, s.D, s.ldf, s.block_stride, rpg);
   }
-  const size_t mat = (size_t)l * (l + 1) * sizeof(double);
   int32_t jrc = SVDC_OK;
-  if (mat <= kLdsBudget) {                          // l <= 138: the whole matrix in the LDS of one workgroup
-    // elements of a column per lane, as the kernel derives them: lanes per pair = largest power of two <= 64 with
-    // pairs x lanes <= threads
+  if ((size_t)l * (l + 1) * sizeof(double) <= kLdsBudget) {   // l <= 138: the whole matrix in the LDS of one workgroup
+    // lanes per pair: the largest power of two <= 64 with pairs x lanes <= threads (1024 threads from 33 pairs on),
+    // and the elements of a column per lane that follow from it; columns padded to lanes x elements up to l = 128
     const int npairs = ((l + 1) & ~1) / 2;
-    const int nt = npairs > 32 ? 1024 : kJacobiThreads;
-    int tp = 64;
-    while (tp > 1 && tp * npairs > nt) tp >>= 1;
-    const int ne = (l + tp - 1) / tp;
-    auto launch = [&](auto kernel) -> int32_t {
+    auto launch = [&](auto kernel, int nt, int la) -> int32_t {
+      const size_t mat = (size_t)l * la * sizeof(double);
       if (set_dyn_lds((const void*)kernel, mat) != SVDC_OK) return SVDC_E_HIP;
       kernel<<<B, nt, mat, st>>>(G, M, sigma, l, s.k, misc, fro2, pl.max_sweeps, info);
       return SVDC_OK;
     };
-    if (nt == 1024) {
-      if (ne <= 8) jrc = launch(jacobi_kernel<8, 1024>);       // l <= 128: 16 lanes per pair
-      else jrc = launch(jacobi_kernel<18, 1024>);              // l = 129..138: 8 lanes per pair
-    } else if (ne <= 1) jrc = launch(jacobi_kernel<1, kJacobiThreads>);
-    else if (ne <= 2) jrc = launch(jacobi_kernel<2, kJacobiThreads>);
-    else jrc = launch(jacobi_kernel<4, kJacobiThreads>);
+    constexpr int NT = kJacobiThreads;
+    if (npairs <= 8) jrc = launch(jacobi_kernel<1, NT, 64, true>, NT, 65);             // l <= 16
+    else if (npairs <= 16) jrc = launch(jacobi_kernel<1, NT, 32, true>, NT, 33);       // l <= 32
+    else if (npairs <= 32) jrc = launch(jacobi_kernel<4, NT, 16, true>, NT, 65);       // l <= 64
+    else if (npairs <= 64) jrc = launch(jacobi_kernel<8, 1024, 16, true>, 1024, 129);  // l <= 128
+    else jrc = launch(jacobi_kernel<18, 1024, 8, false>, 1024, l + 1);                 // l <= 138
   } else {                                          // by column blocks, one launch per round-robin step
     const int nb = (l + kJbCols - 1) / kJbCols, nbe = (nb + 1) & ~1;
-    const size_t lds = (size_t)2 * kJbCols * (l + 1) * sizeof(double);
+    const size_t lds = (size_t)2 * kJbCols * (l <= 192 ? 193 : 257) * sizeof(double);   // columns of 16 lanes x 12 or 16
     int* cnt = (int*)(ws + pl.off_jcnt);
     auto sweeps = [&](auto kernel) -> int32_t {
       if (set_dyn_lds((const void*)kernel, lds) != SVDC_OK) return SVDC_E_HIP;
