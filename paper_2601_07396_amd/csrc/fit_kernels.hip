@@ -818,10 +818,11 @@ __global__ __launch_bounds__(NT) void jacobi_kernel(const double* __restrict__ L
 // The same Jacobi for 138 < l <= 256, where the matrix (l x l float64) no longer fits the LDS of one workgroup: by
 // column blocks.  The columns form nb = ceil(l / 32) blocks; a round-robin over the blocks pairs every block with
 // every other once per sweep, and the pairs of one round-robin step are disjoint, so one launch handles a step with
-// one workgroup per block pair: it brings the pair's 64 columns into LDS, runs one full round-robin of rotations over
-// them (63 steps of 32 concurrent pairs, 16 lanes per pair) and writes them back.  The working matrix A lives in
-// global memory column by column (A[c * l + r]); the very first launch reads its columns from the Cholesky factor
-// instead.  Convergence is tracked per block in three rotating counters cnt[b][0..2]: the launches of sweep s count
+// one workgroup per block pair: it brings the pair's 64 columns into LDS, rotates every pair across the two blocks
+// (32 rounds of 32 concurrent pairs, 16 lanes per pair; in the first step of a sweep every pair among the 64 columns,
+// 63 rounds, which covers the pairs inside the blocks) and writes them back: each pair of columns once per sweep.
+// The working matrix A lives in global memory column by column (A[c * l + r]); the very first launch reads its
+// columns from the Cholesky factor instead.  Convergence is tracked per block in three rotating counters cnt[b][0..2]: the launches of sweep s count
 // the rotations with a cosine above 3.2e-5 in cnt[s % 3], return at once when cnt[(s - 1) % 3] is zero (the previous
 // sweep found nothing: converged, and it stays so because nothing is counted any more), and the first launch of the
 // sweep clears cnt[(s + 1) % 3] for the next one.  jacobi_finish_kernel then sorts and normalises.
@@ -864,12 +865,24 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_block_kernel(const doub
   __syncthreads();
   const int group = t / TP, gl = t % TP;
   int my_rot = 0, my_big = 0;
-  RoundRobin rr;
-  rr.start(NC, group);
-  for (int st = 0; st < NC - 1; ++st) {
-    if (gcol(rr.p) < l && gcol(rr.q) < l) jacobi_rotate<NE, TP, true>(A + rr.p * la, A + rr.q * la, l, gl, &my_rot, &my_big);
-    rr.next();
-    __syncthreads();
+  if (step == 0) {
+    // first step of a sweep: every pair among the 64 columns, i.e. also the pairs inside each block (every block is
+    // in exactly one pair of step 0)
+    RoundRobin rr;
+    rr.start(NC, group);
+    for (int st = 0; st < NC - 1; ++st) {
+      if (gcol(rr.p) < l && gcol(rr.q) < l) jacobi_rotate<NE, TP, true>(A + rr.p * la, A + rr.q * la, l, gl, &my_rot, &my_big);
+      rr.next();
+      __syncthreads();
+    }
+  } else {
+    // later steps: only the pairs across the two blocks, column i of the first with column (i + st) mod 32 of the second
+    const bool ok_p = gcol(group) < l;
+    for (int st = 0; st < kJbCols; ++st) {
+      const int q = kJbCols + ((group + st) & (kJbCols - 1));
+      if (ok_p && gcol(q) < l) jacobi_rotate<NE, TP, true>(A + group * la, A + q * la, l, gl, &my_rot, &my_big);
+      __syncthreads();
+    }
   }
   if (my_big && gl == 0) atomicAdd(&s_big, 1);
   __syncthreads();
