@@ -460,12 +460,12 @@ __global__ __launch_bounds__(256) void rows_times_small_kernel(const float* __re
 // Out = In * L^-T by forward substitution, one thread per row:
 //   q_j = (z_j - sum_{i<j} q_i L[j][i]) / L[j][j]
 // L (float64 Cholesky factor, lower) and the reciprocals of its diagonal are read
-// at wave-uniform addresses (scalar loads); the row lives in registers.  Replaces the
-// explicit inverse factor plus a product for l <= LMAX.
-// ---------------------------------------------------------------------------
+// from LDS as broadcasts; the row lives in registers.  l <= LMAX <= 64: wider factors are applied block by block
+// (cholqr_apply).
 // The l columns may be a column range of wider rows (row stride ld_io, In and Out already offset to the range's
 // first column) and L a diagonal block of a larger factor (row stride ldl, block b at Lfac + b * l_bstride).  In may
 // be the same buffer as Out: a thread reads its whole row before it writes.
+// ---------------------------------------------------------------------------
 template <int LMAX>
 __global__ __launch_bounds__(256) void tri_solve_rows_kernel(const float* In, const double* __restrict__ Lfac,
                                                              const double* __restrict__ rdiag, float* Out,

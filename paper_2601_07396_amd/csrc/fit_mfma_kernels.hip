@@ -1,10 +1,11 @@
-// Matrix-core versions of the two products with F in the basis fit (bf16 features):
+// Matrix-core versions of the two products with F in the basis fit (bf16 features as they are; float32 features
+// split into bf16 high + low parts on the fly, see FPiece and fit_backproject_f32_kernel):
 //   project      Y[N x l] = F * Q           Q stationary in registers (fit_project_mfma_kernel), or, for wide sketches
 //                                           and split operands, shared through LDS by waves that split the rows
 //                                           (fit_project_rows_kernel)
 //   backproject  Z[D x l] += F[rows, :]^T * Y[rows, :]         (Z accumulators stationary in registers)
-// Both stream F exactly once, in 16- or 32-row tiles, on v_mfma_f32_16x16x32_bf16
-// (operand layouts: see mfma_kernels.hip).  A projection that is followed by a back-projection hands Y over as
+// Both stream F exactly once per column range of the sketch (one range up to width 128, two up to 256), in 16- or
+// 32-row tiles, on v_mfma_f32_16x16x32_bf16 (operand layouts: see mfma_kernels.hip).  A projection that is followed by a back-projection hands Y over as
 // packed bf16 operand words (pack_y_word) instead of float32 rows; the last projection of a fit writes float32 rows
 // for the Gram matrix.  backproject stores Z directly when one workgroup covers all rows of a block and otherwise
 // combines the partial results of its row groups with float atomics (it clears Z itself).

@@ -384,12 +384,22 @@ def test_fit_basis_wide_sketch_low_rank_features(dtype, k, p, rank):
 
 @pytest.mark.parametrize("dtype,N,D,k,p", [(torch.bfloat16, 600, 512, 96, 0), (torch.float32, 600, 512, 96, 0),
                                             (torch.bfloat16, 700, 384, 128, 0), (torch.float32, 520, 256, 128, 0),
-                                            (torch.bfloat16, 450, 640, 100, 29), (torch.float32, 300, 320, 65, 64)],
-                         ids=["bf16-l192", "f32-l192", "bf16-l256", "f32-l256", "bf16-l129", "f32-l129"])
-def test_fit_basis_sketch_widths_129_to_256(dtype, N, D, k, p):
-    """Sketch widths 129..256 (the default oversampling p = k puts every rank 65..128 there, config 5's k = 128
+                                            (torch.bfloat16, 450, 640, 100, 29), (torch.float32, 300, 320, 65, 64),
+                                            (torch.bfloat16, 300, 256, 50, 50), (torch.float32, 300, 200, 40, 37),
+                                            (torch.float32, 260, 384, 65, 65), (torch.bfloat16, 420, 256, 75, 75),
+                                            (torch.bfloat16, 139, 256, 70, 70), (torch.float32, 400, 512, 100, 100),
+                                            (torch.bfloat16, 500, 384, 110, 113)],
+                         ids=["bf16-l192", "f32-l192", "bf16-l256", "f32-l256", "bf16-l129", "f32-l129",
+                              "bf16-l100", "f32-l77-general", "f32-l130", "bf16-l150", "bf16-l139", "f32-l200",
+                              "bf16-l223"])
+def test_fit_basis_sketch_widths_65_to_256(dtype, N, D, k, p):
+    """Sketch widths 65..256 (the default oversampling p = k puts every rank 33..128 there, config 5's k = 128
     at l = 256): singular values, captured energy, orthonormality and the leading subspace against the exact
-    truncated SVD, for both storage types."""
+    truncated SVD, for both storage types.  The widths are chosen to hit every branch of the l x l chain: a ragged
+    last column block of the Cholesky factorisation and of its application (100 = 64 + 36, 130 = 2 x 64 + 2,
+    200 = 3 x 64 + 8), the widest matrix that the single-workgroup Jacobi takes (129..138), and, for the Jacobi by
+    column blocks, an odd number of blocks (139 and 150: five, 200 and 223: seven -- one block sits out per step)
+    as well as an even one (192: six, 256: eight)."""
     store = "f32" if dtype == torch.float32 else "bf16"
     # full power-law spectrum sigma_i = 10 / i over all min(N, D) directions: no flat noise bulk at rank k, so a
     # few power iterations converge (sigma_{l+1} / sigma_k is about k / l)
