@@ -478,6 +478,35 @@ def test_fit_status_words():
     assert 0 < pkg.svdcache_fit_status_offset(shape) < pkg.svdcache_workspace_bytes(shape)
 
 
+def test_fit_status_words_column_block_jacobi():
+    """The sweep-cap flag of the Jacobi by column blocks (sketch widths above 138), whose convergence is tracked in
+    three rotating counters on the device: caps of 1, 2 and 3 sweeps end on each of the three counters and are all
+    too few for a 192 x 192 factor (flag set, the call still succeeds and V is orthonormal); the default cap converges
+    (no flag) and gives the basis of the exact decomposition."""
+    g = torch.Generator().manual_seed(78)
+    N, D, k = 500, 256, 96
+    r_all = min(N, D)
+    blocks = []
+    for _ in range(2):
+        left = torch.linalg.qr(torch.randn(N, r_all, generator=g, dtype=torch.float64))[0]
+        right = torch.linalg.qr(torch.randn(D, r_all, generator=g, dtype=torch.float64))[0]
+        blocks.append(((left * (10.0 / torch.arange(1, r_all + 1, dtype=torch.float64))) @ right.T).to(torch.bfloat16))
+    F = torch.stack(blocks).contiguous()
+    for cap in (1, 2, 3):
+        V, _, _, status = pkg.fit_basis(F.to(DEV), k, q=8, max_sweeps=cap, return_status=True)
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [pkg.SVDC_FIT_JACOBI_CAPPED] * 2, f"cap {cap}: {status.cpu().tolist()}"
+        Vd = V.double().cpu()
+        for b in range(2):
+            # columns of L after any number of rotations, normalised: unit norm, but not yet orthogonal
+            assert (Vd[b].norm(dim=0) - 1).abs().max() < 1e-3
+    V, sigma, fro2, status = pkg.fit_basis(F.to(DEV), k, q=8, return_status=True)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0]
+    for b in range(2):
+        _fit_checks(F[b], V[b], sigma[b], fro2[b], k, "bf16")
+
+
 def test_fit_basis_flux_block_full_size():
     """One FLUX-shaped block (4608 x 3072 bf16, k = 32) at full size against the exact decomposition."""
     wl = WORKLOADS["flux1"]
