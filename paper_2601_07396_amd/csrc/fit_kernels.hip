@@ -137,33 +137,77 @@ __global__ __launch_bounds__(256) void fit_gemm_kernel(const T* __restrict__ F, 
 }
 
 // ---------------------------------------------------------------------------
+// 64 x 64 x (4 K4) float64 product on the matrix cores (v_mfma_f64_16x16x4_f64), shared by the Gram matrices and the
+// small tile products below.  Both operands sit in LDS with the contraction index as the row:
+//   As[k][i] (row stride LDA), Bs[k][j] (row stride LDB),  acc += sum_k As[k][i] * Bs[k][j].
+// Wave w of four takes the 32 x 32 quadrant (w / 2, w % 2) as 2 x 2 tiles of 16 x 16.  Lane layout of the
+// instruction (checked on the device with one-hot operands):
+//   A operand: lane -> A[i = lane % 16][k = lane / 16]        B operand: lane -> B[k = lane / 16][j = lane % 16]
+//   D: lane, v  -> D[i = 4 v + lane / 16][j = lane % 16]
+// so a lane reads As[4 k4 + lane / 16][i0 + lane % 16]: 16 consecutive doubles per group of 16 lanes, and with a row
+// stride of 80 doubles the two groups of a half wave fall into different halves of the LDS banks.
+// ---------------------------------------------------------------------------
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+constexpr int kM64Stride = 80;
+
+struct Quadrant {
+  int i0, j0, m, kq;   // first row / column of the wave's quadrant, lane % 16, lane / 16
+  __device__ __forceinline__ Quadrant() {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    i0 = 32 * (wave >> 1); j0 = 32 * (wave & 1); m = lane & 15; kq = lane >> 4;
+  }
+  // row and column (inside the 64 x 64 tile) of element v of accumulator tile (a, b)
+  __device__ __forceinline__ int row(int a, int v) const { return i0 + 16 * a + 4 * v + kq; }
+  __device__ __forceinline__ int col(int b) const { return j0 + 16 * b + m; }
+};
+
+template <int K4>
+__device__ __forceinline__ void mfma64_accumulate(const double* As, const double* Bs, const Quadrant& q,
+                                                  f64x4 (&acc)[2][2]) {
+#pragma unroll
+  for (int k4 = 0; k4 < K4; ++k4) {
+    const double* ar = As + (4 * k4 + q.kq) * kM64Stride + q.i0 + q.m;
+    const double* br = Bs + (4 * k4 + q.kq) * kM64Stride + q.j0 + q.m;
+    const double a0 = ar[0], a1 = ar[16], b0 = br[0], b1 = br[16];
+    acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
+    acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
+    acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
+    acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Partial Gram matrices A^T A in float64, A float32 [rows x l]; rows split over grid.x, 64 x 64 tiles of the lower
 // block triangle (tile row >= tile column) over grid.y: the factorisation that follows never reads the rest.
+// 16 rows per step, staged in LDS as float64 (each value converted once); the next step's rows are fetched into
+// registers while the current ones are multiplied.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void gram_f64_kernel(const float* __restrict__ A, double* G, int rows, int l,
                                                        int rows_per_slice) {
-  // staged as float64 so that each value is converted once, not once per use
-  __shared__ double Ai[16][64];
-  __shared__ double Aj[16][64];
+  __shared__ double Ai[16 * kM64Stride];
+  __shared__ double Aj[16 * kM64Stride];
   const int b = blockIdx.z;
   int ti = 0;
   while ((ti + 1) * (ti + 2) / 2 <= (int)blockIdx.y) ++ti;
   const int tj = blockIdx.y - ti * (ti + 1) / 2;
   const float* a = A + (int64_t)b * rows * l;
   double* g = G + ((int64_t)b * gridDim.x + blockIdx.x) * l * l;   // partial Gram matrix of this row slice
-  const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+  const int t = threadIdx.x;
   const int rbeg = blockIdx.x * rows_per_slice, rend = min(rows, rbeg + rows_per_slice);
-  double acc[4][4];
+  const Quadrant q;
+  f64x4 acc[2][2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+    for (int y = 0; y < 2; ++y) acc[x][y] = f64x4{0.0, 0.0, 0.0, 0.0};
   const bool vec = (l & 3) == 0;
-  for (int r0 = rbeg; r0 < rend; r0 += 16) {
-    const int rr = t >> 4, c = (t & 15) * 4;
+  const int rr = t >> 4, c = (t & 15) * 4;
+  const int ci = ti * 64 + c, cj = tj * 64 + c;
+  float vi[4], vj[4];
+  auto fetch = [&](int r0) {
     const int64_t r = r0 + rr;
-    const int ci = ti * 64 + c, cj = tj * 64 + c;
-    float vi[4] = {0.f, 0.f, 0.f, 0.f}, vj[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { vi[e] = 0.f; vj[e] = 0.f; }
     if (r < rend) {
       if (vec) {
         if (ci < l) *reinterpret_cast<float4*>(vi) = *reinterpret_cast<const float4*>(a + r * l + ci);
@@ -176,36 +220,31 @@ __global__ __launch_bounds__(256) void gram_f64_kernel(const float* __restrict__
         }
       }
     }
+  };
+  if (rbeg < rend) fetch(rbeg);
+  for (int r0 = rbeg; r0 < rend; r0 += 16) {
+    if (r0 > rbeg) __syncthreads();             // the previous step has been read by everybody
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      Ai[rr][c + e] = (double)vi[e];
-      Aj[rr][c + e] = (double)vj[e];
+      Ai[rr * kM64Stride + c + e] = (double)vi[e];
+      Aj[rr * kM64Stride + c + e] = (double)vj[e];
     }
     __syncthreads();
-#pragma unroll
-    for (int rr2 = 0; rr2 < 16; ++rr2) {
-      double x[4], y[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) x[i] = Ai[rr2][ty * 4 + i];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) y[j] = Aj[rr2][tx * 4 + j];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] += x[i] * y[j];
-    }
-    __syncthreads();
+    if (r0 + 16 < rend) fetch(r0 + 16);
+    mfma64_accumulate<4>(Ai, Aj, q, acc);
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int gi = ti * 64 + ty * 4 + i;
-    if (gi >= l) continue;
+  for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int gj = tj * 64 + tx * 4 + j;
-      if (gj < l) g[(int64_t)gi * l + gj] = acc[i][j];
+    for (int v = 0; v < 4; ++v) {
+      const int gi = ti * 64 + q.row(x, v);
+      if (gi >= l) continue;
+#pragma unroll
+      for (int y = 0; y < 2; ++y) {
+        const int gj = tj * 64 + q.col(y);
+        if (gj < l) g[(int64_t)gi * l + gj] = acc[x][y][v];
+      }
     }
-  }
 }
 
 // G[b] = sum over the row slices of the partial Gram matrices, in slice order (no atomics: the same bits every run);
@@ -369,23 +408,23 @@ __global__ __launch_bounds__(256) void chol_reg_kernel(double* G, int64_t bstrid
 }
 
 // ---------------------------------------------------------------------------
-// 64 x 64 tile of a product A[64 x K] (float32 rows) * Bm[K x 64] (float64), accumulated in float64, by one workgroup
-// of 256 threads (thread (ty, tx) of 16 x 16 owns rows 4 ty .. 4 ty + 3, columns tx + 16 jj).  The inner dimension is
-// walked in chunks of 32 staged in LDS; the next chunk's elements are fetched into registers before the current
-// one is multiplied, so their latency is hidden behind the arithmetic.
+// 64 x 64 tile of a product A[64 x K] (float32 rows) * Bm[K x 64] (float64), accumulated in float64 on the matrix
+// cores by one workgroup of 256 threads (mfma64_accumulate).  The inner dimension is walked in chunks of 32 staged in
+// LDS as float64, A transposed to [k][r]; the next chunk's elements are fetched into registers before the current one
+// is multiplied, so their latency is hidden behind the arithmetic.
 //   load_a(r, k)  element (r, k) of A, 0 outside        load_b(k, j)  element (k, j) of Bm, 0 outside
+//   emit(r, j, x) called for every element (r, j) of the tile that this lane holds
 // ---------------------------------------------------------------------------
 constexpr int kTileK = 32;
 struct TileGemmLds {
-  double Bs[kTileK * 64];          // [k][j]
-  float As[64 * (kTileK + 1)];     // [r][k]
+  double Bs[kTileK * kM64Stride];          // [k][j]
+  double As[kTileK * (kM64Stride + 1)];    // [k][r], odd stride: the transposing stores of a wave spread over the banks
 };
 
-template <typename LoadA, typename LoadB>
-__device__ __forceinline__ void tile_gemm_64x64(int K, LoadA load_a, LoadB load_b, TileGemmLds& lds,
-                                                double (&acc)[4][4]) {
-  constexpr int LT = kTileK + 1;
-  const int t = threadIdx.x, ty = t >> 4, tx = t & 15;
+template <typename LoadA, typename LoadB, typename Emit>
+__device__ __forceinline__ void tile_gemm_64x64(int K, LoadA load_a, LoadB load_b, TileGemmLds& lds, Emit emit) {
+  constexpr int LA = kM64Stride + 1;
+  const int t = threadIdx.x;
   // staging role of this thread: 8 elements of each operand per chunk
   const int ar = t >> 5, ak = t & 31;          // A: rows ar + 8 e, column ak
   const int bk = t >> 6, bj = t & 63;          // B: rows bk + 4 e, column bj
@@ -398,29 +437,39 @@ __device__ __forceinline__ void tile_gemm_64x64(int K, LoadA load_a, LoadB load_
       rb[e] = load_b(k0 + bk + 4 * e, bj);
     }
   };
+  const Quadrant q;
+  f64x4 acc[2][2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 2; ++y) acc[x][y] = f64x4{0.0, 0.0, 0.0, 0.0};
   fetch(0);
   for (int k0 = 0; k0 < K; k0 += kTileK) {
     if (k0 > 0) __syncthreads();               // the previous chunk has been read by everybody
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      lds.As[(ar + 8 * e) * LT + ak] = ra[e];
-      lds.Bs[(bk + 4 * e) * 64 + bj] = rb[e];
+      lds.As[ak * LA + ar + 8 * e] = (double)ra[e];
+      lds.Bs[(bk + 4 * e) * kM64Stride + bj] = rb[e];
     }
     __syncthreads();
     if (k0 + kTileK < K) fetch(k0 + kTileK);
-#pragma unroll 8
-    for (int i = 0; i < kTileK; ++i) {
-      double av[4], bv[4];
 #pragma unroll
-      for (int ii = 0; ii < 4; ++ii) av[ii] = (double)lds.As[(4 * ty + ii) * LT + i];
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) bv[jj] = lds.Bs[i * 64 + tx + 16 * jj];
-#pragma unroll
-      for (int ii = 0; ii < 4; ++ii)
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) acc[ii][jj] += av[ii] * bv[jj];
+    for (int k4 = 0; k4 < kTileK / 4; ++k4) {
+      const double* arow = lds.As + (4 * k4 + q.kq) * LA + q.i0 + q.m;
+      const double* brow = lds.Bs + (4 * k4 + q.kq) * kM64Stride + q.j0 + q.m;
+      const double a0 = arow[0], a1 = arow[16], b0 = brow[0], b1 = brow[16];
+      acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
     }
   }
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+#pragma unroll
+      for (int y = 0; y < 2; ++y) emit(q.row(x, v), q.col(y), acc[x][y][v]);
 }
 
 // ---------------------------------------------------------------------------
@@ -430,30 +479,17 @@ __global__ __launch_bounds__(256) void rows_times_small_kernel(const float* __re
                                                                const double* __restrict__ M, float* Out,
                                                                int rows, int l, int m, int ldm) {
   __shared__ TileGemmLds lds;
-  const int b = blockIdx.z, t = threadIdx.x;
+  const int b = blockIdx.z;
   const float* in = In + (int64_t)b * rows * l;
   const double* mm = M + (int64_t)b * l * ldm;
   float* out = Out + (int64_t)b * rows * m;
   const int r0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
-  double acc[4][4];
-#pragma unroll
-  for (int ii = 0; ii < 4; ++ii)
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) acc[ii][jj] = 0.0;
   tile_gemm_64x64(
       l, [&](int r, int k) { return (r0 + r < rows && k < l) ? in[(int64_t)(r0 + r) * l + k] : 0.f; },
-      [&](int k, int j) { return (k < l && j0 + j < m) ? mm[(int64_t)k * ldm + j0 + j] : 0.0; }, lds, acc);
-  const int ty = t >> 4, tx = t & 15;
-#pragma unroll
-  for (int ii = 0; ii < 4; ++ii) {
-    const int row = r0 + 4 * ty + ii;
-    if (row >= rows) continue;
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-      const int j = j0 + tx + 16 * jj;
-      if (j < m) out[(int64_t)row * m + j] = (float)acc[ii][jj];
-    }
-  }
+      [&](int k, int j) { return (k < l && j0 + j < m) ? mm[(int64_t)k * ldm + j0 + j] : 0.0; }, lds,
+      [&](int r, int j, double x) {
+        if (r0 + r < rows && j0 + j < m) out[(int64_t)(r0 + r) * m + j0 + j] = (float)x;
+      });
 }
 
 // ---------------------------------------------------------------------------
@@ -596,30 +632,18 @@ __global__ __launch_bounds__(256) void rows_minus_product_kernel(const float* __
                                                                  const double* __restrict__ G, int rows, int l,
                                                                  int c0, int w) {
   __shared__ TileGemmLds lds;
-  const int b = blockIdx.y, t = threadIdx.x;
+  const int b = blockIdx.y;
   const float* in = In + (int64_t)b * rows * l;
   float* out = Out + (int64_t)b * rows * l;
   const double* g = G + (int64_t)b * l * l;
   const int r0 = blockIdx.x * 64;
-  double acc[4][4];
-#pragma unroll
-  for (int ii = 0; ii < 4; ++ii)
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) acc[ii][jj] = 0.0;
   tile_gemm_64x64(
       c0, [&](int r, int k) { return (r0 + r < rows && k < c0) ? out[(int64_t)(r0 + r) * l + k] : 0.f; },
-      [&](int k, int j) { return (k < c0 && j < w) ? g[(int64_t)k * l + c0 + j] : 0.0; }, lds, acc);
-  const int ty = t >> 4, tx = t & 15;
-#pragma unroll
-  for (int ii = 0; ii < 4; ++ii) {
-    const int row = r0 + 4 * ty + ii;
-    if (row >= rows) continue;
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-      const int j = tx + 16 * jj;
-      if (j < w) out[(int64_t)row * l + c0 + j] = (float)((double)in[(int64_t)row * l + c0 + j] - acc[ii][jj]);
-    }
-  }
+      [&](int k, int j) { return (k < c0 && j < w) ? g[(int64_t)k * l + c0 + j] : 0.0; }, lds,
+      [&](int r, int j, double x) {
+        const int64_t at = (int64_t)(r0 + r) * l + c0 + j;
+        if (r0 + r < rows && j < w) out[at] = (float)((double)in[at] - x);
+      });
 }
 
 // ---------------------------------------------------------------------------
