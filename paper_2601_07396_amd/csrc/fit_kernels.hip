@@ -268,14 +268,16 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restri
 constexpr double kRankTol = 1e-12;
 
 // ---------------------------------------------------------------------------
-// Register-blocked Cholesky factor for l <= 16 * BS (BS = 4: l <= 64), factor only:
-// thread (ti, tj) of a 16 x 16 grid owns the BS x BS block (ti, tj) of the matrix
-// in registers; a wave owns four block columns, so the 16 threads that hold the
-// current column sit in one wave and the waves whose columns are finished only
-// pass the barrier.  Right-looking: per column c the owners publish the column
-// through LDS (double buffered, one barrier per column) and every thread at or
-// below the diagonal and right of c applies the rank-1 update to its block; only
-// the block column that contains c needs per-element conditions.
+// Register-blocked Cholesky factor for l <= 64, factor only: thread (ti, tj) of a 16 x 16 grid owns the 4 x 4 block
+// (ti, tj) of the matrix in registers; a wave owns four block columns.  Right-looking by panels of 4 columns (one
+// block column), two barriers per panel:
+//   the thread on the diagonal factors its 4 x 4 block and publishes it,
+//   the threads below it in the block column (the same wave) solve their blocks against it, X = B L_d^-T, and publish
+//   the panel (64 rows x 4),
+//   every thread below or on the diagonal and right of the panel subtracts the rank-4 product of the panel rows of
+//   its block row and of its block column.
+// (One column at a time, with the column published through LDS and a barrier per column, took three times as long:
+// the per-column chain of barrier, pivot, reciprocal square root and rank-1 update is what costs, not the flops.)
 //   G      in/out  [l x l] at row stride ld, block b at G + b * bstride: lower triangle = L with
 //                  G + shift I = L L^T, upper triangle zeroed
 //   rdiag  out     (nullable) 1 / L[i][i], block b at rdiag + b * rd_bstride
@@ -299,8 +301,10 @@ template <int BS>
 __global__ __launch_bounds__(256) void chol_reg_kernel(double* G, int64_t bstride, int ld, double* rdiag,
                                                        int64_t rd_bstride, int l, double rel_shift, int32_t* info,
                                                        ChoShift sh, ChoUpdate up) {
+  static_assert(BS == 4, "4 x 4 blocks");
   constexpr int LM = 16 * BS;          // padded matrix size
-  __shared__ double colbuf[2][LM];
+  __shared__ double panel[LM][BS];     // the current block column of L, rows below its diagonal block
+  __shared__ double dblk[BS][BS];      // its diagonal block: strict lower part, reciprocals of the diagonal on the diagonal
   __shared__ double s_shift;
   const int b = blockIdx.x, t = threadIdx.x, tj = t >> 4, ti = t & 15;
   double* g = G + (int64_t)b * bstride;
@@ -331,7 +335,8 @@ __global__ __launch_bounds__(256) void chol_reg_kernel(double* G, int64_t bstrid
     }
   if (up.Ut && ti >= tj) {   // a -= L21 L21^T, from the transposed factor (rows of Ut are contiguous over i)
     const double* ut = up.Ut + (int64_t)b * up.bstride;
-    for (int kk = 0; kk < up.ku; ++kk) {
+#pragma unroll 8
+    for (int kk = 0; kk < up.ku; ++kk) {   // ku is a multiple of 64; unrolled so that the loads of several steps are in flight
       double ui[BS], uj[BS];
 #pragma unroll
       for (int ii = 0; ii < BS; ++ii) ui[ii] = (BS * ti + ii < l) ? ut[(int64_t)kk * up.ldut + BS * ti + ii] : 0.0;
@@ -343,55 +348,65 @@ __global__ __launch_bounds__(256) void chol_reg_kernel(double* G, int64_t bstrid
         for (int jj = 0; jj < BS; ++jj) a[ii][jj] -= ui[ii] * uj[jj];
     }
   }
-  const bool below = ti > tj;          // every element of the block is below the diagonal
+  const double pivot_floor = s_shift * (kRankTol / rel_shift);
   bool dependent = false;
-  for (int c = 0; c < l; ++c) {
-    double* col = colbuf[c & 1];
-    const int cb = c / BS, cq = c % BS;
-    if (tj == cb && ti >= tj) {        // publish rows BS ti .. BS ti + BS - 1 of column c
+  const int nbk = (l + BS - 1) / BS;
+  for (int cb = 0; cb < nbk; ++cb) {
+    if (ti == cb && tj == cb) {        // factor the diagonal block in place (lower part), publish it
 #pragma unroll
-      for (int ii = 0; ii < BS; ++ii) {
-        double v = a[ii][0];
+      for (int q = 0; q < BS; ++q) {
+        dependent |= (BS * cb + q < l) && a[q][q] < pivot_floor;
+        const double piv2 = fmax(a[q][q], 1e-300);
+        // 1 / sqrt(piv2): hardware estimate refined by two Newton steps (an exact sqrt and a division per
+        // column would dominate this kernel)
+        double rs = __builtin_amdgcn_rsq(piv2);
+        rs = rs * (1.5 - 0.5 * piv2 * rs * rs);
+        rs = rs * (1.5 - 0.5 * piv2 * rs * rs);
+        a[q][q] = piv2 * rs;
+        dblk[q][q] = rs;
 #pragma unroll
-        for (int q = 1; q < BS; ++q) v = (q == cq) ? a[ii][q] : v;
-        col[BS * ti + ii] = v;
+        for (int i = q + 1; i < BS; ++i) {
+          a[i][q] *= rs;
+          dblk[i][q] = a[i][q];
+        }
+#pragma unroll
+        for (int j = q + 1; j < BS; ++j)
+#pragma unroll
+          for (int i = j; i < BS; ++i) a[i][j] -= a[i][q] * a[j][q];
       }
     }
     __syncthreads();
-    if (tj < cb || ti < tj) continue;  // block column finished, or block above the diagonal
-    const double piv2 = fmax(col[c], 1e-300);
-    dependent |= col[c] < s_shift * (kRankTol / rel_shift);
-    // 1 / sqrt(piv2): hardware estimate refined by two Newton steps (an exact sqrt and a division per
-    // column would dominate this kernel)
-    double rs = __builtin_amdgcn_rsq(piv2);
-    rs = rs * (1.5 - 0.5 * piv2 * rs * rs);
-    rs = rs * (1.5 - 0.5 * piv2 * rs * rs);
-    const double piv = piv2 * rs, inv = rs * rs;
-    double ci[BS], cjs[BS];
+    if (tj == cb && ti > cb) {         // X = B L_d^-T, row by row; publish the panel
+      const double r0 = dblk[0][0], r1 = dblk[1][1], r2 = dblk[2][2], r3 = dblk[3][3];
+      const double l10 = dblk[1][0], l20 = dblk[2][0], l21 = dblk[2][1], l30 = dblk[3][0], l31 = dblk[3][1],
+                   l32 = dblk[3][2];
 #pragma unroll
-    for (int ii = 0; ii < BS; ++ii) ci[ii] = col[BS * ti + ii];
-#pragma unroll
-    for (int jj = 0; jj < BS; ++jj) cjs[jj] = col[BS * tj + jj] * inv;
-    if (tj > cb) {                     // all columns of the block are right of c
-      if (below) {
-#pragma unroll
-        for (int ii = 0; ii < BS; ++ii)
-#pragma unroll
-          for (int jj = 0; jj < BS; ++jj) a[ii][jj] -= ci[ii] * cjs[jj];
-      } else {
-#pragma unroll
-        for (int ii = 0; ii < BS; ++ii)
-#pragma unroll
-          for (int jj = 0; jj <= ii; ++jj) a[ii][jj] -= ci[ii] * cjs[jj];
+      for (int ii = 0; ii < BS; ++ii) {
+        const double x0 = a[ii][0] * r0;
+        const double x1 = (a[ii][1] - x0 * l10) * r1;
+        const double x2 = (a[ii][2] - x0 * l20 - x1 * l21) * r2;
+        const double x3 = (a[ii][3] - x0 * l30 - x1 * l31 - x2 * l32) * r3;
+        a[ii][0] = x0; a[ii][1] = x1; a[ii][2] = x2; a[ii][3] = x3;
+        panel[BS * ti + ii][0] = x0; panel[BS * ti + ii][1] = x1;
+        panel[BS * ti + ii][2] = x2; panel[BS * ti + ii][3] = x3;
       }
-    } else {                           // the block column that contains c
+    }
+    __syncthreads();
+    if (tj > cb && ti >= tj) {         // rank-4 update of the blocks right of the panel
+      double pi[BS][BS], pj[BS][BS];
 #pragma unroll
       for (int ii = 0; ii < BS; ++ii)
 #pragma unroll
-        for (int jj = 0; jj < BS; ++jj) {
-          if (jj > cq && (below || ii >= jj)) a[ii][jj] -= ci[ii] * cjs[jj];
-          else if (jj == cq && (below || ii >= cq)) a[ii][jj] = (!below && ii == cq) ? piv : ci[ii] * rs;
+        for (int q = 0; q < BS; ++q) {
+          pi[ii][q] = panel[BS * ti + ii][q];
+          pj[ii][q] = panel[BS * tj + ii][q];
         }
+#pragma unroll
+      for (int ii = 0; ii < BS; ++ii)
+#pragma unroll
+        for (int jj = 0; jj < BS; ++jj)
+#pragma unroll
+          for (int q = 0; q < BS; ++q) a[ii][jj] -= pi[ii][q] * pj[jj][q];
     }
   }
 #pragma unroll
@@ -403,8 +418,8 @@ __global__ __launch_bounds__(256) void chol_reg_kernel(double* G, int64_t bstrid
       if (i < l && j < l) g[(int64_t)i * ld + j] = v;
       if (rdiag && i == j && i < l) rdiag[(int64_t)b * rd_bstride + i] = 1.0 / v;
     }
-  // the thread that owns the last diagonal block has seen every pivot
-  if (info && dependent && ti == tj && ti == (l - 1) / BS) atomicOr(info + b, SVDC_FIT_RANK_DEFICIENT);
+  // every thread on the diagonal has seen the pivots of its own block
+  if (info && dependent) atomicOr(info + b, SVDC_FIT_RANK_DEFICIENT);
 }
 
 // ---------------------------------------------------------------------------
@@ -585,7 +600,7 @@ __global__ __launch_bounds__(256) void chol_panel_kernel(double* G, const double
   int ri[4];
 #pragma unroll
   for (int ii = 0; ii < 4; ++ii) ri[ii] = min(r0 + 4 * ty + ii, l - 1);
-#pragma unroll 4
+#pragma unroll 8
   for (int c = 0; c < c0; ++c) {
     const double* gc = g + (int64_t)c * l;
     double av[4], bv[4];
