@@ -614,8 +614,11 @@ __global__ __launch_bounds__(256) void full_step_mfma_kernel(const T* F, const u
 
 bool mfma_shape_supported(const svdc_shape& s) {
   if (s.D % 128 != 0 || s.k > 128 || s.k % 4 != 0) return false;
-  const int ch = s.D / 128;   // hidden sizes 256, 512, 1024, 1536, 2048, 3072, 4096
-  return ch == 2 || ch == 4 || ch == 8 || ch == 12 || ch == 16 || ch == 24 || ch == 32;
+  // hidden sizes 256, 512, 1024, 1152, 1536, 1920, 2048, 2560, 3072, 4096, 5120 (the full step is instantiated per width)
+  switch (s.D / 128) {
+    case 2: case 4: case 8: case 9: case 12: case 15: case 16: case 20: case 24: case 32: case 40: return true;
+    default: return false;
+  }
 }
 
 size_t mfma_packed_bytes(const svdc_shape& s) {
@@ -789,10 +792,14 @@ int32_t full_step_by_width(const svdc_shape& s, const void* F, const void* packe
     case 2: return full_step_by_rank<T, 2, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
     case 4: return full_step_by_rank<T, 4, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
     case 8: return full_step_by_rank<T, 8, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
+    case 9: return full_step_by_rank<T, 9, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
     case 12: return full_step_by_rank<T, 12, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
+    case 15: return full_step_by_rank<T, 15, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
     case 16: return full_step_by_rank<T, 16, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
+    case 20: return full_step_by_rank<T, 20, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
     case 24: return full_step_by_rank<T, 24, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
     case 32: return full_step_by_rank<T, 32, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
+    case 40: return full_step_by_rank<T, 40, SPLIT>(s, F, packed, R, S, C, alpha, init, re, st);
     default: return SVDC_E_SHAPE;
   }
 }

@@ -241,7 +241,9 @@ def _lowrank_problem(B, N, D, k, seed, rho=0.05):
 @pytest.mark.parametrize("B,N,D,k", [(2, 200, 256, 32), (1, 77, 512, 8), (3, 64, 256, 64), (1, 131, 512, 128),
                                      (2, 49, 256, 20), (1, 150, 3072, 32), (2, 70, 3072, 64), (1, 140, 3072, 128),
                                      (1, 33, 3072, 16), (1, 80, 1024, 32), (1, 70, 1536, 64), (1, 50, 2048, 16),
-                                     (1, 130, 2048, 128), (1, 45, 4096, 32), (1, 66, 4096, 64)])
+                                     (1, 130, 2048, 128), (1, 45, 4096, 32), (1, 66, 4096, 64),
+                                     (1, 70, 1152, 32), (2, 70, 1152, 64), (1, 90, 1920, 16), (1, 140, 1920, 128),
+                                     (1, 75, 2560, 32), (1, 80, 2560, 64), (1, 60, 5120, 32), (1, 130, 5120, 128)])
 def test_mfma_full_step_and_forecast(B, N, D, k):
     F, V, S0 = _lowrank_problem(B, N, D, k, seed=N * 7 + k)
     shape = pkg.make_shape(F, k)
@@ -781,7 +783,8 @@ def test_rank_sweep_float32_at_stacked_prompt_shape(k):
 
 @pytest.mark.parametrize("B,N,D,k", [(2, 200, 256, 32), (1, 77, 512, 8), (1, 131, 512, 128), (1, 150, 3072, 32),
                                      (1, 70, 3072, 64), (2, 49, 256, 20), (1, 60, 1024, 32), (1, 50, 1536, 16),
-                                     (1, 70, 2048, 64), (1, 40, 4096, 32)])
+                                     (1, 70, 2048, 64), (1, 40, 4096, 32), (1, 50, 1152, 32), (1, 70, 1920, 64),
+                                     (1, 40, 2560, 16), (1, 36, 5120, 32), (1, 129, 5120, 128)])
 def test_mfma_float32_features(B, N, D, k):
     Fb, V, S0 = _lowrank_problem(B, N, D, k, seed=N * 3 + k)
     g = torch.Generator().manual_seed(N)
