@@ -205,7 +205,7 @@ __global__ __launch_bounds__(256) void fit_project_mfma_kernel(const T* __restri
       for (int jt = 0; jt < KT; ++jt) part[wave][tt][jt][lane] = acc[2 * rd + tt][jt];
     __syncthreads();
     if (Yp) {
-      // packed output for the back-projection: the two tiles of this round are one 32-row step (see pack_y_word)
+      // packed output for the back-projection: the two tiles of this pass of the loop are one 32-row step (see pack_y_word)
       const int step = (tile0 + 2 * rd) / 2;
 #pragma unroll
       for (int jt = 0; jt < KT; ++jt) {
