@@ -710,14 +710,15 @@ void backproject_groups(const svdc_shape& s, int* gpb, int* rows) {
   *gpb = (s.N + r - 1) / r;
 }
 
-// largest instantiated slab width (chunks per wave) that divides D / 128 and is at most `cap`
+// largest instantiated slab width (chunks per wave) that divides D / 128 and is at most `cap` (compile time: what
+// the registers hold) and `maxw` (run time)
 template <int cap, typename Fn12, typename Fn6, typename Fn4, typename Fn3, typename Fn2, typename Fn1>
-void by_width(int m, Fn12 f12, Fn6 f6, Fn4 f4, Fn3 f3, Fn2 f2, Fn1 f1) {
-  if constexpr (cap >= 12) { if (m % 12 == 0) return f12(); }
-  if constexpr (cap >= 6) { if (m % 6 == 0) return f6(); }
-  if constexpr (cap >= 4) { if (m % 4 == 0) return f4(); }
-  if constexpr (cap >= 3) { if (m % 3 == 0) return f3(); }
-  if (m % 2 == 0) return f2();
+void by_width(int m, int maxw, Fn12 f12, Fn6 f6, Fn4 f4, Fn3 f3, Fn2 f2, Fn1 f1) {
+  if constexpr (cap >= 12) { if (maxw >= 12 && m % 12 == 0) return f12(); }
+  if constexpr (cap >= 6) { if (maxw >= 6 && m % 6 == 0) return f6(); }
+  if constexpr (cap >= 4) { if (maxw >= 4 && m % 4 == 0) return f4(); }
+  if constexpr (cap >= 3) { if (maxw >= 3 && m % 3 == 0) return f3(); }
+  if (maxw >= 2 && m % 2 == 0) return f2();
   return f1();
 }
 
@@ -727,7 +728,7 @@ void project_kt(const svdc_shape& s, int l, const void* F, const void* Qp, float
   // float32 features hold 8 registers per piece in flight and always carry both sketch parts: narrower slabs
   constexpr int cap = std::is_same<T, float>::value ? 3 : (KT == 4 ? 4 : width_for<KT>());
   by_width<cap>(
-      s.D / 128, [&] { project_launch<T, (cap >= 12 ? 12 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
+      s.D / 128, cap, [&] { project_launch<T, (cap >= 12 ? 12 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
       [&] { project_launch<T, (cap >= 6 ? 6 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
       [&] { project_launch<T, (cap >= 4 ? 4 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
       [&] { project_launch<T, (cap >= 3 ? 3 : 1), KT>(s, l, F, Qp, Y, Yp, fro, split, ld, st); },
@@ -755,8 +756,21 @@ template <typename T, int KT>
 void backproject_kt(const svdc_shape& s, int l, const void* F, const float* Y, const u32x4* Yp, float* Z,
                     Strides ld, hipStream_t st) {
   constexpr int cap = std::is_same<T, float>::value ? width_for_f32<KT>() : width_for<KT>();
+  // Small batches: narrower slabs give more workgroups without more row groups, whose partial sums meet in float
+  // atomics (one per element and row group): the widest slab that still gives 64 slabs over all blocks, if any.
+  // Measured at 4608 x 3072, width 64: 42 -> 15 us for one block, 55 -> 36 us for 4, 72 -> 53 us for 8; from 28
+  // blocks on the widest slab is the fastest again.  Not for float32 features, whose back-projection reads and
+  // splits Y as float32 rows once per slab (18432 x 3072, one block: 3.7 -> 4.7 ms per fit at width 128 when tried).
+  constexpr int64_t kMinSlabs = 64;
+  const int m = s.D / 128;
+  int maxw = cap;
+  if (!std::is_same<T, float>::value && Yp) {   // packed Y only: float32 rows of Y cost the same once per slab
+    maxw = 1;
+    for (int w : {2, 3, 4, 6, 12})
+      if (w <= cap && m % w == 0 && (int64_t)(m / w) * s.B >= kMinSlabs) maxw = w;
+  }
   by_width<cap>(
-      s.D / 128, [&] { backproject_one<T, (cap >= 12 ? 12 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
+      s.D / 128, maxw, [&] { backproject_one<T, (cap >= 12 ? 12 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
       [&] { backproject_one<T, (cap >= 6 ? 6 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
       [&] { backproject_one<T, (cap >= 4 ? 4 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
       [&] { backproject_one<T, (cap >= 3 ? 3 : 1), KT>(s, l, F, Y, Yp, Z, ld, st); },
