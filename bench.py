@@ -176,7 +176,7 @@ def main():
     ap.add_argument("--packed-state", choices=["auto", "on", "off"], default="auto",
                     help="cached steps read the packed copy of the state that the full step writes "
                          "(svdcache_full_step_packed / svdcache_forecast_packed) instead of the float32 state; "
-                         "auto = from rank 33 on, where it pays")
+                         "auto = from rank 33 on while the state (B x N x k float32) is at most 128 MB, where it pays")
     ap.add_argument("--probes", action="store_true",
                     help="time the memory-system probe kernels (measured ceilings of this machine) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -243,9 +243,12 @@ def main():
     Fh = torch.empty_like(feats[0])
     S = torch.empty(B, N, k, device=dev)
     # the state in the cached step's operand format, written by the full step (matrix-core shapes)
-    # (pays from rank 33 on: -5 % per cached step at rank 64, -11 % at rank 128; nothing at rank <= 32, where the
-    # conversion it saves is hidden anyway)
-    use_ps = args.packed_state == "on" or (args.packed_state == "auto" and k > 32)
+    # (pays from rank 33 on: -4 % per cached step at rank 64, -11 % at rank 128; nothing at rank <= 32, where the
+    # conversion it saves is hidden anyway -- and only while state and copy stay in the 256 MB Infinity Cache between
+    # the full step and the cached steps: at 60 x 119056 rows, 1.8 GB of state, the copy costs the full step 8 % and
+    # the cached step gains nothing)
+    state_bytes = B * N * k * 4
+    use_ps = args.packed_state == "on" or (args.packed_state == "auto" and k > 32 and state_bytes <= 128 * 2**20)
     Sp = pkg.alloc_packed_state(shape, dev) if (packed is not None and use_ps) else None
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
