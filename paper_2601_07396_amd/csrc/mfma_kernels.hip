@@ -685,6 +685,13 @@ int32_t forecast_by_width(const svdc_shape& s, const CoefStates& cs, const void*
   const int m = s.D / 128;
   if constexpr (kMax >= 12) {
     if (m % 12 == 0) return forecast_launch<T, 12, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
+    // hidden sizes that 12 does not divide (1152 = 9 x 128, 2560 and 5120 = 20 and 40 x 128, 4096 = 32 x 128); only
+    // the basic kernel, to bound the number of instantiations
+    if constexpr (!EXT) {
+      if (m % 10 == 0) return forecast_launch<T, 10, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
+      if (m % 9 == 0) return forecast_launch<T, 9, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
+      if (m % 8 == 0) return forecast_launch<T, 8, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
+    }
   }
   // bf16 features at rank 64 with split operands: the estimate above gives 6, but 8 chunks still fit (500 of the 512
   // registers, no spills); a workgroup then covers a third of a 3072-channel row instead of a quarter
@@ -694,11 +701,14 @@ int32_t forecast_by_width(const svdc_shape& s, const CoefStates& cs, const void*
   }
   if constexpr (kMax >= 6) {
     if (m % 6 == 0) return forecast_launch<T, 6, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
-  }
-  if constexpr (kMax >= 4) {
-    if (m % 4 == 0) return forecast_launch<T, 4, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
+    if constexpr (!EXT) {   // 1920 = 15 x 128
+      if (m % 5 == 0) return forecast_launch<T, 5, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
+    }
   }
   if constexpr (kMax == 3 && KT2 == 4 && SPLIT && sizeof(T) == 2 && !EXT) {   // likewise 4 chunks at rank 128
+    if (m % 4 == 0) return forecast_launch<T, 4, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
+  }
+  if constexpr (kMax >= 4) {
     if (m % 4 == 0) return forecast_launch<T, 4, KT2, SPLIT, PD, EXT, PS>(s, cs, packed, R, X, Fhat, st);
   }
   if constexpr (kMax >= 3) {
