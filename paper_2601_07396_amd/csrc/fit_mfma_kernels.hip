@@ -264,13 +264,14 @@ __global__ __launch_bounds__(256) void fit_project_rows_kernel(const T* __restri
                                                                u32x4* Yp, double* fro_acc, int N, int D, int l,
                                                                int64_t ldf, int64_t bstride,
                                                                int groups_per_block, int ldy) {
-  // Chunks of F in flight per wave.  With split operands they are requested two at a time (PD = 4): the two
-  // 64-byte pieces of a 128-byte line belong to neighbouring chunks, and asked for a whole chunk's work apart the
-  // line comes from L2 twice (4 % slower).  With plain operands at width 128 the extra registers cost more than
-  // that (11 % slower), so there a slot is refilled as soon as its chunk is done (PD = 2).
+  // Four chunks of F in flight per wave.  With split operands they are requested two at a time: the two 64-byte
+  // pieces of a 128-byte line belong to neighbouring chunks, and asked for a whole chunk's work apart the line comes
+  // from L2 twice (4 % slower).  With plain operands a slot is refilled as soon as its chunk is done (two chunks
+  // in flight instead of four: 3 % slower at width 128).
   constexpr bool PAIRED = SPLIT;
-  constexpr int PD = PAIRED ? 4 : 2;
+  constexpr int PD = 4;
   static_assert(SC == 2 || SC == 4, "slab of 2 or 4 chunks");
+  static_assert(PAIRED || SC == PD, "without pairing the ring slot of a chunk is its index in the slab");
   constexpr int NP = SPLIT ? 2 : 1;           // operand parts (high, low)
   constexpr int WPW = SC * KT / kWaves;       // operand words a wave stages per slab and part
   static_assert(SC * KT % kWaves == 0, "staging must divide among the waves");
