@@ -176,7 +176,7 @@ def main():
     ap.add_argument("--packed-state", choices=["auto", "on", "off"], default="auto",
                     help="cached steps read the packed copy of the state that the full step writes "
                          "(svdcache_full_step_packed / svdcache_forecast_packed) instead of the float32 state; "
-                         "auto = from rank 33 on while the state (B x N x k float32) is at most 128 MB, where it pays")
+                         "auto = from rank 33 on while the state (B x N x k float32) is at most 128 MB, or with --fast, where it pays")
     ap.add_argument("--probes", action="store_true",
                     help="time the memory-system probe kernels (measured ceilings of this machine) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -248,7 +248,10 @@ def main():
     # the full step and the cached steps: at 60 x 119056 rows, 1.8 GB of state, the copy costs the full step 8 % and
     # the cached step gains nothing)
     state_bytes = B * N * k * 4
-    use_ps = args.packed_state == "on" or (args.packed_state == "auto" and k > 32 and state_bytes <= 128 * 2**20)
+    # (in SVDC_FAST the conversion that the copy saves is a larger share of the cached step: there it pays at any size,
+    # 997 against 1012 ms per trajectory at that shape)
+    use_ps = args.packed_state == "on" or (args.packed_state == "auto" and k > 32 and
+                                           (state_bytes <= 128 * 2**20 or args.fast))
     Sp = pkg.alloc_packed_state(shape, dev) if (packed is not None and use_ps) else None
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
