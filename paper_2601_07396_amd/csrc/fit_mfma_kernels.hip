@@ -71,22 +71,29 @@ struct FPiece<float> {
 // Per block: hi array of D * LP elements followed by the lo array, LP = 16 KT.
 // Q points at the first of the l columns to pack; ldq is the row stride of the whole matrix (sketches wider than 128
 // are packed, and multiplied, as two column ranges).
+// One workgroup per 32-channel chunk cg: its 32 rows of Q are read row by row (contiguous), staged in LDS, and
+// written out as the chunk's KT operand words of 1 KB each (both parts), so that reads and writes are coalesced.
 __global__ __launch_bounds__(256) void pack_q_kernel(const float* __restrict__ Q, uint16_t* __restrict__ P, int D,
                                                      int l, int KT, int ldq) {
-  const int b = blockIdx.y;
-  const int64_t per = (int64_t)D * KT * 16;
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= per) return;
-  const int e = idx & 7, lane = (idx >> 3) & 63, r = lane & 15, g = lane >> 4;
-  const int64_t tile = idx >> 9;
-  const int jt = tile % KT, cg = tile / KT;
-  const int d = 32 * cg + 8 * g + e, j = 16 * jt + r;
-  const float x = j < l ? Q[((int64_t)b * D + d) * ldq + j] : 0.f;
-  const bf16_t hi = (bf16_t)x;
-  const bf16_t lo = (bf16_t)(x - (float)hi);
-  uint16_t* p = P + (int64_t)b * 2 * per;
-  p[idx] = __builtin_bit_cast(uint16_t, hi);
-  p[per + idx] = __builtin_bit_cast(uint16_t, lo);
+  __shared__ float tile[32][129];   // [channel in the chunk][coefficient], l <= 128
+  const int b = blockIdx.y, cg = blockIdx.x, t = threadIdx.x;
+  const int LP = 16 * KT;
+  const float* q = Q + ((int64_t)b * D + 32 * cg) * ldq;
+  for (int idx = t; idx < 32 * LP; idx += 256) {
+    const int d = idx / LP, j = idx % LP;
+    tile[d][j] = j < l ? q[(int64_t)d * ldq + j] : 0.f;
+  }
+  __syncthreads();
+  const int64_t per = (int64_t)D * LP;
+  uint16_t* p = P + (int64_t)b * 2 * per + (int64_t)cg * KT * 512;
+  for (int idx = t; idx < KT * 512; idx += 256) {
+    const int e = idx & 7, lane = (idx >> 3) & 63, r = lane & 15, g = lane >> 4, jt = idx >> 9;
+    const float x = tile[8 * g + e][16 * jt + r];
+    const bf16_t hi = (bf16_t)x;
+    const bf16_t lo = (bf16_t)(x - (float)hi);
+    p[idx] = __builtin_bit_cast(uint16_t, hi);
+    p[per + idx] = __builtin_bit_cast(uint16_t, lo);
+  }
 }
 
 // Packed Y for the back-projection: Y rounded to bf16, already in the layout of its MFMA operand, so that the
@@ -828,8 +835,7 @@ void fit_mfma_pack_q(const svdc_shape& s, int l, const float* Q, void* Qp, hipSt
   char* out = static_cast<char*>(Qp);
   for (int h = 0; h < n; ++h) {
     const int KT = kt_for(r[h].l);
-    const int64_t per = (int64_t)s.D * KT * 16;
-    pack_q_kernel<<<dim3((unsigned)((per + 255) / 256), s.B), 256, 0, st>>>(Q + r[h].j0, (uint16_t*)out, s.D, r[h].l, KT, l);
+    pack_q_kernel<<<dim3((unsigned)(s.D / 32), s.B), 256, 0, st>>>(Q + r[h].j0, (uint16_t*)out, s.D, r[h].l, KT, l);
     out += packed_q_bytes_one(s, r[h].l);
   }
 }
