@@ -94,8 +94,8 @@ typedef struct {
                             5 (f32); -1 -> none: the sketch is F^T Omega alone (plain randomized range finder, two
                             products with F in all; exact when rank(F) <= l, crude when the spectrum decays slowly) */
   uint64_t seed;         /* seed of the Gaussian test matrix                     */
-  int32_t jacobi_max_sweeps; /* cap on the sweeps of the small SVD; 0 -> 40 (a sweep that rotates nothing ends it: 6-9
-                                sweeps in practice); at most 1000 */
+  int32_t jacobi_max_sweeps; /* cap on the sweeps of the small SVD; 0 -> 40 (20 for sketch widths above 138); a sweep
+                                that rotates nothing ends it: 6-9 sweeps in practice; at most 1000 */
   int32_t reserved;      /* set to 0 */
 } svdc_fit_params;
 

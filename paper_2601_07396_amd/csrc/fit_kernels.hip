@@ -992,6 +992,7 @@ __global__ __launch_bounds__(256) void sumsq_kernel(const T* __restrict__ F, dou
 // ---------------------------------------------------------------------------
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+constexpr size_t kLdsBudget = 150 * 1024;  // dynamic LDS a single workgroup may take (160 KB per CU)
 constexpr int kGramSlices = 16;   // row slices whose partial Gram matrices are summed in a fixed order
 
 bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan) {
@@ -1011,7 +1012,9 @@ bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan)
   plan->seed = p ? p->seed : 0;
   const int sweeps = p ? p->jacobi_max_sweeps : 0;
   if (sweeps < 0 || sweeps > 1000) return false;
-  plan->max_sweeps = sweeps == 0 ? 40 : sweeps;
+  // default cap: 40 sweeps; 20 for the Jacobi by column blocks (l > 138), which takes 8-9 and whose launches are
+  // issued up to the cap (those after convergence return at once, but are not free)
+  plan->max_sweeps = sweeps == 0 ? ((size_t)l * (l + 1) * sizeof(double) <= kLdsBudget ? 40 : 20) : sweeps;
   size_t off = 0;
   const size_t B = s.B;
   plan->off_Q = off; off = align_up(off + B * s.D * l * sizeof(float), 256);
@@ -1039,7 +1042,6 @@ bool make_fit_plan(const svdc_shape& s, const svdc_fit_params* p, FitPlan* plan)
 
 namespace {
 
-constexpr size_t kLdsBudget = 150 * 1024;  // dynamic LDS a single workgroup may take (160 KB per CU)
 
 int32_t set_dyn_lds(const void* fn, size_t bytes) {
   if (bytes <= 48 * 1024) return SVDC_OK;
