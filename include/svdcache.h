@@ -133,7 +133,9 @@ size_t svdcache_fit_status_offset(const svdc_shape* shape, const svdc_fit_params
 size_t svdcache_packed_basis_bytes(const svdc_shape* shape);
 
 /* 1 if full_step / forecast run their matrix-core (MFMA) kernels for this
- * shape when a packed basis is supplied, 0 if they use the general kernels. */
+ * shape when a packed basis is supplied, 0 if they use the general kernels.
+ * The matrix-core kernels cover k <= 128 with k a multiple of 4 and D one of 256, 512, 1024, 1152, 1536, 1920, 2048,
+ * 2560, 3072, 4096, 5120, for both dtypes. */
 int32_t svdcache_has_mfma_path(const svdc_shape* shape);
 
 /* Basis fit (Sec. 3.2, Eq. 4-5): the k leading right singular vectors of each
